@@ -1,0 +1,231 @@
+/*
+ * CPU oracle for one GPU's share of an expert-parallel MoE layer.
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It exists so that the GPU library can be checked against a plain,
+ * slow, obviously-correct statement of what the layer computes.  It shares no code, header, table
+ * or helper with the GPU library, and nothing in the product path may call it.
+ *
+ * What is computed follows the paper's problem statement:
+ *   - MoE structure (Sec. II-A): every token activates its top-k experts as chosen by the gate; each
+ *     activated expert runs its FFN (GEMM-1, GEMM-2); the k outputs are aggregated.
+ *   - Weighted aggregation (Sec. III-C): expert output o_i is scaled by gate weight w_i and the scaled
+ *     outputs are summed without further weighting, y = sum_i (w_i * o_i).
+ *   - Expert -> GPU map (Sec. III-D, switch routing): rank(e) = e / experts_per_rank.
+ *   - Layout allocation (Sec. III-D, AL Table): each expert owns a dense layout tensor whose rows are
+ *     handed out one after the other; here in ascending token order, which makes the table unique.
+ *   - Per-expert active counts are known from routing before Dispatch (Sec. III-E, nactive[expert]).
+ * The paper does not state the gate function or the FFN activation; the readings used are: softmax over
+ * the logits, top-k on the raw logits with ties broken towards the lower expert index, weights
+ * renormalised over the k picks, and a SwiGLU FFN  (silu(x Wg) * (x Wu)) Wd  without biases.
+ *
+ * Floating point: inputs are fp32 (or bf16 bit patterns widened exactly); all sums are accumulated in
+ * MOE_ACC_T (double unless overridden at compile time with -DMOE_ACC_T=float) in ascending index order;
+ * exp() is evaluated in double.  Nothing is blocked, fused or reordered beyond that.
+ *
+ * Pins (tests/, -m "not gpu"): brute-force NumPy re-derivations on tiny inputs, a hand-worked 4-token
+ * example, sum-to-one and permutation invariants, the identical-experts == dense-FFN identity, the
+ * closed-form expected dedup count, and the float-vs-double accumulation twin.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#ifndef MOE_ACC_T
+#define MOE_ACC_T double
+#endif
+typedef MOE_ACC_T acc_t;
+
+#define ORACLE_OK 0
+#define ORACLE_BAD_ARG (-1)
+#define ORACLE_NOMEM (-2)
+
+/* element type codes of activations and weights */
+#define ELT_F32 0
+#define ELT_BF16 1
+
+static inline float load_elt(const void *base, size_t i, int elt) {
+  if (elt == ELT_F32) return ((const float *)base)[i];
+  uint32_t bits = ((uint32_t)((const uint16_t *)base)[i]) << 16; /* bf16 -> fp32 is exact */
+  float v;
+  memcpy(&v, &bits, sizeof v);
+  return v;
+}
+
+int moe_oracle_acc_bytes(void) { return (int)sizeof(acc_t); }
+
+int moe_oracle_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/*
+ * Routing (Sec. II-A "topk experts selected by the gate network").
+ * For each token: repeatedly take the not-yet-taken expert with the largest logit (lowest index on
+ * ties); slot order is pick order.  w_j = exp(l_j - l_0) / sum_i exp(l_i - l_0), sum in slot order.
+ * Returns ORACLE_BAD_ARG on a non-finite logit.
+ */
+int moe_oracle_route_topk(int T, int E, int k, const float *logits, int32_t *topk_idx, float *topk_w) {
+  if (T < 0 || E < 1 || k < 1 || k > E || !logits || !topk_idx || !topk_w) return ORACLE_BAD_ARG;
+  unsigned char *taken = (unsigned char *)malloc((size_t)E);
+  if (!taken) return ORACLE_NOMEM;
+  for (int t = 0; t < T; ++t) {
+    const float *row = logits + (size_t)t * E;
+    for (int e = 0; e < E; ++e) {
+      if (!isfinite(row[e])) { free(taken); return ORACLE_BAD_ARG; }
+      taken[e] = 0;
+    }
+    for (int j = 0; j < k; ++j) {
+      int best = -1;
+      for (int e = 0; e < E; ++e) {
+        if (taken[e]) continue;
+        if (best < 0 || row[e] > row[best]) best = e; /* strict '>' keeps the lowest index on ties */
+      }
+      taken[best] = 1;
+      topk_idx[(size_t)t * k + j] = best;
+    }
+    double m = (double)row[topk_idx[(size_t)t * k]];
+    double sum = 0.0;
+    for (int j = 0; j < k; ++j) sum += exp((double)row[topk_idx[(size_t)t * k + j]] - m);
+    for (int j = 0; j < k; ++j)
+      topk_w[(size_t)t * k + j] = (float)(exp((double)row[topk_idx[(size_t)t * k + j]] - m) / sum);
+  }
+  free(taken);
+  return ORACLE_OK;
+}
+
+/*
+ * Dispatch tables (Sec. III-D AL Table; Sec. III-E nactive[expert]).
+ * counts[e]  = number of (token, slot) pairs routed to e; offsets = exclusive prefix sum (E+1 entries).
+ * Pairs are visited in ascending pair id p = t*k + j; the pair takes the next free row of its expert:
+ * inv_perm[p] = row, perm[row] = p.
+ */
+int moe_oracle_build_tables(int T, int E, int k, const int32_t *topk_idx, int32_t *counts, int32_t *offsets,
+                            int32_t *perm, int32_t *inv_perm) {
+  if (T < 0 || E < 1 || k < 1 || !topk_idx || !counts || !offsets || !perm || !inv_perm) return ORACLE_BAD_ARG;
+  for (int e = 0; e < E; ++e) counts[e] = 0;
+  for (size_t p = 0; p < (size_t)T * k; ++p) {
+    int e = topk_idx[p];
+    if (e < 0 || e >= E) return ORACLE_BAD_ARG;
+    counts[e]++;
+  }
+  offsets[0] = 0;
+  for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+  int32_t *cursor = (int32_t *)calloc((size_t)E, sizeof(int32_t));
+  if (!cursor) return ORACLE_NOMEM;
+  for (size_t p = 0; p < (size_t)T * k; ++p) {
+    int e = topk_idx[p];
+    int32_t row = offsets[e] + cursor[e]++;
+    inv_perm[p] = row;
+    perm[row] = (int32_t)p;
+  }
+  free(cursor);
+  return ORACLE_OK;
+}
+
+/*
+ * Dedup table (Sec. II-B redundancy: one transfer per distinct (token, destination GPU);
+ * Sec. III-D: destination = expert / experts_per_rank).
+ * Entries are the distinct (rank, token) pairs in (rank ascending, token ascending) order;
+ * dedup_mask has bit j set iff slot j of that token lies in that rank.  Needs k <= 32.
+ */
+int moe_oracle_build_dedup(int T, int E, int k, int R, const int32_t *topk_idx, int32_t *rank_counts,
+                           int32_t *rank_offsets, int32_t *dedup_tok, uint32_t *dedup_mask,
+                           int32_t *pair_to_dedup) {
+  if (T < 0 || E < 1 || k < 1 || k > 32 || R < 1 || E % R != 0) return ORACLE_BAD_ARG;
+  if (!topk_idx || !rank_counts || !rank_offsets || !dedup_tok || !dedup_mask || !pair_to_dedup)
+    return ORACLE_BAD_ARG;
+  const int epr = E / R;
+  int32_t n = 0;
+  rank_offsets[0] = 0;
+  for (int r = 0; r < R; ++r) {
+    rank_counts[r] = 0;
+    for (int t = 0; t < T; ++t) {
+      uint32_t mask = 0;
+      for (int j = 0; j < k; ++j)
+        if (topk_idx[(size_t)t * k + j] / epr == r) mask |= (uint32_t)1 << j;
+      if (!mask) continue;
+      dedup_tok[n] = t;
+      dedup_mask[n] = mask;
+      for (int j = 0; j < k; ++j)
+        if (mask >> j & 1u) pair_to_dedup[(size_t)t * k + j] = n;
+      ++n;
+      rank_counts[r]++;
+    }
+    rank_offsets[r + 1] = n;
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * Forward for a list of tokens (Sec. II-A GEMM-1 / GEMM-2; Sec. III-C weighted sum).
+ *   for each selected token t, for each slot j whose expert e is hosted by local ranks [lrb, lre):
+ *     g = x_t Wg[le], u = x_t Wu[le], h = silu(g) * u, o = h Wd[le], y_t += w[t,j] * o
+ * tokens == NULL means tokens 0..n_tok-1.  y_out is [n_tok, d] in double; rows without a local slot are 0.
+ * Weights are indexed by local expert le = e - lrb*E/R and stored input-major: Wg,Wu [E_loc,d,f], Wd [E_loc,f,d].
+ */
+int moe_oracle_forward(int T, int d, int f, int E, int k, int R, int lrb, int lre, int elt, const void *x,
+                       const int32_t *topk_idx, const float *topk_w, const void *W_gate, const void *W_up,
+                       const void *W_down, const int32_t *tokens, int n_tok, double *y_out) {
+  if (T < 0 || d < 1 || f < 1 || E < 1 || k < 1 || R < 1 || E % R != 0) return ORACLE_BAD_ARG;
+  if (lrb < 0 || lre <= lrb || lre > R || (elt != ELT_F32 && elt != ELT_BF16)) return ORACLE_BAD_ARG;
+  if (!x || !topk_idx || !topk_w || !W_gate || !W_up || !W_down || !y_out || n_tok < 0) return ORACLE_BAD_ARG;
+  const int epr = E / R;
+  const int e_lo = lrb * epr, e_hi = lre * epr;
+  int status = ORACLE_OK;
+#pragma omp parallel
+  {
+    acc_t *g = (acc_t *)malloc(sizeof(acc_t) * (size_t)f);
+    acc_t *u = (acc_t *)malloc(sizeof(acc_t) * (size_t)f);
+    acc_t *o = (acc_t *)malloc(sizeof(acc_t) * (size_t)d);
+    acc_t *acc = (acc_t *)malloc(sizeof(acc_t) * (size_t)d);
+    if (!g || !u || !o || !acc) {
+#pragma omp critical
+      status = ORACLE_NOMEM;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int i = 0; i < n_tok; ++i) {
+        const int t = tokens ? tokens[i] : i;
+        for (int m = 0; m < d; ++m) acc[m] = 0;
+        if (t >= 0 && t < T) {
+          for (int j = 0; j < k; ++j) {
+            const int e = topk_idx[(size_t)t * k + j];
+            if (e < e_lo || e >= e_hi) continue;
+            const size_t le = (size_t)(e - e_lo);
+            const size_t wgu = le * (size_t)d * f, wdn = le * (size_t)f * d;
+            for (int n = 0; n < f; ++n) { g[n] = 0; u[n] = 0; }
+            for (int c = 0; c < d; ++c) {
+              const acc_t xc = (acc_t)load_elt(x, (size_t)t * d + c, elt);
+              const size_t rowb = wgu + (size_t)c * f;
+              for (int n = 0; n < f; ++n) {
+                g[n] += xc * (acc_t)load_elt(W_gate, rowb + n, elt);
+                u[n] += xc * (acc_t)load_elt(W_up, rowb + n, elt);
+              }
+            }
+            for (int n = 0; n < f; ++n) {
+              const double gv = (double)g[n];
+              g[n] = (acc_t)((gv / (1.0 + exp(-gv))) * (double)u[n]); /* h = silu(g) * u, kept unrounded */
+            }
+            for (int m = 0; m < d; ++m) o[m] = 0;
+            for (int n = 0; n < f; ++n) {
+              const acc_t hn = g[n];
+              const size_t rowb = wdn + (size_t)n * d;
+              for (int m = 0; m < d; ++m) o[m] += hn * (acc_t)load_elt(W_down, rowb + m, elt);
+            }
+            const acc_t w = (acc_t)topk_w[(size_t)t * k + j];
+            for (int m = 0; m < d; ++m) acc[m] += w * o[m];
+          }
+        }
+        for (int m = 0; m < d; ++m) y_out[(size_t)i * d + m] = (double)acc[m];
+      }
+    }
+    free(g); free(u); free(o); free(acc);
+  }
+  return status;
+}

@@ -1,0 +1,265 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+Each test names the mistake it is there to catch.
+"""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+
+import brute
+from paper_2605_05607_amd import workloads as wl
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "hand_example_4tok.json")
+
+
+def small_cfg(**kw):
+    base = dict(name="s", T=24, d=16, f=24, E=8, k=3, R=4, local_rank_begin=1, local_rank_end=3, dtype=wl.F32,
+                router="normal", seed=7)
+    base.update(kw)
+    return wl.MoEConfig(**base)
+
+
+# ---------------------------------------------------------------- hand-worked example
+def test_hand_example_tables(oracle):
+    g = json.load(open(GOLD))
+    logits = np.array(g["logits"], dtype=np.float32)
+    idx, w = oracle.route_topk(logits, g["k"])
+    assert idx.tolist() == g["topk_idx"]  # includes the e2 == e3 tie of token 2 -> lower index first
+    np.testing.assert_allclose(w, np.array(g["topk_w"]), atol=1e-7)
+    counts, offsets, perm, inv = oracle.build_tables(idx, g["E"])
+    assert counts.tolist() == g["counts"] and offsets.tolist() == g["offsets"]
+    assert perm.tolist() == g["perm"] and inv.tolist() == g["inv_perm"]
+    rc, ro, tok, mask, p2d = oracle.build_dedup(idx, g["E"], g["R"])
+    assert rc.tolist() == g["rank_counts"] and ro.tolist() == g["rank_offsets"]
+    assert tok.tolist() == g["dedup_tok"] and mask.tolist() == g["dedup_mask"]
+    assert p2d.tolist() == g["pair_to_dedup"]
+
+
+def test_hand_example_forward_identical_experts(oracle):
+    """Identical experts, local = rank 0 only: y[t] = (sum of local weights) * FFN(x_t); token 2 has no local slot."""
+    g = json.load(open(GOLD))
+    rng = np.random.default_rng(3)
+    d, f = 8, 12
+    x = rng.standard_normal((4, d)).astype(np.float32)
+    Wg1, Wu1 = rng.standard_normal((2, d, f)).astype(np.float32) * 0.3
+    Wd1 = rng.standard_normal((f, d)).astype(np.float32) * 0.3
+    idx = np.array(g["topk_idx"], dtype=np.int32)
+    w = np.array(g["topk_w"], dtype=np.float32)
+    Wg, Wu, Wd = (np.stack([a, a]) for a in (Wg1, Wu1, Wd1))  # rank 0 hosts experts 0 and 1
+    y = oracle.forward(x, idx, w, Wg, Wu, Wd, E=4, R=2, local_rank_begin=0, local_rank_end=1)
+    ffn = brute.ffn_dense(x, Wg1, Wu1, Wd1)
+    scale = np.zeros(4)
+    for t, s in g["local_rank0"]["y_scale"].items():
+        scale[int(t)] = s
+    np.testing.assert_allclose(y, scale[:, None] * ffn, rtol=1e-6, atol=1e-7)
+    assert np.all(y[2] == 0.0)
+
+
+# ---------------------------------------------------------------- routing
+@pytest.mark.parametrize("T,E,k", [(50, 8, 2), (33, 16, 16), (40, 5, 1), (64, 256, 8), (17, 3, 3)])
+def test_route_vs_full_sort_and_full_softmax(oracle, T, E, k):
+    rng = np.random.default_rng(T * 1000 + E)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[::3] = np.round(logits[::3] * 2) / 2  # plenty of exact ties
+    idx, w = oracle.route_topk(logits, k)
+    bidx, bw = brute.route_bruteforce(logits, k)
+    assert np.array_equal(idx, bidx)
+    np.testing.assert_allclose(w, bw, atol=2e-7)
+    np.testing.assert_allclose(w.astype(np.float64).sum(axis=1), 1.0, atol=1e-6)
+
+
+def test_route_special_cases(oracle):
+    from scipy.special import softmax
+    rng = np.random.default_rng(0)
+    logits = rng.standard_normal((20, 6)).astype(np.float32)
+    idx1, w1 = oracle.route_topk(logits, 1)
+    assert np.array_equal(idx1[:, 0], logits.argmax(axis=1)) and np.all(w1 == 1.0)
+    idxE, wE = oracle.route_topk(logits, 6)  # k = E: plain softmax, in descending-logit order
+    sm = softmax(logits.astype(np.float64), axis=1)
+    np.testing.assert_allclose(wE, np.take_along_axis(sm, idxE, axis=1), atol=2e-7)
+    assert np.all(np.diff(np.take_along_axis(logits, idxE, axis=1), axis=1) <= 0)
+
+
+def test_route_signed_zero_is_a_tie(oracle):
+    logits = np.array([[-0.0, 0.0, -1.0], [0.0, -0.0, -1.0]], dtype=np.float32)
+    idx, w = oracle.route_topk(logits, 2)
+    assert idx.tolist() == [[0, 1], [0, 1]]
+    np.testing.assert_allclose(w, 0.5)
+
+
+def test_route_rejects_nonfinite(oracle):
+    logits = np.array([[0.0, np.nan, 1.0]], dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.route_topk(logits, 2)
+
+
+# ---------------------------------------------------------------- dispatch tables
+@pytest.mark.parametrize("T,E,k", [(1, 4, 2), (100, 8, 2), (257, 32, 8), (64, 4, 4), (90, 64, 1)])
+def test_tables_vs_stable_argsort(oracle, T, E, k):
+    rng = np.random.default_rng(E + k)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[:, : E // 2] -= 2.0  # skew: some experts (nearly) empty
+    idx, _ = oracle.route_topk(logits, k)
+    counts, offsets, perm, inv = oracle.build_tables(idx, E)
+    bc, bo, bp, bi = brute.tables_bruteforce(idx, E)
+    assert np.array_equal(counts, bc) and np.array_equal(offsets, bo)
+    assert np.array_equal(perm, bp) and np.array_equal(inv, bi)
+    # invariants: permutation, inverse, dense per-expert segments with strictly increasing token ids
+    assert counts.sum() == T * k
+    assert np.array_equal(np.sort(perm), np.arange(T * k))
+    assert np.array_equal(perm[inv], np.arange(T * k))
+    for e in range(E):
+        seg = perm[offsets[e]:offsets[e + 1]]
+        assert np.all(idx.ravel()[seg] == e)
+        assert np.all(np.diff(seg // k) > 0)
+
+
+def test_tables_empty_input(oracle):
+    idx = np.zeros((0, 2), dtype=np.int32)
+    counts, offsets, perm, inv = oracle.build_tables(idx, 4)
+    assert counts.tolist() == [0] * 4 and offsets.tolist() == [0] * 5 and perm.size == 0
+
+
+# ---------------------------------------------------------------- dedup
+@pytest.mark.parametrize("T,E,k,R", [(60, 8, 2, 4), (40, 16, 4, 16), (40, 16, 4, 1), (55, 32, 8, 4), (30, 32, 32, 8),
+                                     (25, 6, 1, 3)])
+def test_dedup_vs_set_enumeration(oracle, T, E, k, R):
+    rng = np.random.default_rng(T + R)
+    idx, _ = oracle.route_topk(rng.standard_normal((T, E)).astype(np.float32), k)
+    rc, ro, tok, mask, p2d = oracle.build_dedup(idx, E, R)
+    brc, btok, bmask, bp2d = brute.dedup_bruteforce(idx, E, R)
+    assert np.array_equal(rc, brc) and np.array_equal(tok, btok)
+    assert np.array_equal(mask, bmask) and np.array_equal(p2d, bp2d)
+    assert np.array_equal(ro, np.concatenate([[0], np.cumsum(rc)]))
+    assert sum(bin(int(m)).count("1") for m in mask) == T * k
+    if R == 1 or k == 1:
+        assert ro[R] == T
+    if R == E:
+        assert ro[R] == T * k
+
+
+@pytest.mark.parametrize("name", ["tiny", "deepseek_v3", "qwen3", "mixtral", "gpt_oss"])
+def test_dedup_count_matches_closed_form_for_uniform_routing(oracle, name):
+    """With iid continuous logits the top-k set is a uniform k-subset, so E[U_all]/T has a closed form."""
+    cfg = wl.CONFIGS[name].scaled(router="normal", T=4096, d=8, dtype=wl.F32)
+    w = wl.make_workload(cfg, weights=False)
+    idx, _ = oracle.route_topk(w.logits, cfg.k)
+    _, ro, *_ = oracle.build_dedup(idx, cfg.E, cfg.R)
+    mean = brute.expected_unique_ranks_per_token(cfg.E, cfg.R, cfg.k)
+    # per-token count lies in [1, min(k, R)]: its variance is at most (range/2)^2
+    sigma = (min(cfg.k, cfg.R) - 1) / 2 / math.sqrt(cfg.T) + 1e-12
+    assert abs(ro[cfg.R] / cfg.T - mean) <= 4 * sigma
+
+
+def test_closed_form_values_quoted_for_the_configs():
+    vals = {n: brute.expected_unique_ranks_per_token(c.E, c.R, c.k) for n, c in wl.CONFIGS.items()}
+    assert abs(vals["tiny"] - 1.857) < 1e-3 and abs(vals["deepseek_v3"] - 5.295) < 1e-3
+    assert abs(vals["qwen3"] - 5.339) < 1e-3 and abs(vals["mixtral"] - 2.0) < 1e-12
+    assert abs(vals["gpt_oss"] - 2.754) < 1e-3
+    # redundancy claim of Sec. II-B (256 experts, 32 GPUs): share of four-direction traffic that is redundant
+    for k, lo in ((8, 0.40), (16, 0.44), (32, 0.46)):
+        u = brute.expected_unique_ranks_per_token(256, 32, k)
+        assert lo < (2 * u - 2) / (4 * u) < 0.5
+
+
+# ---------------------------------------------------------------- forward
+def _draw(cfg, seed=0):
+    w = wl.make_workload(cfg)
+    return w
+
+
+def test_forward_single_expert_is_dense_ffn(oracle):
+    """E = 1, k = 1: the layer is one dense SwiGLU FFN (catches transposed weights, wrong activation)."""
+    cfg = small_cfg(E=1, k=1, R=1, local_rank_begin=0, local_rank_end=1, T=9, d=10, f=14)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, 1)
+    y = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, 1, 1, 0, 1)
+    np.testing.assert_allclose(y, brute.ffn_dense(w.x, w.W_gate[0], w.W_up[0], w.W_down[0]), rtol=1e-9, atol=1e-11)
+
+
+@pytest.mark.parametrize("lr", [(0, 4), (1, 3), (3, 4)])
+def test_forward_vs_table_free_bruteforce(oracle, lr):
+    cfg = small_cfg(local_rank_begin=lr[0], local_rank_end=lr[1])
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    y = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr)
+    yb = brute.forward_bruteforce(w.x, w.logits, cfg.k, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr)
+    np.testing.assert_allclose(y, yb, rtol=1e-6, atol=1e-7)  # topk_w is stored in fp32
+
+
+def test_forward_identical_experts_all_local_is_dense_ffn(oracle):
+    cfg = small_cfg(local_rank_begin=0, local_rank_end=4)
+    w = _draw(cfg)
+    Wg, Wu, Wd = (np.repeat(a[:1], cfg.E, axis=0) for a in (w.W_gate, w.W_up, w.W_down))
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    y = oracle.forward(w.x, idx, tw, Wg, Wu, Wd, cfg.E, cfg.R, 0, 4)
+    np.testing.assert_allclose(y, brute.ffn_dense(w.x, Wg[0], Wu[0], Wd[0]), rtol=1e-6, atol=1e-7)
+
+
+def test_forward_algebraic_properties(oracle):
+    cfg = small_cfg(T=40, local_rank_begin=1, local_rank_end=2)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    args = (cfg.E, cfg.R, cfg.local_rank_begin, cfg.local_rank_end)
+    y = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, *args)
+    # linear in W_down
+    y3 = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, (w.W_down * np.float32(4.0)), *args)
+    np.testing.assert_allclose(y3, 4.0 * y, rtol=1e-12)
+    # zero up-projection or zero gate (silu(0) = 0) kills the output
+    assert np.all(oracle.forward(w.x, idx, tw, w.W_gate, np.zeros_like(w.W_up), w.W_down, *args) == 0)
+    assert np.all(oracle.forward(w.x, idx, tw, np.zeros_like(w.W_gate), w.W_up, w.W_down, *args) == 0)
+    # token-permutation equivariance
+    p = np.random.default_rng(1).permutation(cfg.T)
+    yp = oracle.forward(w.x[p], idx[p], tw[p], w.W_gate, w.W_up, w.W_down, *args)
+    np.testing.assert_array_equal(yp, y[p])
+    # token subset == rows of the full result; tokens without a local slot are exactly zero
+    sel = np.array([5, 0, 17], dtype=np.int32)
+    ys = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, *args, tokens=sel)
+    np.testing.assert_array_equal(ys, y[sel])
+    epr = cfg.E // cfg.R
+    local = (idx // epr >= cfg.local_rank_begin) & (idx // epr < cfg.local_rank_end)
+    assert np.all(y[~local.any(axis=1)] == 0) and (~local.any(axis=1)).any()
+    # swapping gate and up changes the result (silu is applied to the gate branch only)
+    ysw = oracle.forward(w.x, idx, tw, w.W_up, w.W_gate, w.W_down, *args)
+    assert np.abs(ysw - y).max() > 1e-3
+
+
+def test_forward_bf16_inputs_are_widened_exactly(oracle):
+    cfg = small_cfg(dtype=wl.BF16)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    args = (cfg.E, cfg.R, cfg.local_rank_begin, cfg.local_rank_end)
+    y16 = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, *args)
+    y32 = oracle.forward(*(wl.bf16_bits_to_f32(a) for a in (w.x,)), idx, tw,
+                         *(wl.bf16_bits_to_f32(a) for a in (w.W_gate, w.W_up, w.W_down)), *args)
+    np.testing.assert_array_equal(y16, y32)
+
+
+def test_forward_float_accumulation_twin(oracle):
+    """fp32-accumulating build vs fp64-accumulating build: bounds the oracle's own rounding error."""
+    cfg = small_cfg(T=16, d=256, f=128)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    args = (cfg.E, cfg.R, cfg.local_rank_begin, cfg.local_rank_end)
+    y64 = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, *args, acc="f64")
+    y32 = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, *args, acc="f32")
+    assert np.abs(y64 - y32).max() <= 1e-5 * math.sqrt(cfg.d) * np.abs(y64).max()
+    assert np.abs(y64 - y32).max() > 0
+
+
+def test_bf16_rounding_helper_is_rne():
+    import struct
+
+    def bits(v):
+        return struct.unpack("<I", struct.pack("<f", v))[0]
+
+    vals = np.array([1.0, 1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, 1.0 + 2 ** -8 + 2 ** -20, -2.5, 0.0, 3.0e38], dtype=np.float32)
+    got = wl.f32_to_bf16_bits(vals)
+    # 1 + 2^-8 is a tie -> even (1.0); 1 + 3*2^-8 is a tie -> even (1 + 2^-6 = 0x3F82)
+    assert got[0] == 0x3F80 and got[1] == 0x3F80 and got[2] == 0x3F82 and got[3] == 0x3F81
+    assert got[4] == bits(-2.5) >> 16 and got[5] == 0
+    back = wl.bf16_bits_to_f32(got)
+    assert np.all(np.abs(back[:5] - vals[:5]) <= np.abs(vals[:5]) * 2 ** -8)
