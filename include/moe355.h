@@ -1,0 +1,176 @@
+/*
+ * moe355 -- one GPU's share of an expert-parallel MoE layer on AMD MI355X (gfx950).
+ *
+ * The calls follow the problem statement of "Accelerating MoE with Dynamic In-Switch Computing on
+ * Multi-GPUs" (DySHARP): the gate produces the routing before Dispatch (Sec. III-E), Dispatch places
+ * each token in the dense per-expert layout tensors of the GPUs that host its experts (Sec. III-D,
+ * AL Table), the experts run GEMM-1 and GEMM-2 (Sec. II-A), GEMM-2's epilogue applies the gate weight
+ * and Combine is an unweighted reduction of the k scaled outputs (Sec. III-C).  On one GPU the
+ * multicast of Dispatch becomes "read each token row once per GPU" and the in-switch reduction of
+ * Combine becomes "reduce a token's local partial outputs before its single write-back" (Sec. II-C).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; nothing is allocated, freed, copied to
+ *     the host or synchronised by the library.  `stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).  Work is enqueued on that stream only.
+ *   - Arrays are dense and row-major.  Inputs are never modified.  Outputs are fully overwritten.
+ *   - Return value: MOE_OK (0) or a negative moe_status.  Argument validation happens before the first
+ *     HIP call, so the error paths can be exercised on a host without a GPU.  No exception or abort
+ *     crosses this boundary.
+ *   - T == 0 is valid: tables describe an empty layer and y is not touched.
+ *   - Preconditions that are NOT checked (the result is then unspecified, but no access leaves the
+ *     caller's buffers): logits are finite; the k expert ids of a token are distinct and in [0, E).
+ */
+#ifndef MOE355_H
+#define MOE355_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE355_API __attribute__((visibility("default")))
+
+typedef enum {
+  MOE_OK = 0,
+  MOE_ERR_INVALID_ARG = -1, /* null pointer, E % R != 0, k out of range, bad local range, misaligned row size */
+  MOE_ERR_UNSUPPORTED = -2, /* dtype or extent this build has no kernel for                                   */
+  MOE_ERR_WORKSPACE = -3,   /* workspace pointer null or smaller than the matching *_workspace_bytes()         */
+  MOE_ERR_HIP = -4          /* a kernel launch was rejected by the runtime                                     */
+} moe_status;
+
+typedef enum { MOE_F32 = 0, MOE_BF16 = 1 } moe_dtype;
+
+/*
+ * Layer shape.  T tokens, hidden size d, expert FFN width f, E experts in total, k experts per token,
+ * R virtual ranks ("GPUs" of the expert-parallel group; expert e lives on rank e / (E/R), Sec. III-D).
+ * This GPU hosts ranks [local_rank_begin, local_rank_end), i.e. experts
+ * [local_rank_begin*E/R, local_rank_end*E/R), E_loc of them.
+ * Limits: E % R == 0; 1 <= k <= min(E, 32); E <= 4096; d and f multiples of 8 (rows are 16-byte multiples).
+ * dtype is the element type of x, the expert weights and y; accumulation is always fp32.
+ */
+typedef struct {
+  int32_t T, d, f, E, k, R;
+  int32_t local_rank_begin, local_rank_end;
+  int32_t dtype; /* moe_dtype */
+} moe_shape;
+
+/*
+ * Dispatch tables (all device pointers, caller-allocated).  A "pair" is (token t, slot j), id p = t*k + j.
+ *   counts[e]        pairs routed to expert e  (the nactive[expert] of Sec. III-E)            [E]
+ *   offsets[e]       first layout row of expert e; offsets[E] = number of valid pairs          [E+1]
+ *   perm[row]        pair id stored in layout row `row` (token id list per tile, Sec. IV-B)    [T*k]
+ *   inv_perm[p]      layout row of pair p (algebraic -> layout index, Sec. III-D); rows of one  [T*k]
+ *                    expert are handed out in ascending token order
+ *   rank_counts[r]   distinct tokens that have at least one slot on rank r                      [R]
+ *   rank_offsets[r]  exclusive prefix sum; rank_offsets[R] = U_all, the number of entries below [R+1]
+ *   dedup_tok[u]     token of entry u; entries are ordered by (rank, token)                     [T*min(k,R)]
+ *   dedup_mask[u]    bit j set iff slot j of that token lies on that rank                       [T*min(k,R)]
+ *   pair_to_dedup[p] entry index of (rank of pair p, token of pair p)                           [T*k]
+ * Only the first rank_offsets[R] entries of dedup_tok / dedup_mask are written.
+ */
+typedef struct {
+  int32_t *counts;
+  int32_t *offsets;
+  int32_t *perm;
+  int32_t *inv_perm;
+  int32_t *rank_counts;
+  int32_t *rank_offsets;
+  int32_t *dedup_tok;
+  uint32_t *dedup_mask;
+  int32_t *pair_to_dedup;
+} moe_dispatch;
+
+/* Host-only size queries (no HIP call).  Return 0 for an invalid shape. */
+MOE355_API size_t moe_dispatch_workspace_bytes(const moe_shape *shape);
+MOE355_API size_t moe_forward_workspace_bytes(const moe_shape *shape);
+/* Bytes of the packed gate/up buffer (which = 0) or the packed down buffer (which = 1). */
+MOE355_API size_t moe_packed_weight_bytes(const moe_shape *shape, int which);
+
+/*
+ * Routing (Sec. II-A: each token activates the top-k experts chosen by the gate).
+ * logits [T,E] fp32.  For each token the k largest logits are selected (ties: lower expert index first)
+ * and reported in descending order in topk_idx [T,k]; topk_w [T,k] is the softmax over the logits
+ * renormalised over the k picks (fp32, sums to 1).
+ */
+MOE355_API int moe_route_topk(const moe_shape *shape, const float *logits, int32_t *topk_idx, float *topk_w,
+                              void *stream);
+
+/*
+ * Dispatch tables from the routing (Sec. III-D AL Table / Sec. III-E nactive / Sec. II-B redundancy).
+ * Fills every array of `out` for all E experts and all R ranks (local or not).  The result is unique:
+ * integer-exact and independent of scheduling.  workspace >= moe_dispatch_workspace_bytes(shape).
+ */
+MOE355_API int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One-off re-tiling of the static expert weights into the layout the GEMM kernels stream
+ * (not part of the per-step path).  Inputs are the plain "input x output" matrices of the local experts:
+ * W_gate, W_up [E_loc, d, f], W_down [E_loc, f, d].  Outputs are opaque buffers of
+ * moe_packed_weight_bytes(shape, 0 / 1) bytes, 256-byte aligned, valid for any T.
+ */
+MOE355_API int moe_pack_weights(const moe_shape *shape, const void *W_gate, const void *W_up, const void *W_down,
+                                void *packed_gate_up, void *packed_down, void *stream);
+
+/*
+ * Fused Dispatch -> GEMM-1 -> SwiGLU -> GEMM-2 (x gate weight) -> Combine for the local experts
+ * (Sec. II-A, III-C, IV-A).  x [T,d]; y [T,d], y[t] = sum over the local slots j of token t of
+ * topk_w[t,j] * FFN_{e(t,j)}(x[t]); rows of tokens without a local slot are written as zeros.
+ * Token rows are gathered straight into the GEMM-1 tiles (no dispatched copy of x is materialised);
+ * each y row is written exactly once, without atomics.
+ * `tables` must come from moe_build_dispatch on the same shape and topk_idx.
+ * workspace >= moe_forward_workspace_bytes(shape), 256-byte aligned; its contents are scratch.
+ */
+MOE355_API int moe_fused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                 const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                 const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                 void *stream);
+
+/*
+ * moe_fused_forward with the kernel boundaries marked for measurement: `events` points at five hipEvent_t
+ * (created by the caller with timing enabled; a NULL entry is skipped) which are recorded on `stream`
+ * [0] before the first kernel, [1] after the tile-table kernel, [2] after GEMM-1, [3] after GEMM-2,
+ * [4] after Combine.  The kernels and their order are those of moe_fused_forward.
+ */
+MOE355_API int moe_fused_forward_timed(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                       const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                       const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                       void *stream, void *const *events);
+
+/*
+ * Phase-split entry points, used to measure Dispatch and Combine on their own (Sec. VI "pure
+ * communication" test) and as building blocks of the unfused comparison path.
+ *
+ * moe_dispatch_gather: materialise the local layout tensor xs [P_cap, d] (P_cap = T*min(k,E_loc) rows):
+ *   every entry of the dedup table that belongs to a local rank reads its token row once and writes it
+ *   to the layout row of each of its slots (the one-GPU form of the multicast of Sec. II-C).
+ * moe_combine_reduce: rows [P_cap, d] fp32 are the gate-weighted expert outputs in layout order;
+ *   y[t] = sum of the rows of t's local slots (slot order), one write per token, zeros if none.
+ */
+MOE355_API int moe_dispatch_gather(const moe_shape *shape, const void *x, const moe_dispatch *tables, void *xs,
+                                   void *stream);
+MOE355_API int moe_combine_reduce(const moe_shape *shape, const float *rows, const int32_t *topk_idx,
+                                  const moe_dispatch *tables, void *y, void *stream);
+
+/*
+ * Unfused comparison path (Sec. V-C style baseline without redundancy removal): explicit gather copy,
+ * the same grouped GEMMs on the copied rows, then a scatter-add of every weighted row into a zeroed fp32
+ * buffer with atomics, then a cast to y.  Same arguments as moe_fused_forward; needs
+ * moe_unfused_workspace_bytes(shape).
+ */
+MOE355_API size_t moe_unfused_workspace_bytes(const moe_shape *shape);
+MOE355_API int moe_unfused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                   const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                   const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                   void *stream);
+
+/* Static string for a status code. */
+MOE355_API const char *moe_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE355_H */

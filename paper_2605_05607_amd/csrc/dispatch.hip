@@ -1,0 +1,242 @@
+// moe_build_dispatch: per-expert counts and offsets (the nactive[expert] of Sec. III-E), the stable
+// algebraic<->layout row maps (AL Table of Sec. III-D; token id list per tile of Sec. IV-B) and the table of
+// distinct (token, rank) pairs (the redundancy of Sec. II-B; rank(e) = e / experts_per_rank, Sec. III-D).
+//
+// Three small kernels, no atomics on device memory, so the result does not depend on scheduling:
+//   1. hist : the token range is cut into <= 64 chunks, one wave per chunk counts its pairs per expert and
+//             its first-of-rank pairs per rank (LDS counters);
+//   2. scan : per expert, an exclusive wave scan across the chunks (lane = chunk) gives each chunk its
+//             starting cursor; a block scan across experts gives offsets;
+//   3. place: each wave walks its chunk again in pair order; lanes holding the same expert are found with
+//             one ballot per bit of the expert id, the popcount of the lower lanes is the rank inside the
+//             group, and the highest lane of the group advances the LDS cursor.
+#include "common.h"
+
+namespace moe355 {
+
+constexpr int kMaxChunks = 64;
+
+struct PairLane {
+  int t, j, e, r;
+  bool active, valid;
+};
+
+// Lane -> pair assignment of one iteration: floor(64 / k) whole tokens, slot-major inside a token.
+__device__ __forceinline__ PairLane load_pair(const int32_t *__restrict__ topk_idx, int t0, int t_end, int k,
+                                              int tpi, int E, int epr) {
+  PairLane p;
+  const int lane = lane_id();
+  const int tl = lane / k;
+  p.j = lane - tl * k;
+  p.t = t0 + tl;
+  p.active = tl < tpi && p.t < t_end;
+  p.e = p.active ? topk_idx[(size_t)p.t * k + p.j] : -1;
+  p.valid = p.active && p.e >= 0 && p.e < E;
+  p.r = p.valid ? p.e / epr : -1;
+  return p;
+}
+
+// Slots of the same token that lie on the same rank as this lane's slot (bit jj per slot).
+__device__ __forceinline__ uint32_t same_rank_slots(const PairLane &p, int k) {
+  const int lane = lane_id();
+  uint32_t m = 0;
+  for (int jj = 0; jj < k; ++jj) {
+    const int rr = __shfl(p.r, (lane - p.j + jj) & 63, 64);
+    if (p.valid && rr == p.r) m |= 1u << jj;
+  }
+  return m;
+}
+
+// Lanes among `pred` lanes whose `key` equals this lane's key (bits = number of significant key bits).
+__device__ __forceinline__ unsigned long long match_lanes(bool pred, int key, int bits) {
+  unsigned long long m = __ballot(pred);
+  for (int b = 0; b < bits; ++b) {
+    const bool bit = (key >> b) & 1;
+    const unsigned long long bal = __ballot(pred && bit);
+    m &= bit ? bal : ~bal;
+  }
+  return m;
+}
+
+__global__ __launch_bounds__(kWave) void dispatch_hist_kernel(const int32_t *__restrict__ topk_idx, int T, int E,
+                                                              int k, int R, int tpc, int32_t *__restrict__ chunk_cnt,
+                                                              int32_t *__restrict__ chunk_rcnt) {
+  extern __shared__ int sm[];
+  int *cnt = sm;
+  int *rcnt = sm + E;
+  const int lane = lane_id();
+  const int c = blockIdx.x;
+  for (int i = lane; i < E + R; i += kWave) sm[i] = 0;
+  __syncthreads();
+  const int epr = E / R;
+  const int tpi = kWave / k;
+  const int t_begin = c * tpc;
+  const int t_end = min(T, t_begin + tpc);
+  for (int t0 = t_begin; t0 < t_end; t0 += tpi) {
+    const PairLane p = load_pair(topk_idx, t0, t_end, k, tpi, E, epr);
+    const uint32_t slots = same_rank_slots(p, k);
+    if (p.valid) {
+      atomicAdd(&cnt[p.e], 1);
+      if ((slots & ((1u << p.j) - 1u)) == 0) atomicAdd(&rcnt[p.r], 1);  // first slot of its (token, rank)
+    }
+  }
+  __syncthreads();
+  for (int i = lane; i < E; i += kWave) chunk_cnt[(size_t)c * E + i] = cnt[i];
+  for (int i = lane; i < R; i += kWave) chunk_rcnt[(size_t)c * R + i] = rcnt[i];
+}
+
+__global__ __launch_bounds__(1024) void dispatch_scan_kernel(int nch, int E, int R, int32_t *__restrict__ chunk_cnt,
+                                                             int32_t *__restrict__ chunk_rcnt,
+                                                             int32_t *__restrict__ counts,
+                                                             int32_t *__restrict__ offsets,
+                                                             int32_t *__restrict__ rank_counts,
+                                                             int32_t *__restrict__ rank_offsets) {
+  extern __shared__ int sm[];
+  int *tot = sm;            // [E]
+  int *rtot = sm + E;       // [R]
+  int *scratch = rtot + R;  // [17]
+  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
+  const int nwaves = blockDim.x >> 6;
+  // across chunks: exclusive scan per expert / per rank, lane = chunk
+  for (int e = wave; e < E + R; e += nwaves) {
+    int32_t *col = e < E ? chunk_cnt + e : chunk_rcnt + (e - E);
+    const int stride = e < E ? E : R;
+    const int v = lane < nch ? col[(size_t)lane * stride] : 0;
+    const int inc = wave_inclusive_scan(v);
+    if (lane < nch) col[(size_t)lane * stride] = inc - v;
+    if (lane == 63) sm[e] = inc;
+  }
+  __syncthreads();
+  // across experts, then across ranks: each thread owns a run of consecutive items
+  for (int pass = 0; pass < 2; ++pass) {
+    const int n = pass == 0 ? E : R;
+    const int *src = pass == 0 ? tot : rtot;
+    int32_t *cnt_out = pass == 0 ? counts : rank_counts;
+    int32_t *off_out = pass == 0 ? offsets : rank_offsets;
+    const int ipt = (n + blockDim.x - 1) / blockDim.x;
+    const int lo = min(n, (int)threadIdx.x * ipt);
+    const int hi = min(n, lo + ipt);
+    int local = 0;
+    for (int i = lo; i < hi; ++i) local += src[i];
+    int total;
+    int run = block_exclusive_scan(local, scratch, &total);
+    for (int i = lo; i < hi; ++i) {
+      const int v = src[i];
+      cnt_out[i] = v;
+      off_out[i] = run;
+      run += v;
+    }
+    if (threadIdx.x == 0) off_out[n] = total;
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(kWave) void dispatch_place_kernel(
+    const int32_t *__restrict__ topk_idx, int T, int E, int k, int R, int tpc, int ebits, int rbits,
+    const int32_t *__restrict__ chunk_cnt, const int32_t *__restrict__ chunk_rcnt,
+    const int32_t *__restrict__ offsets, const int32_t *__restrict__ rank_offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv_perm, int32_t *__restrict__ dedup_tok, uint32_t *__restrict__ dedup_mask,
+    int32_t *__restrict__ pair_to_dedup) {
+  extern __shared__ int sm[];
+  int *cursor = sm;       // [E] next free layout row of each expert for this chunk
+  int *rcursor = sm + E;  // [R] next free dedup entry of each rank for this chunk
+  const int lane = lane_id();
+  const int c = blockIdx.x;
+  for (int i = lane; i < E; i += kWave) cursor[i] = offsets[i] + chunk_cnt[(size_t)c * E + i];
+  for (int i = lane; i < R; i += kWave) rcursor[i] = rank_offsets[i] + chunk_rcnt[(size_t)c * R + i];
+  __syncthreads();
+  const int epr = E / R;
+  const int tpi = kWave / k;
+  const int t_begin = c * tpc;
+  const int t_end = min(T, t_begin + tpc);
+  const unsigned long long lower = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+  const long long npairs = (long long)T * k;
+  const long long ndedup = (long long)T * min(k, R);
+  for (int t0 = t_begin; t0 < t_end; t0 += tpi) {
+    const PairLane p = load_pair(topk_idx, t0, t_end, k, tpi, E, epr);
+    const size_t pid = (size_t)p.t * k + p.j;
+
+    // ---- layout row of every pair (stable: lower lanes are earlier pairs) ----
+    const unsigned long long grp = match_lanes(p.valid, p.e, ebits);
+    int row = -1;
+    if (p.valid) row = cursor[p.e] + __popcll(grp & lower);
+    __syncthreads();
+    if (p.valid && (lane == 63 || (grp >> (lane + 1)) == 0)) cursor[p.e] = row + 1;
+    if (p.active) inv_perm[pid] = row;
+    if (p.valid && row >= 0 && row < npairs) perm[row] = (int32_t)pid;
+
+    // ---- distinct (token, rank) entries ----
+    const uint32_t slots = same_rank_slots(p, k);
+    const bool first = p.valid && (slots & ((1u << p.j) - 1u)) == 0;
+    const unsigned long long rgrp = match_lanes(first, p.r, rbits);
+    int pos = -1;
+    if (first) pos = rcursor[p.r] + __popcll(rgrp & lower);
+    __syncthreads();
+    if (first && (lane == 63 || (rgrp >> (lane + 1)) == 0)) rcursor[p.r] = pos + 1;
+    if (first && pos >= 0 && pos < ndedup) {
+      dedup_tok[pos] = p.t;
+      dedup_mask[pos] = slots;
+    }
+    const int first_slot = slots ? __builtin_ctz(slots) : 0;
+    const int pos_of_first = __shfl(pos, (lane - p.j + first_slot) & 63, 64);
+    if (p.active) pair_to_dedup[pid] = p.valid ? pos_of_first : -1;
+    __syncthreads();
+  }
+}
+
+}  // namespace moe355
+
+using namespace moe355;
+
+static int chunking(int T, int *tpc) {
+  if (T <= 0) {
+    *tpc = 1;
+    return 0;
+  }
+  *tpc = ceil_div(T, kMaxChunks);
+  return ceil_div(T, *tpc);
+}
+
+extern "C" size_t moe_dispatch_workspace_bytes(const moe_shape *shape) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK) return 0;
+  return align_up((size_t)kMaxChunks * (shape->E + shape->R) * sizeof(int32_t), 256);
+}
+
+extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!topk_idx || !out) return MOE_ERR_INVALID_ARG;
+  if (!out->counts || !out->offsets || !out->perm || !out->inv_perm || !out->rank_counts || !out->rank_offsets ||
+      !out->dedup_tok || !out->dedup_mask || !out->pair_to_dedup)
+    return MOE_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < moe_dispatch_workspace_bytes(shape)) return MOE_ERR_WORKSPACE;
+  const int T = shape->T, E = shape->E, k = shape->k, R = shape->R;
+  int tpc;
+  const int nch = chunking(T, &tpc);
+  int32_t *chunk_cnt = static_cast<int32_t *>(workspace);
+  int32_t *chunk_rcnt = chunk_cnt + (size_t)kMaxChunks * E;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t sm_wave = (size_t)(E + R) * sizeof(int);
+  if (nch > 0) {
+    hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nch), dim3(kWave), sm_wave, st, topk_idx, T, E, k, R, tpc,
+                       chunk_cnt, chunk_rcnt);
+    if ((rc = launch_status()) != MOE_OK) return rc;
+  }
+  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), sm_wave + 17 * sizeof(int), st, nch, E, R, chunk_cnt,
+                     chunk_rcnt, out->counts, out->offsets, out->rank_counts, out->rank_offsets);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  if (nch > 0) {
+    int ebits = 0, rbits = 0;
+    while ((1 << ebits) < E) ++ebits;
+    while ((1 << rbits) < R) ++rbits;
+    hipLaunchKernelGGL(dispatch_place_kernel, dim3(nch), dim3(kWave), sm_wave, st, topk_idx, T, E, k, R, tpc, ebits,
+                       rbits, chunk_cnt, chunk_rcnt, out->offsets, out->rank_offsets, out->perm, out->inv_perm,
+                       out->dedup_tok, out->dedup_mask, out->pair_to_dedup);
+    if ((rc = launch_status()) != MOE_OK) return rc;
+  }
+  return MOE_OK;
+}

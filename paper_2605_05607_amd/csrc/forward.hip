@@ -1,0 +1,684 @@
+// moe_fused_forward and its building blocks: weight packing, tile table, grouped SwiGLU GEMMs (GEMM-1 and
+// GEMM-2 of Sec. II-A) with the token gather fused into GEMM-1's operand load (Dispatch of Sec. II-A without a
+// materialised copy), the gate weight applied in GEMM-2's epilogue (Sec. III-C), and the per-token reduction
+// with a single write-back (Combine; the one-GPU form of the in-switch reduction of Sec. II-C).
+#include <algorithm>
+
+#include "common.h"
+
+namespace moe355 {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS stage image of B (32 KiB)
+
+// ------------------------------------------------------------------------------------------------
+// Weight packing (one-off).  Output tile (le, nt, kt) holds kBN output columns x kBK reduction indices,
+// stored column-major-in-k: row n_l of the tile is the 128-byte run of its 64 k values, cut into eight
+// 16-byte chunks; chunk c of row n_l is stored at slot c ^ (n_l & 7) so that the MFMA operand reads of
+// eight neighbouring rows fall on different LDS banks.  Zero-padded outside the matrix.
+// GATED tiles interleave gate and up columns so that one wave owns both halves of the same h columns:
+// tile rows [0,128) belong to the wave column 0, [128,256) to wave column 1; inside each, rows [0,64) are
+// gate columns and [64,128) the matching up columns.
+// ------------------------------------------------------------------------------------------------
+template <bool GATED>
+__global__ __launch_bounds__(256) void pack_bf16_kernel(const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1,
+                                                        bf16_t *__restrict__ out, int K, int N, int n_ntiles,
+                                                        int n_ktiles) {
+  // grid: x = kt, y = nt, z = le;   256 threads: thread = tile row n_l, loops over the 8 chunks
+  const int kt = blockIdx.x, nt = blockIdx.y, le = blockIdx.z;
+  const int n_l = threadIdx.x;
+  const bf16_t *W;
+  int col;
+  if (GATED) {
+    const int wn = n_l >> 7, b = (n_l & 127) >> 5, i = n_l & 31;
+    W = b < 2 ? W0 : W1;
+    col = nt * (kBN / 2) + wn * 64 + (b & 1) * 32 + i;
+  } else {
+    W = W0;
+    col = nt * kBN + n_l;
+  }
+  const size_t wbase = (size_t)le * K * N;
+  bf16_t *tile = out + ((size_t)(le * n_ntiles + nt) * n_ktiles + kt) * (kBN * kBK);
+  for (int c = 0; c < 8; ++c) {
+    bf16x8 v;
+    for (int q = 0; q < 8; ++q) {
+      const int kk = kt * kBK + c * 8 + q;
+      v[q] = (col < N && kk < K) ? W[wbase + (size_t)kk * N + col] : (bf16_t)0.0f;
+    }
+    *reinterpret_cast<bf16x8 *>(tile + (size_t)n_l * kBK + ((c ^ (n_l & 7)) << 3)) = v;
+  }
+}
+
+__global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, size_t n) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
+}
+
+// ------------------------------------------------------------------------------------------------
+// Tile table and per-row metadata of the local layout segment.
+// header[0] = number of M tiles, header[1] = P (local rows), header[2] = first layout row of the segment.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict__ offsets,
+                                                       const int32_t *__restrict__ perm,
+                                                       const float *__restrict__ topk_w, int T, int k, int e_lo,
+                                                       int E_loc, int bm, int P_cap, int max_mtiles,
+                                                       int32_t *__restrict__ header, int32_t *__restrict__ tile_e,
+                                                       int32_t *__restrict__ tile_m0,
+                                                       int32_t *__restrict__ tile_rows,
+                                                       int32_t *__restrict__ row_tok, float *__restrict__ row_w) {
+  __shared__ int scratch[17];
+  const int base = offsets[e_lo];
+  const int P = max(0, min(P_cap, offsets[e_lo + E_loc] - base));
+  const long long npairs = (long long)T * k;
+  for (int r = blockIdx.x * blockDim.x + threadIdx.x; r < P; r += gridDim.x * blockDim.x) {
+    int p = perm[base + r];
+    p = p < 0 ? 0 : (p >= npairs ? (int)(npairs - 1) : p);
+    row_tok[r] = p / k;
+    row_w[r] = topk_w[p];
+  }
+  if (blockIdx.x != 0) return;
+  // M tiles of expert le: ceil(count / bm), listed expert after expert
+  const int ipt = (E_loc + blockDim.x - 1) / blockDim.x;
+  const int lo = min(E_loc, (int)threadIdx.x * ipt);
+  const int hi = min(E_loc, lo + ipt);
+  int local = 0;
+  for (int le = lo; le < hi; ++le) {
+    const int cnt = max(0, offsets[e_lo + le + 1] - offsets[e_lo + le]);
+    local += (cnt + bm - 1) / bm;
+  }
+  int total;
+  int run = block_exclusive_scan(local, scratch, &total);
+  for (int le = lo; le < hi; ++le) {
+    const int start = offsets[e_lo + le] - base;
+    const int cnt = max(0, offsets[e_lo + le + 1] - offsets[e_lo + le]);
+    for (int m = 0; m < cnt; m += bm) {
+      if (run < max_mtiles && start + m < P) {
+        tile_e[run] = le;
+        tile_m0[run] = start + m;
+        tile_rows[run] = min(bm, min(cnt - m, P - (start + m)));
+      }
+      ++run;
+    }
+  }
+  if (threadIdx.x == 0) {
+    header[0] = min(total, max_mtiles);
+    header[1] = P;
+    header[2] = base;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Grouped bf16 GEMM on the matrix cores.  C[rows of one expert tile, kBN/2 or kBN columns] = A * W_e.
+//   A rows   : row_map == nullptr -> A[m0 + r, :]; else A[row_map[m0 + r], :] (token gather of Dispatch).
+//   B tiles  : packed images streamed linearly from HBM.
+//   GATED    : epilogue h = silu(g) * u, written as bf16   (GEMM-1)
+//   !GATED   : epilogue o = acc * row_w[row], written fp32 (GEMM-2, gate weight of Sec. III-C)
+// 256 threads = 4 waves in a 2 x 2 arrangement, each wave owns 64 x 128 of the 128 x 256 tile as
+// 2 x 4 MFMA 32x32x16 accumulators.  One LDS stage (48 KiB) with the next stage prefetched into registers;
+// two workgroups per CU overlap each other's load and MFMA phases.
+// ------------------------------------------------------------------------------------------------
+struct GemmArgs {
+  const void *A;
+  const int32_t *row_map;
+  const void *Bp;
+  void *out;
+  const float *row_w;
+  const int32_t *header, *tile_e, *tile_m0, *tile_rows;
+  int K, N, lda, ldo, n_ntiles, n_ktiles;
+};
+
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+template <bool GATED>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[(kBM + kBN) * kBK * 2];
+  unsigned char *sA = smem;
+  unsigned char *sB = smem + kBM * kBK * 2;
+
+  const int mt = blockIdx.y;
+  if (mt >= g.header[0]) return;
+  const int nt = blockIdx.x;
+  const int le = g.tile_e[mt];
+  const int m0 = g.tile_m0[mt];
+  const int rows = g.tile_rows[mt];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  // ---- global -> register staging assignment ----
+  const int a_chunk = tid & 7;  // 16-byte chunk (8 reduction indices) inside the 64-wide k slab
+  const bf16_t *a_src[4];
+  int a_dst[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = (tid >> 3) + 32 * i;
+    const int rc = r < rows ? r : rows - 1;  // padding rows repeat the last valid row (results discarded)
+    const int src_row = g.row_map ? g.row_map[m0 + rc] : m0 + rc;
+    a_src[i] = static_cast<const bf16_t *>(g.A) + (size_t)src_row * g.lda + a_chunk * 8;
+    a_dst[i] = (r * 8 + (a_chunk ^ (r & 7))) * 16;
+  }
+  const unsigned char *b_src =
+      static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
+
+  uint4 ra[4], rb[8];
+  auto load_stage = [&](int kt) {
+    const bool k_ok = kt * kBK + a_chunk * 8 < g.K;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      ra[i] = k_ok ? *reinterpret_cast<const uint4 *>(a_src[i] + kt * kBK) : make_uint4(0, 0, 0, 0);
+    const unsigned char *bt = b_src + (size_t)kt * kTileBytes;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const uint4 *>(bt + i * 4096);
+  };
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int ni = 0; ni < 4; ++ni)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+  // 32-row blocks of this wave that contain at least one valid row
+  const bool act0 = wm * 64 < rows;
+  const bool act1 = wm * 64 + 32 < rows;
+
+  // ---- LDS -> MFMA operand addressing ----
+  const int l31 = lane & 31, khalf = lane >> 5, sw = lane & 7;
+  const int a_row_off = (wm * 64 + l31) * 128;   // bytes; + mi * 32 rows
+  const int b_row_off = (wn * 128 + l31) * 128;  // bytes; + ni * 32 rows
+
+  load_stage(0);
+  for (int kt = 0; kt < g.n_ktiles; ++kt) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(sA + a_dst[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4 *>(sB + tid * 16 + i * 4096) = rb[i];
+    __syncthreads();
+    if (kt + 1 < g.n_ktiles) load_stage(kt + 1);
+    if (act0) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const int slot = ((kk * 2 + khalf) ^ sw) * 16;
+        bf16x8 b[4];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) b[ni] = *reinterpret_cast<const bf16x8 *>(sB + b_row_off + ni * 4096 + slot);
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(sA + a_row_off + slot);
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) acc[0][ni] = mfma_bf16(a0, b[ni], acc[0][ni]);
+        if (act1) {
+          const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(sA + a_row_off + 4096 + slot);
+#pragma unroll
+          for (int ni = 0; ni < 4; ++ni) acc[1][ni] = mfma_bf16(a1, b[ni], acc[1][ni]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- epilogue ----
+  // accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+    if (!(mi == 0 ? act0 : act1)) continue;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row_l = wm * 64 + mi * 32 + (r >> 2) * 8 + khalf * 4 + (r & 3);
+      if (row_l >= rows) continue;
+      const size_t grow = (size_t)(m0 + row_l);
+      if (GATED) {
+        bf16_t *h = static_cast<bf16_t *>(g.out) + grow * g.ldo;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int col = nt * (kBN / 2) + wn * 64 + b * 32 + l31;
+          const float gv = acc[mi][b][r], uv = acc[mi][b + 2][r];
+          if (col < g.N) h[col] = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
+        }
+      } else {
+        float *o = static_cast<float *>(g.out) + grow * g.ldo;
+        const float w = g.row_w[grow];
+#pragma unroll
+        for (int ni = 0; ni < 4; ++ni) {
+          const int col = nt * kBN + wn * 128 + ni * 32 + l31;
+          if (col < g.N) o[col] = acc[mi][ni][r] * w;
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Plain fp32 grouped GEMM (vector ALU) for fp32 layers: 64 x 64 tile, 16-wide k slab, 4 x 4 per thread.
+// Weights are the unpacked "input x output" matrices.
+// ------------------------------------------------------------------------------------------------
+template <bool GATED>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
+  __shared__ float sA[kFBM][kFBK + 1];
+  __shared__ float sB[GATED ? 2 : 1][kFBK][kFBN];
+  const int mt = blockIdx.y;
+  if (mt >= g.header[0]) return;
+  const int nt = blockIdx.x;
+  const int le = g.tile_e[mt];
+  const int m0 = g.tile_m0[mt];
+  const int rows = g.tile_rows[mt];
+  const int tid = threadIdx.x;
+  const int ty = tid >> 4, tx = tid & 15;
+  const float *A = static_cast<const float *>(g.A);
+  const size_t wsz = (size_t)g.K * g.N;
+  const float *W0 = static_cast<const float *>(g.Bp) + (size_t)le * wsz;
+  // gate matrices of all local experts come first, then the up matrices
+  const float *W1 = GATED ? W0 + (size_t)g.n_ktiles * wsz : nullptr;  // n_ktiles carries E_loc for this kernel
+
+  const int ar = tid >> 2, akq = (tid & 3) * 4;
+  const int arc = ar < rows ? ar : rows - 1;
+  const int a_row = g.row_map ? g.row_map[m0 + arc] : m0 + arc;
+  const float *a_src = A + (size_t)a_row * g.lda + akq;
+  const int bk = tid >> 4, bn4 = (tid & 15) * 4;
+  const int n0 = nt * kFBN;
+
+  float accg[4][4] = {}, accu[4][4] = {};
+  for (int k0 = 0; k0 < g.K; k0 += kFBK) {
+    float4 av = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k0 + akq < g.K) av = *reinterpret_cast<const float4 *>(a_src + k0);
+    sA[ar][akq + 0] = av.x; sA[ar][akq + 1] = av.y; sA[ar][akq + 2] = av.z; sA[ar][akq + 3] = av.w;
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f), bv1 = bv;
+    if (k0 + bk < g.K && n0 + bn4 < g.N) {
+      bv = *reinterpret_cast<const float4 *>(W0 + (size_t)(k0 + bk) * g.N + n0 + bn4);
+      if (GATED) bv1 = *reinterpret_cast<const float4 *>(W1 + (size_t)(k0 + bk) * g.N + n0 + bn4);
+    }
+    *reinterpret_cast<float4 *>(&sB[0][bk][bn4]) = bv;
+    if (GATED) *reinterpret_cast<float4 *>(&sB[GATED ? 1 : 0][bk][bn4]) = bv1;
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < kFBK; ++kk) {
+      float a[4], b0[4], b1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = sA[ty * 4 + i][kk];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        b0[j] = sB[0][kk][tx + 16 * j];
+        if (GATED) b1[j] = sB[GATED ? 1 : 0][kk][tx + 16 * j];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          accg[i][j] = fmaf(a[i], b0[j], accg[i][j]);
+          if (GATED) accu[i][j] = fmaf(a[i], b1[j], accu[i][j]);
+        }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row_l = ty * 4 + i;
+    if (row_l >= rows) continue;
+    const size_t grow = (size_t)(m0 + row_l);
+    float *out = static_cast<float *>(g.out) + grow * g.ldo;
+    const float w = GATED ? 1.f : g.row_w[grow];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + tx + 16 * j;
+      if (col >= g.N) continue;
+      if (GATED) {
+        const float gv = accg[i][j];
+        out[col] = (gv / (1.0f + expf(-gv))) * accu[i][j];
+      } else {
+        out[col] = accg[i][j] * w;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Combine: one workgroup per token sums the gate-weighted rows of the token's local slots in slot order
+// (fp32) and writes the y row once; tokens without a local slot get zeros.
+// ------------------------------------------------------------------------------------------------
+template <typename OutT>
+__device__ __forceinline__ void store8(OutT *dst, const float (&v)[8]);
+template <>
+__device__ __forceinline__ void store8<float>(float *dst, const float (&v)[8]) {
+  *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+template <>
+__device__ __forceinline__ void store8<bf16_t>(bf16_t *dst, const float (&v)[8]) {
+  bf16x8 o;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) o[q] = (bf16_t)v[q];
+  *reinterpret_cast<bf16x8 *>(dst) = o;
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ rows,
+                                                      const int32_t *__restrict__ topk_idx,
+                                                      const int32_t *__restrict__ inv_perm,
+                                                      const int32_t *__restrict__ offsets, int k, int d, int e_lo,
+                                                      int E_loc, int P_cap, OutT *__restrict__ y) {
+  __shared__ int srow[kMaxTopK];
+  __shared__ int snum;
+  const int t = blockIdx.x;
+  if (threadIdx.x == 0) {
+    const int base = offsets[e_lo];
+    int n = 0;
+    for (int j = 0; j < k; ++j) {
+      const int e = topk_idx[(size_t)t * k + j];
+      if (e < e_lo || e >= e_lo + E_loc) continue;
+      const int row = inv_perm[(size_t)t * k + j] - base;
+      if (row >= 0 && row < P_cap) srow[n++] = row;
+    }
+    snum = n;
+  }
+  __syncthreads();
+  const int n = snum;
+  for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < n; ++i) {
+      const float *src = rows + (size_t)srow[i] * d + c;
+      const float4 lo = *reinterpret_cast<const float4 *>(src);
+      const float4 hi = *reinterpret_cast<const float4 *>(src + 4);
+      acc[0] += lo.x; acc[1] += lo.y; acc[2] += lo.z; acc[3] += lo.w;
+      acc[4] += hi.x; acc[5] += hi.y; acc[6] += hi.z; acc[7] += hi.w;
+    }
+    store8<OutT>(y + (size_t)t * d + c, acc);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Dispatch as a materialised copy (phase-split entry point): one workgroup per local dedup entry reads the
+// token row once and writes it to the layout row of every slot in the entry's mask.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void dispatch_gather_kernel(const uint4 *__restrict__ x,
+                                                              const int32_t *__restrict__ rank_offsets,
+                                                              const int32_t *__restrict__ dedup_tok,
+                                                              const uint32_t *__restrict__ dedup_mask,
+                                                              const int32_t *__restrict__ inv_perm,
+                                                              const int32_t *__restrict__ offsets, int T, int k,
+                                                              int lrb, int lre, int e_lo, int P_cap, int row_chunks,
+                                                              uint4 *__restrict__ xs) {
+  const int u0 = rank_offsets[lrb];
+  const int u = u0 + blockIdx.x;
+  if (u >= rank_offsets[lre]) return;
+  const int t = dedup_tok[u];
+  uint32_t mask = dedup_mask[u];
+  if (t < 0 || t >= T) return;
+  const int base = offsets[e_lo];
+  for (int c = threadIdx.x; c < row_chunks; c += blockDim.x) {
+    const uint4 v = x[(size_t)t * row_chunks + c];
+    uint32_t m = mask;
+    while (m) {
+      const int j = __builtin_ctz(m);
+      m &= m - 1;
+      if (j >= k) break;
+      const int row = inv_perm[(size_t)t * k + j] - base;
+      if (row >= 0 && row < P_cap) xs[(size_t)row * row_chunks + c] = v;
+    }
+  }
+}
+
+// ---- pieces of the unfused comparison path ----
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4 *__restrict__ x,
+                                                          const int32_t *__restrict__ header,
+                                                          const int32_t *__restrict__ row_tok, int row_chunks,
+                                                          uint4 *__restrict__ xs) {
+  const int r = blockIdx.x;
+  if (r >= header[1]) return;
+  const int t = row_tok[r];
+  for (int c = threadIdx.x; c < row_chunks; c += blockDim.x)
+    xs[(size_t)r * row_chunks + c] = x[(size_t)t * row_chunks + c];
+}
+
+__global__ void fill_zero_kernel(float4 *__restrict__ p, size_t n4) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n4; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+__global__ __launch_bounds__(256) void scatter_add_kernel(const float *__restrict__ rows,
+                                                          const int32_t *__restrict__ header,
+                                                          const int32_t *__restrict__ row_tok, int d,
+                                                          float *__restrict__ y32) {
+  const int r = blockIdx.x;
+  if (r >= header[1]) return;
+  const int t = row_tok[r];
+  for (int c = threadIdx.x; c < d; c += blockDim.x) atomicAdd(&y32[(size_t)t * d + c], rows[(size_t)r * d + c]);
+}
+
+template <typename OutT>
+__global__ __launch_bounds__(256) void cast_rows_kernel(const float *__restrict__ y32, OutT *__restrict__ y,
+                                                        size_t n8) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+    float v[8];
+    const float4 lo = *reinterpret_cast<const float4 *>(y32 + i * 8);
+    const float4 hi = *reinterpret_cast<const float4 *>(y32 + i * 8 + 4);
+    v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    store8<OutT>(y + i * 8, v);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Host-side launch helpers
+// ------------------------------------------------------------------------------------------------
+struct Ws {
+  int32_t *header, *tile_e, *tile_m0, *tile_rows, *row_tok;
+  float *row_w;
+  void *h;
+  float *o;
+};
+
+static Ws carve(void *workspace, const FwdLayout &L) {
+  unsigned char *b = static_cast<unsigned char *>(workspace);
+  Ws w;
+  w.header = reinterpret_cast<int32_t *>(b + L.header);
+  w.tile_e = reinterpret_cast<int32_t *>(b + L.tile_e);
+  w.tile_m0 = reinterpret_cast<int32_t *>(b + L.tile_m0);
+  w.tile_rows = reinterpret_cast<int32_t *>(b + L.tile_rows);
+  w.row_tok = reinterpret_cast<int32_t *>(b + L.row_tok);
+  w.row_w = reinterpret_cast<float *>(b + L.row_w);
+  w.h = b + L.h;
+  w.o = reinterpret_cast<float *>(b + L.o);
+  return w;
+}
+
+static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch *tb, const float *topk_w,
+                       const Ws &w, hipStream_t st) {
+  const int blocks = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (dv.P_cap + 255) / 256));
+  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), 0, st, tb->offsets, tb->perm, topk_w, s->T, s->k,
+                     dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles, w.header, w.tile_e, w.tile_m0,
+                     w.tile_rows, w.row_tok, w.row_w);
+  return launch_status();
+}
+
+// GEMM-1 (gated) then GEMM-2 on the rows described by the tile table.  a1 / a1_map select the A operand of
+// GEMM-1: the token matrix with the row -> token map (fused gather) or a materialised copy (map == nullptr).
+static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, const int32_t *a1_map, int a1_ld,
+                        const void *packed_gu, const void *packed_down, const Ws &w, hipStream_t st,
+                        void *const *events = nullptr) {
+  auto mark = [&](int i) {
+    if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
+  };
+  GemmArgs g1{};
+  g1.A = a1; g1.row_map = a1_map; g1.Bp = packed_gu; g1.out = w.h; g1.row_w = nullptr;
+  g1.header = w.header; g1.tile_e = w.tile_e; g1.tile_m0 = w.tile_m0; g1.tile_rows = w.tile_rows;
+  g1.K = s->d; g1.N = s->f; g1.lda = a1_ld; g1.ldo = s->f;
+  GemmArgs g2 = g1;
+  g2.A = w.h; g2.row_map = nullptr; g2.Bp = packed_down; g2.out = w.o; g2.row_w = w.row_w;
+  g2.K = s->f; g2.N = s->d; g2.lda = s->f; g2.ldo = s->d;
+  if (s->dtype == MOE_BF16) {
+    g1.n_ntiles = ceil_div(s->f, kBN / 2); g1.n_ktiles = ceil_div(s->d, kBK);
+    g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kBK);
+    hipLaunchKernelGGL(gemm_bf16_kernel<true>, dim3(g1.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g1);
+    int rc = launch_status();
+    mark(2);
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL(gemm_bf16_kernel<false>, dim3(g2.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g2);
+    mark(3);
+    return launch_status();
+  }
+  g1.n_ntiles = ceil_div(s->f, kFBN); g1.n_ktiles = dv.E_loc;
+  g2.n_ntiles = ceil_div(s->d, kFBN); g2.n_ktiles = dv.E_loc;
+  hipLaunchKernelGGL(gemm_f32_kernel<true>, dim3(g1.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g1);
+  int rc = launch_status();
+  mark(2);
+  if (rc != MOE_OK) return rc;
+  hipLaunchKernelGGL(gemm_f32_kernel<false>, dim3(g2.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g2);
+  mark(3);
+  return launch_status();
+}
+
+static int launch_combine(const moe_shape *s, const Derived &dv, const float *rows, const int32_t *topk_idx,
+                          const moe_dispatch *tb, void *y, hipStream_t st) {
+  if (s->dtype == MOE_BF16)
+    hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(s->T), dim3(256), 0, st, rows, topk_idx, tb->inv_perm,
+                       tb->offsets, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, static_cast<bf16_t *>(y));
+  else
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(s->T), dim3(256), 0, st, rows, topk_idx, tb->inv_perm,
+                       tb->offsets, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, static_cast<float *>(y));
+  return launch_status();
+}
+
+static bool tables_ok(const moe_dispatch *t) {
+  return t && t->counts && t->offsets && t->perm && t->inv_perm && t->rank_counts && t->rank_offsets &&
+         t->dedup_tok && t->dedup_mask && t->pair_to_dedup;
+}
+
+}  // namespace moe355
+
+using namespace moe355;
+
+extern "C" int moe_pack_weights(const moe_shape *shape, const void *W_gate, const void *W_up, const void *W_down,
+                                void *packed_gate_up, void *packed_down, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!W_gate || !W_up || !W_down || !packed_gate_up || !packed_down) return MOE_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  const int d = shape->d, f = shape->f;
+  if (shape->dtype == MOE_F32) {
+    const size_t one = (size_t)dv.E_loc * d * f;
+    float *gu = static_cast<float *>(packed_gate_up);
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(1024), dim3(256), 0, st, static_cast<const float *>(W_gate), gu, one);
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(1024), dim3(256), 0, st, static_cast<const float *>(W_up), gu + one, one);
+    hipLaunchKernelGGL(copy_f32_kernel, dim3(1024), dim3(256), 0, st, static_cast<const float *>(W_down),
+                       static_cast<float *>(packed_down), one);
+    return launch_status();
+  }
+  const int nt1 = ceil_div(f, kBN / 2), kt1 = ceil_div(d, kBK);
+  const int nt2 = ceil_div(d, kBN), kt2 = ceil_div(f, kBK);
+  if (nt1 > 65535 || nt2 > 65535 || dv.E_loc > 65535) return MOE_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(pack_bf16_kernel<true>, dim3(kt1, nt1, dv.E_loc), dim3(256), 0, st,
+                     static_cast<const bf16_t *>(W_gate), static_cast<const bf16_t *>(W_up),
+                     static_cast<bf16_t *>(packed_gate_up), d, f, nt1, kt1);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  hipLaunchKernelGGL(pack_bf16_kernel<false>, dim3(kt2, nt2, dv.E_loc), dim3(256), 0, st,
+                     static_cast<const bf16_t *>(W_down), static_cast<const bf16_t *>(nullptr),
+                     static_cast<bf16_t *>(packed_down), f, d, nt2, kt2);
+  return launch_status();
+}
+
+static int forward_common(const moe_shape *shape, const void *x, const int32_t *topk_idx, const float *topk_w,
+                          const moe_dispatch *tables, const void *packed_gate_up, const void *packed_down, void *y,
+                          void *workspace, size_t workspace_bytes, void *stream, bool fused,
+                          void *const *events = nullptr) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!x || !topk_idx || !topk_w || !packed_gate_up || !packed_down || !y || !tables_ok(tables))
+    return MOE_ERR_INVALID_ARG;
+  const size_t need = fused ? moe_forward_workspace_bytes(shape) : moe_unfused_workspace_bytes(shape);
+  if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MOE_ERR_INVALID_ARG;
+  if (dv.max_mtiles > 65535) return MOE_ERR_UNSUPPORTED;
+  if (shape->T == 0) return MOE_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const FwdLayout L = forward_layout(shape, dv);
+  const Ws w = carve(workspace, L);
+  auto mark = [&](int i) {
+    if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
+  };
+  mark(0);
+  if ((rc = launch_prep(shape, dv, tables, topk_w, w, st)) != MOE_OK) return rc;
+  mark(1);
+  if (fused) {
+    if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, st, events)) != MOE_OK)
+      return rc;
+    rc = launch_combine(shape, dv, w.o, topk_idx, tables, y, st);
+    mark(4);
+    return rc;
+  }
+  // unfused: gather copy -> GEMMs on the copy -> zero -> atomic scatter-add -> cast
+  unsigned char *b = static_cast<unsigned char *>(workspace);
+  const size_t rows = (size_t)(dv.P_cap > 0 ? dv.P_cap : 1);
+  void *xs = b + L.total;
+  float *y32 = reinterpret_cast<float *>(b + L.total + align_up(rows * (size_t)shape->d * dv.elt, 256));
+  const int row_chunks = shape->d * dv.elt / 16;
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, static_cast<const uint4 *>(x),
+                     w.header, w.row_tok, row_chunks, static_cast<uint4 *>(xs));
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  if ((rc = launch_gemms(shape, dv, xs, nullptr, shape->d, packed_gate_up, packed_down, w, st)) != MOE_OK) return rc;
+  const size_t n = (size_t)shape->T * shape->d;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<float4 *>(y32), n / 4);
+  hipLaunchKernelGGL(scatter_add_kernel, dim3((unsigned)rows), dim3(256), 0, st, w.o, w.header, w.row_tok, shape->d,
+                     y32);
+  if (shape->dtype == MOE_BF16)
+    hipLaunchKernelGGL(cast_rows_kernel<bf16_t>, dim3(2048), dim3(256), 0, st, y32, static_cast<bf16_t *>(y), n / 8);
+  else
+    hipLaunchKernelGGL(cast_rows_kernel<float>, dim3(2048), dim3(256), 0, st, y32, static_cast<float *>(y), n / 8);
+  return launch_status();
+}
+
+extern "C" int moe_fused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx, const float *topk_w,
+                                 const moe_dispatch *tables, const void *packed_gate_up, const void *packed_down,
+                                 void *y, void *workspace, size_t workspace_bytes, void *stream) {
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true);
+}
+
+extern "C" int moe_fused_forward_timed(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                       const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                       const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                       void *stream, void *const *events) {
+  if (!events) return MOE_ERR_INVALID_ARG;
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, events);
+}
+
+extern "C" int moe_unfused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                   const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                   const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                   void *stream) {
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, false);
+}
+
+extern "C" int moe_dispatch_gather(const moe_shape *shape, const void *x, const moe_dispatch *tables, void *xs,
+                                   void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!x || !xs || !tables_ok(tables)) return MOE_ERR_INVALID_ARG;
+  if (shape->T == 0) return MOE_OK;
+  const int nlr = shape->local_rank_end - shape->local_rank_begin;
+  const int64_t max_entries = (int64_t)shape->T * (shape->k < nlr ? shape->k : nlr);
+  hipLaunchKernelGGL(dispatch_gather_kernel, dim3((unsigned)max_entries), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const uint4 *>(x), tables->rank_offsets, tables->dedup_tok, tables->dedup_mask,
+                     tables->inv_perm, tables->offsets, shape->T, shape->k, shape->local_rank_begin,
+                     shape->local_rank_end, dv.e_lo, (int)dv.P_cap, shape->d * dv.elt / 16, static_cast<uint4 *>(xs));
+  return launch_status();
+}
+
+extern "C" int moe_combine_reduce(const moe_shape *shape, const float *rows, const int32_t *topk_idx,
+                                  const moe_dispatch *tables, void *y, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!rows || !topk_idx || !y || !tables_ok(tables)) return MOE_ERR_INVALID_ARG;
+  if (shape->T == 0) return MOE_OK;
+  return launch_combine(shape, dv, rows, topk_idx, tables, y, (hipStream_t)stream);
+}

@@ -1,0 +1,78 @@
+"""Device-buffer bookkeeping around the C ABI: allocates the caller-owned arrays once and forwards every step
+to the library.  No arithmetic happens here."""
+from __future__ import annotations
+
+import numpy as np
+
+from . import binding as B
+
+
+def to_device(a: np.ndarray, device="cuda"):
+    """Host array -> device tensor.  uint16 arrays are bf16 bit patterns and become torch.bfloat16."""
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def from_device_bf16_bits(t) -> np.ndarray:
+    import torch
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class MoELayer:
+    """All device state of one layer: routing outputs, dispatch tables, packed weights, workspaces, y."""
+
+    def __init__(self, cfg, device="cuda", unfused: bool = False):
+        import torch
+        self.cfg = cfg
+        self.device = device
+        self.shape = B.shape_of(cfg)
+        s = self.shape
+        self.elt_dtype = torch.bfloat16 if cfg.dtype == B.MOE_BF16 else torch.float32
+        n = max(1, s.T * s.k)
+        self.topk_idx = torch.empty(n, dtype=torch.int32, device=device)
+        self.topk_w = torch.empty(n, dtype=torch.float32, device=device)
+        self.tables = B.DispatchTables(s, device)
+        self.dispatch_ws = torch.empty(max(1, B.moe_dispatch_workspace_bytes(s)), dtype=torch.uint8, device=device)
+        nbytes = B.moe_unfused_workspace_bytes(s) if unfused else B.moe_forward_workspace_bytes(s)
+        self.forward_ws = torch.empty(max(1, nbytes), dtype=torch.uint8, device=device)
+        self.y = torch.empty((max(1, s.T), s.d), dtype=self.elt_dtype, device=device)
+        self.packed_gate_up = None
+        self.packed_down = None
+
+    def load_weights(self, W_gate: np.ndarray, W_up: np.ndarray, W_down: np.ndarray) -> None:
+        import torch
+        s = self.shape
+        self.packed_gate_up = torch.empty(B.moe_packed_weight_bytes(s, 0), dtype=torch.uint8, device=self.device)
+        self.packed_down = torch.empty(B.moe_packed_weight_bytes(s, 1), dtype=torch.uint8, device=self.device)
+        g, u, d = (to_device(a, self.device) for a in (W_gate, W_up, W_down))
+        B.moe_pack_weights(s, g, u, d, self.packed_gate_up, self.packed_down)
+        torch.cuda.synchronize()
+        del g, u, d
+
+    def route(self, logits) -> None:
+        B.moe_route_topk(self.shape, logits, self.topk_idx, self.topk_w)
+
+    def build_dispatch(self) -> None:
+        B.moe_build_dispatch(self.shape, self.topk_idx, self.tables, self.dispatch_ws)
+
+    def forward(self, x) -> None:
+        B.moe_fused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
+                            self.packed_down, self.y, self.forward_ws)
+
+    def forward_unfused(self, x) -> None:
+        B.moe_unfused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
+                              self.packed_down, self.y, self.forward_ws)
+
+    def step(self, logits, x) -> None:
+        """One pass of the whole hot path."""
+        self.route(logits)
+        self.build_dispatch()
+        self.forward(x)
+
+    def y_host(self) -> np.ndarray:
+        """y as float64 on the host (bf16 values widened exactly)."""
+        import torch
+        return self.y[: self.shape.T].to(torch.float64).cpu().numpy()

@@ -1,0 +1,101 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol and rejects bad arguments
+before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_05607_amd import binding as B
+from paper_2605_05607_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "moe355.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"MOE355_API\s+[\w\s\*]+?\b(moe_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert {"moe_route_topk", "moe_build_dispatch", "moe_fused_forward", "moe_pack_weights"} <= set(names)
+    assert len(names) >= 12
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert B.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert B.status_string(code)
+
+
+def good_shape(**kw):
+    base = dict(T=64, d=64, f=128, E=8, k=2, R=4, local_rank_begin=0, local_rank_end=4, dtype=B.MOE_BF16)
+    base.update(kw)
+    return B.make_shape(**base)
+
+
+@pytest.mark.parametrize("kw", [dict(E=10, R=4), dict(k=9), dict(k=0), dict(k=33, E=64), dict(T=-1), dict(d=60),
+                                dict(f=100), dict(local_rank_begin=2, local_rank_end=2), dict(local_rank_end=5),
+                                dict(local_rank_begin=-1), dict(R=0)])
+def test_invalid_shapes_are_rejected_everywhere(kw):
+    s = good_shape(**kw)
+    lib = B.lib()
+    fake = 4096  # never dereferenced: validation fails first
+    assert lib.moe_route_topk(C.byref(s), fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert B.moe_dispatch_workspace_bytes(s) == 0 and B.moe_forward_workspace_bytes(s) == 0
+    assert B.moe_packed_weight_bytes(s, 0) == 0
+    assert lib.moe_pack_weights(C.byref(s), fake, fake, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+
+
+def test_unsupported_dtype_and_extent():
+    lib = B.lib()
+    assert lib.moe_route_topk(C.byref(good_shape(dtype=7)), 4096, 4096, 4096, None) == B.MOE_ERR_UNSUPPORTED
+    assert lib.moe_route_topk(C.byref(good_shape(E=8192, R=1, local_rank_end=1)), 4096, 4096, 4096, None) \
+        == B.MOE_ERR_UNSUPPORTED
+
+
+def test_null_pointers_and_small_workspace():
+    lib = B.lib()
+    s = good_shape()
+    fake = 4096
+    assert lib.moe_route_topk(None, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_topk(C.byref(s), None, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    tb = B.moe_dispatch(*([fake] * 9))
+    assert lib.moe_build_dispatch(C.byref(s), None, C.byref(tb), fake, 1 << 20, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_build_dispatch(C.byref(s), fake, C.byref(tb), fake, 16, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_build_dispatch(C.byref(s), fake, C.byref(tb), None, 1 << 20, None) == B.MOE_ERR_WORKSPACE
+    holes = B.moe_dispatch(*([fake] * 8 + [None]))
+    assert lib.moe_build_dispatch(C.byref(s), fake, C.byref(holes), fake, 1 << 20, None) == B.MOE_ERR_INVALID_ARG
+    need = B.moe_forward_workspace_bytes(s)
+    args = (C.byref(s), fake, fake, fake, C.byref(tb), fake, fake, fake)
+    assert lib.moe_fused_forward(*args, 4096, need - 1, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_fused_forward(*args, 4096 + 8, need, None) == B.MOE_ERR_INVALID_ARG  # misaligned workspace
+    assert lib.moe_fused_forward(C.byref(s), None, fake, fake, C.byref(tb), fake, fake, fake, 4096, need, None) \
+        == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_unfused_forward(*args, 4096, need, None) == B.MOE_ERR_WORKSPACE  # needs the larger workspace
+    assert lib.moe_dispatch_gather(C.byref(s), fake, C.byref(tb), None, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_combine_reduce(C.byref(s), None, fake, C.byref(tb), fake, None) == B.MOE_ERR_INVALID_ARG
+
+
+def test_sizes_for_the_named_configs():
+    for name, cfg in wl.CONFIGS.items():
+        s = B.shape_of(cfg)
+        assert B.moe_dispatch_workspace_bytes(s) >= 64 * (cfg.E + cfg.R) * 4
+        elt = 2 if cfg.dtype == wl.BF16 else 4
+        raw = cfg.E_loc * cfg.d * cfg.f * elt
+        assert B.moe_packed_weight_bytes(s, 0) >= 2 * raw and B.moe_packed_weight_bytes(s, 1) >= raw
+        assert B.moe_packed_weight_bytes(s, 0) < 2.2 * raw + (1 << 20)
+        rows = cfg.T * min(cfg.k, cfg.E_loc)
+        assert B.moe_forward_workspace_bytes(s) >= rows * (cfg.f * elt + cfg.d * 4)
+        assert B.moe_unfused_workspace_bytes(s) > B.moe_forward_workspace_bytes(s)
+
+
+def test_t_zero_is_a_noop_on_the_host():
+    s = good_shape(T=0)
+    lib = B.lib()
+    assert lib.moe_route_topk(C.byref(s), 4096, 4096, 4096, None) == B.MOE_OK
