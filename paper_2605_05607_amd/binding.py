@@ -44,6 +44,9 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        # torch ships its own HIP runtime (same SONAME as the system one).  Import it first so that this library
+        # binds to the runtime that owns torch's streams and allocations instead of loading a second copy.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, sz, i32 = C.c_void_p, C.c_size_t, C.c_int
         sp, dp = C.POINTER(moe_shape), C.POINTER(moe_dispatch)

@@ -37,6 +37,10 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Shape checks common to all entry points.  Returns MOE_OK or the error to hand back.
 int check_shape(const moe_shape *s, Derived *out);
 
+// hipGetLastError() reports (and clears) the last error of ANY earlier runtime call on this thread, including
+// the caller's own; every entry point therefore drops a stale error before its first launch and reads the
+// status after each launch.
+inline void begin_launches() { (void)hipGetLastError(); }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
 
 // ---- layout of the forward workspace (offsets in bytes, 256-byte aligned) ----

@@ -220,6 +220,7 @@ extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_id
   int32_t *chunk_cnt = static_cast<int32_t *>(workspace);
   int32_t *chunk_rcnt = chunk_cnt + (size_t)kMaxChunks * E;
   hipStream_t st = (hipStream_t)stream;
+  begin_launches();
   const size_t sm_wave = (size_t)(E + R) * sizeof(int);
   if (nch > 0) {
     hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nch), dim3(kWave), sm_wave, st, topk_idx, T, E, k, R, tpc,

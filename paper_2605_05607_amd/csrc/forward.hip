@@ -559,6 +559,7 @@ extern "C" int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
   if (rc != MOE_OK) return rc;
   if (!W_gate || !W_up || !W_down || !packed_gate_up || !packed_down) return MOE_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
+  begin_launches();
   const int d = shape->d, f = shape->f;
   if (shape->dtype == MOE_F32) {
     const size_t one = (size_t)dv.E_loc * d * f;
@@ -597,6 +598,7 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   if (dv.max_mtiles > 65535) return MOE_ERR_UNSUPPORTED;
   if (shape->T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
+  begin_launches();
   const FwdLayout L = forward_layout(shape, dv);
   const Ws w = carve(workspace, L);
   auto mark = [&](int i) {
@@ -666,6 +668,7 @@ extern "C" int moe_dispatch_gather(const moe_shape *shape, const void *x, const 
   if (shape->T == 0) return MOE_OK;
   const int nlr = shape->local_rank_end - shape->local_rank_begin;
   const int64_t max_entries = (int64_t)shape->T * (shape->k < nlr ? shape->k : nlr);
+  begin_launches();
   hipLaunchKernelGGL(dispatch_gather_kernel, dim3((unsigned)max_entries), dim3(256), 0, (hipStream_t)stream,
                      static_cast<const uint4 *>(x), tables->rank_offsets, tables->dedup_tok, tables->dedup_mask,
                      tables->inv_perm, tables->offsets, shape->T, shape->k, shape->local_rank_begin,
@@ -680,5 +683,6 @@ extern "C" int moe_combine_reduce(const moe_shape *shape, const float *rows, con
   if (rc != MOE_OK) return rc;
   if (!rows || !topk_idx || !y || !tables_ok(tables)) return MOE_ERR_INVALID_ARG;
   if (shape->T == 0) return MOE_OK;
+  begin_launches();
   return launch_combine(shape, dv, rows, topk_idx, tables, y, (hipStream_t)stream);
 }

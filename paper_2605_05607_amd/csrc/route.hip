@@ -79,6 +79,7 @@ extern "C" int moe_route_topk(const moe_shape *shape, const float *logits, int32
   if (rc != MOE_OK) return rc;
   if (!logits || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
   if (shape->T == 0) return MOE_OK;
+  begin_launches();
   const size_t per_wave = (size_t)(shape->E + kMaxTopK) * sizeof(uint32_t);
   int waves = kRouteWaves;
   while (waves > 1 && waves * per_wave > 48 * 1024) waves >>= 1;
