@@ -11,6 +11,7 @@ namespace moe355 {
 typedef __bf16 bf16_t;
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS stage image of B (32 KiB)
 
@@ -153,30 +154,55 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   const int wm = wave >> 1, wn = wave & 1;
 
   // ---- global -> register staging assignment ----
+  // (scalar variables instead of small arrays: the arrays were left in scratch memory by the compiler)
   const int a_chunk = tid & 7;  // 16-byte chunk (8 reduction indices) inside the 64-wide k slab
-  const bf16_t *a_src[4];
-  int a_dst[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 3) + 32 * i;
-    const int rc = r < rows ? r : rows - 1;  // padding rows repeat the last valid row (results discarded)
-    const int src_row = g.row_map ? g.row_map[m0 + rc] : m0 + rc;
-    a_src[i] = static_cast<const bf16_t *>(g.A) + (size_t)src_row * g.lda + a_chunk * 8;
-    a_dst[i] = (r * 8 + (a_chunk ^ (r & 7))) * 16;
-  }
+  const bf16_t *a_base = static_cast<const bf16_t *>(g.A) + a_chunk * 8;
+#define MOE355_A_ROW(i)                                                                     \
+  const int a_r##i = (tid >> 3) + 32 * i;                                                   \
+  const int a_rc##i = a_r##i < rows ? a_r##i : rows - 1; /* padding rows repeat a valid row */ \
+  const bf16_t *a_src##i =                                                                  \
+      a_base + (size_t)(g.row_map ? g.row_map[m0 + a_rc##i] : m0 + a_rc##i) * g.lda;         \
+  const int a_dst##i = (a_r##i * 8 + (a_chunk ^ (a_r##i & 7))) * 16;
+  MOE355_A_ROW(0) MOE355_A_ROW(1) MOE355_A_ROW(2) MOE355_A_ROW(3)
+#undef MOE355_A_ROW
   const unsigned char *b_src =
       static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
 
-  uint4 ra[4], rb[8];
-  auto load_stage = [&](int kt) {
-    const bool k_ok = kt * kBK + a_chunk * 8 < g.K;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      ra[i] = k_ok ? *reinterpret_cast<const uint4 *>(a_src[i] + kt * kBK) : make_uint4(0, 0, 0, 0);
-    const unsigned char *bt = b_src + (size_t)kt * kTileBytes;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) rb[i] = *reinterpret_cast<const uint4 *>(bt + i * 4096);
-  };
+  u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3, rb4, rb5, rb6, rb7;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#define MOE355_LOAD_STAGE(KT)                                                   \
+  do {                                                                          \
+    const int kt_ = (KT);                                                       \
+    const bool k_ok_ = kt_ * kBK + a_chunk * 8 < g.K;                           \
+    ra0 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src0 + kt_ * kBK) : zero4; \
+    ra1 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src1 + kt_ * kBK) : zero4; \
+    ra2 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src2 + kt_ * kBK) : zero4; \
+    ra3 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src3 + kt_ * kBK) : zero4; \
+    const unsigned char *bt_ = b_src + (size_t)kt_ * kTileBytes;                \
+    rb0 = *reinterpret_cast<const u32x4 *>(bt_ + 0 * 4096);                     \
+    rb1 = *reinterpret_cast<const u32x4 *>(bt_ + 1 * 4096);                     \
+    rb2 = *reinterpret_cast<const u32x4 *>(bt_ + 2 * 4096);                     \
+    rb3 = *reinterpret_cast<const u32x4 *>(bt_ + 3 * 4096);                     \
+    rb4 = *reinterpret_cast<const u32x4 *>(bt_ + 4 * 4096);                     \
+    rb5 = *reinterpret_cast<const u32x4 *>(bt_ + 5 * 4096);                     \
+    rb6 = *reinterpret_cast<const u32x4 *>(bt_ + 6 * 4096);                     \
+    rb7 = *reinterpret_cast<const u32x4 *>(bt_ + 7 * 4096);                     \
+  } while (0)
+#define MOE355_STORE_STAGE()                                          \
+  do {                                                                \
+    *reinterpret_cast<u32x4 *>(sA + a_dst0) = ra0;                    \
+    *reinterpret_cast<u32x4 *>(sA + a_dst1) = ra1;                    \
+    *reinterpret_cast<u32x4 *>(sA + a_dst2) = ra2;                    \
+    *reinterpret_cast<u32x4 *>(sA + a_dst3) = ra3;                    \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 0 * 4096) = rb0;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 1 * 4096) = rb1;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 2 * 4096) = rb2;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 3 * 4096) = rb3;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 4 * 4096) = rb4;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 5 * 4096) = rb5;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 6 * 4096) = rb6;       \
+    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 7 * 4096) = rb7;       \
+  } while (0)
 
   f32x16 acc[2][4];
 #pragma unroll
@@ -195,14 +221,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
   const int a_row_off = (wm * 64 + l31) * 128;   // bytes; + mi * 32 rows
   const int b_row_off = (wn * 128 + l31) * 128;  // bytes; + ni * 32 rows
 
-  load_stage(0);
+  MOE355_LOAD_STAGE(0);
   for (int kt = 0; kt < g.n_ktiles; ++kt) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(sA + a_dst[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) *reinterpret_cast<uint4 *>(sB + tid * 16 + i * 4096) = rb[i];
+    MOE355_STORE_STAGE();
     __syncthreads();
-    if (kt + 1 < g.n_ktiles) load_stage(kt + 1);
+    if (kt + 1 < g.n_ktiles) MOE355_LOAD_STAGE(kt + 1);
     if (act0) {
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
