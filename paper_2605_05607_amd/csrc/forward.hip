@@ -16,40 +16,32 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS stage image of B (32 KiB)
 
 // ------------------------------------------------------------------------------------------------
-// Weight packing (one-off).  Output tile (le, nt, kt) holds kBN output columns x kBK reduction indices,
-// stored column-major-in-k: row n_l of the tile is the 128-byte run of its 64 k values, cut into eight
-// 16-byte chunks; chunk c of row n_l is stored at slot c ^ (n_l & 7) so that the MFMA operand reads of
-// eight neighbouring rows fall on different LDS banks.  Zero-padded outside the matrix.
-// GATED tiles interleave gate and up columns so that one wave owns both halves of the same h columns:
-// tile rows [0,128) belong to the wave column 0, [128,256) to wave column 1; inside each, rows [0,64) are
-// gate columns and [64,128) the matching up columns.
+// Weight packing (one-off).  Output tile (le, nt, kt) covers kBN output columns x kBK reduction indices and is
+// stored as the exact register images the MFMA B operand needs, so the GEMM kernel loads B straight from
+// global memory into registers with fully coalesced 16-byte loads and never stages it in LDS:
+//   tile = 4 waves x 4 k-substeps x 2 fragments x (64 lanes x 16 bytes);
+//   fragment (w, kk, j), lane l holds column n_l = w*64 + j*32 + (l & 31) at the 8 reduction indices
+//   kt*64 + kk*16 + (l >> 5)*8 + 0..7.
+// GATED tiles pair gate and up columns inside one wave: fragment j = 0 holds gate columns
+// nt*128 + w*32 + 0..31 and j = 1 the up columns of the same h columns.  Zero-padded outside the matrix.
 // ------------------------------------------------------------------------------------------------
 template <bool GATED>
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1,
                                                         bf16_t *__restrict__ out, int K, int N, int n_ntiles,
                                                         int n_ktiles) {
-  // grid: x = kt, y = nt, z = le;   256 threads: thread = tile row n_l, loops over the 8 chunks
   const int kt = blockIdx.x, nt = blockIdx.y, le = blockIdx.z;
-  const int n_l = threadIdx.x;
-  const bf16_t *W;
-  int col;
-  if (GATED) {
-    const int wn = n_l >> 7, b = (n_l & 127) >> 5, i = n_l & 31;
-    W = b < 2 ? W0 : W1;
-    col = nt * (kBN / 2) + wn * 64 + (b & 1) * 32 + i;
-  } else {
-    W = W0;
-    col = nt * kBN + n_l;
-  }
   const size_t wbase = (size_t)le * K * N;
   bf16_t *tile = out + ((size_t)(le * n_ntiles + nt) * n_ktiles + kt) * (kBN * kBK);
-  for (int c = 0; c < 8; ++c) {
+  for (int c = threadIdx.x; c < kBN * kBK / 8; c += blockDim.x) {
+    const int frag = c >> 6, l = c & 63;
+    const int w = frag >> 3, kk = (frag >> 1) & 3, j = frag & 1;
+    const bf16_t *W = (GATED && j == 1) ? W1 : W0;
+    const int col = GATED ? nt * (kBN / 2) + w * 32 + (l & 31) : nt * kBN + w * 64 + j * 32 + (l & 31);
+    const int k0 = kt * kBK + kk * 16 + (l >> 5) * 8;
     bf16x8 v;
-    for (int q = 0; q < 8; ++q) {
-      const int kk = kt * kBK + c * 8 + q;
-      v[q] = (col < N && kk < K) ? W[wbase + (size_t)kk * N + col] : (bf16_t)0.0f;
-    }
-    *reinterpret_cast<bf16x8 *>(tile + (size_t)n_l * kBK + ((c ^ (n_l & 7)) << 3)) = v;
+    for (int q = 0; q < 8; ++q)
+      v[q] = (col < N && k0 + q < K) ? W[wbase + (size_t)(k0 + q) * N + col] : (bf16_t)0.0f;
+    *reinterpret_cast<bf16x8 *>(tile + (size_t)c * 8) = v;
   }
 }
 
@@ -114,12 +106,15 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
 // ------------------------------------------------------------------------------------------------
 // Grouped bf16 GEMM on the matrix cores.  C[rows of one expert tile, kBN/2 or kBN columns] = A * W_e.
 //   A rows   : row_map == nullptr -> A[m0 + r, :]; else A[row_map[m0 + r], :] (token gather of Dispatch).
-//   B tiles  : packed images streamed linearly from HBM.
+//              128 x 64 slabs go global -> registers -> LDS (double buffered, 16-byte chunks XOR-swizzled by
+//              row so that the operand reads of eight neighbouring rows hit different banks).
+//   B        : packed register images, global -> registers, one k-step ahead of their use.
 //   GATED    : epilogue h = silu(g) * u, written as bf16   (GEMM-1)
 //   !GATED   : epilogue o = acc * row_w[row], written fp32 (GEMM-2, gate weight of Sec. III-C)
-// 256 threads = 4 waves in a 2 x 2 arrangement, each wave owns 64 x 128 of the 128 x 256 tile as
-// 2 x 4 MFMA 32x32x16 accumulators.  One LDS stage (48 KiB) with the next stage prefetched into registers;
-// two workgroups per CU overlap each other's load and MFMA phases.
+// 256 threads = 4 waves side by side along N; every wave owns all 128 rows x 64 columns as 4 x 2 MFMA
+// 32x32x16 accumulators, so no B data is shared between waves.  NBLK = number of 32-row blocks that hold
+// valid rows (the others are skipped: small experts are weight-streaming bound and need no padding math).
+// One barrier per k-step; two workgroups per CU overlap each other's stalls.
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
   const void *A;
@@ -135,146 +130,166 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+constexpr int kAStageBytes = kBM * kBK * 2;  // 16 KiB
+
+template <bool GATED, int NBLK>
+__device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *sA, int nt, int le, int m0,
+                                               int rows) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = tid >> 6;
+
+  // ---- A: global -> register staging assignment (scalars, not arrays, so nothing lands in scratch) ----
+  const int a_chunk = tid & 7;  // 16-byte chunk (8 reduction indices) inside the 64-wide k slab
+  const bf16_t *a_base = static_cast<const bf16_t *>(g.A) + a_chunk * 8;
+#define MOE355_A_ROW(i)                                                                        \
+  const int a_r##i = (tid >> 3) + 32 * i;                                                      \
+  const int a_rc##i = a_r##i < rows ? a_r##i : rows - 1; /* padding rows repeat a valid row */ \
+  const bf16_t *a_src##i =                                                                     \
+      a_base + (size_t)(g.row_map ? g.row_map[m0 + a_rc##i] : m0 + a_rc##i) * g.lda;            \
+  const int a_dst##i = (a_r##i * 8 + (a_chunk ^ (a_r##i & 7))) * 16;
+  MOE355_A_ROW(0) MOE355_A_ROW(1) MOE355_A_ROW(2) MOE355_A_ROW(3)
+#undef MOE355_A_ROW
+  u32x4 ra0, ra1, ra2, ra3;
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+#define MOE355_LOAD_A(KT)                                                                        \
+  do {                                                                                           \
+    const int kt_ = (KT);                                                                        \
+    const bool k_ok_ = kt_ * kBK + a_chunk * 8 < g.K;                                            \
+    const int ko_ = k_ok_ ? kt_ * kBK : 0; /* branch-free: load a valid chunk, then select */    \
+    ra0 = *reinterpret_cast<const u32x4 *>(a_src0 + ko_);                                        \
+    if (NBLK > 1) ra1 = *reinterpret_cast<const u32x4 *>(a_src1 + ko_);                          \
+    if (NBLK > 2) ra2 = *reinterpret_cast<const u32x4 *>(a_src2 + ko_);                          \
+    if (NBLK > 3) ra3 = *reinterpret_cast<const u32x4 *>(a_src3 + ko_);                          \
+    if (!k_ok_) ra0 = ra1 = ra2 = ra3 = zero4;                                                   \
+  } while (0)
+#define MOE355_STORE_A(BUF)                                                     \
+  do {                                                                          \
+    unsigned char *s_ = sA + (BUF) * kAStageBytes;                              \
+    *reinterpret_cast<u32x4 *>(s_ + a_dst0) = ra0;                              \
+    if (NBLK > 1) *reinterpret_cast<u32x4 *>(s_ + a_dst1) = ra1;                \
+    if (NBLK > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst2) = ra2;                \
+    if (NBLK > 3) *reinterpret_cast<u32x4 *>(s_ + a_dst3) = ra3;                \
+  } while (0)
+
+  // ---- B: this wave's 8 fragments of a k-step are 8 KiB contiguous; lane l reads 16 bytes of each ----
+  const unsigned char *b_src = static_cast<const unsigned char *>(g.Bp) +
+                               ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + w * 8192 + lane * 16;
+  bf16x8 b00, b01, b10, b11, b20, b21, b30, b31;  // b<kk><j>
+#define MOE355_LOAD_B(KK, KT)                                                                        \
+  do {                                                                                               \
+    const unsigned char *p_ = b_src + (size_t)(KT) * kTileBytes + (KK) * 2048;                       \
+    b##KK##0 = *reinterpret_cast<const bf16x8 *>(p_);                                                \
+    b##KK##1 = *reinterpret_cast<const bf16x8 *>(p_ + 1024);                                         \
+  } while (0)
+
+  f32x16 acc[NBLK][2];
+#pragma unroll
+  for (int mi = 0; mi < NBLK; ++mi)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][j][r] = 0.f;
+
+  // ---- LDS -> MFMA A operand addressing: lane l reads row l & 31 of a 32-row block, k half l >> 5 ----
+  const int l31 = lane & 31, khalf = lane >> 5, sw = lane & 7;
+  const int a_row_off = l31 * 128;
+
+  const int KT = g.n_ktiles;
+  MOE355_LOAD_A(0);
+  MOE355_LOAD_B(0, 0); MOE355_LOAD_B(1, 0); MOE355_LOAD_B(2, 0); MOE355_LOAD_B(3, 0);
+  MOE355_STORE_A(0);
+  __syncthreads();
+  MOE355_LOAD_A(KT > 1 ? 1 : 0);
+
+#define MOE355_READ_A(DST, KK)                                                                         \
+  do {                                                                                                 \
+    const int slot_ = (((KK) * 2 + khalf) ^ sw) * 16;                                                  \
+    _Pragma("unroll") for (int mi = 0; mi < NBLK; ++mi) DST[mi] =                                      \
+        *reinterpret_cast<const bf16x8 *>(sCur + a_row_off + mi * 4096 + slot_);                       \
+  } while (0)
+  // one 16-wide k-substep: this substep's MFMAs, then refill its B fragments with those of the next k-step
+#define MOE355_KSTEP(KK)                                                                               \
+  do {                                                                                                 \
+    bf16x8 a_[NBLK];                                                                                   \
+    MOE355_READ_A(a_, KK);                                                                             \
+    _Pragma("unroll") for (int mi = 0; mi < NBLK; ++mi) {                                              \
+      acc[mi][0] = mfma_bf16(a_[mi], b##KK##0, acc[mi][0]);                                            \
+      acc[mi][1] = mfma_bf16(a_[mi], b##KK##1, acc[mi][1]);                                            \
+    }                                                                                                  \
+    MOE355_LOAD_B(KK, kt_next);                                                                        \
+  } while (0)
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const unsigned char *sCur = sA + (kt & 1) * kAStageBytes;
+    // the reloads past the last k-step repeat the last slab: in bounds, never used
+    const int kt_next = kt + 1 < KT ? kt + 1 : kt;
+    MOE355_KSTEP(0);
+    MOE355_KSTEP(1);
+    MOE355_KSTEP(2);
+    MOE355_KSTEP(3);
+    MOE355_STORE_A((kt & 1) ^ 1);  // slab kt+1 into the buffer that was read during k-step kt-1
+    // Instruction order asked of the scheduler for the block above: the A fragments of substep kk+1 are read
+    // from LDS while the MFMAs of substep kk run, and each substep's B refill is issued right behind its
+    // MFMAs so that it keeps a whole k-step of distance to its use.
+    // (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write)
+    __builtin_amdgcn_sched_group_barrier(0x100, NBLK, 0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, NBLK, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NBLK, 0);
+      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x200, NBLK, 0);
+    __syncthreads();
+    MOE355_LOAD_A(kt + 2 < KT ? kt + 2 : kt_next);
+  }
+#undef MOE355_READ_A
+#undef MOE355_KSTEP
+#undef MOE355_LOAD_B
+#undef MOE355_LOAD_A
+#undef MOE355_STORE_A
+
+  // ---- epilogue ----
+  // accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block
+#pragma unroll
+  for (int mi = 0; mi < NBLK; ++mi) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row_l = mi * 32 + (r >> 2) * 8 + khalf * 4 + (r & 3);
+      if (row_l >= rows) continue;
+      const size_t grow = (size_t)(m0 + row_l);
+      if (GATED) {
+        const int col = nt * (kBN / 2) + w * 32 + l31;
+        const float gv = acc[mi][0][r], uv = acc[mi][1][r];
+        if (col < g.N)
+          static_cast<bf16_t *>(g.out)[grow * g.ldo + col] = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
+      } else {
+        float *o = static_cast<float *>(g.out) + grow * g.ldo;
+        const float wgt = g.row_w[grow];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int col = nt * kBN + w * 64 + j * 32 + l31;
+          if (col < g.N) o[col] = acc[mi][j][r] * wgt;
+        }
+      }
+    }
+  }
+}
+
 template <bool GATED>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[(kBM + kBN) * kBK * 2];
-  unsigned char *sA = smem;
-  unsigned char *sB = smem + kBM * kBK * 2;
-
+  __shared__ __attribute__((aligned(16))) unsigned char sA[2 * kAStageBytes];
   const int mt = blockIdx.y;
   if (mt >= g.header[0]) return;
   const int nt = blockIdx.x;
   const int le = g.tile_e[mt];
   const int m0 = g.tile_m0[mt];
   const int rows = g.tile_rows[mt];
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-
-  // ---- global -> register staging assignment ----
-  // (scalar variables instead of small arrays: the arrays were left in scratch memory by the compiler)
-  const int a_chunk = tid & 7;  // 16-byte chunk (8 reduction indices) inside the 64-wide k slab
-  const bf16_t *a_base = static_cast<const bf16_t *>(g.A) + a_chunk * 8;
-#define MOE355_A_ROW(i)                                                                     \
-  const int a_r##i = (tid >> 3) + 32 * i;                                                   \
-  const int a_rc##i = a_r##i < rows ? a_r##i : rows - 1; /* padding rows repeat a valid row */ \
-  const bf16_t *a_src##i =                                                                  \
-      a_base + (size_t)(g.row_map ? g.row_map[m0 + a_rc##i] : m0 + a_rc##i) * g.lda;         \
-  const int a_dst##i = (a_r##i * 8 + (a_chunk ^ (a_r##i & 7))) * 16;
-  MOE355_A_ROW(0) MOE355_A_ROW(1) MOE355_A_ROW(2) MOE355_A_ROW(3)
-#undef MOE355_A_ROW
-  const unsigned char *b_src =
-      static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
-
-  u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3, rb4, rb5, rb6, rb7;
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
-#define MOE355_LOAD_STAGE(KT)                                                   \
-  do {                                                                          \
-    const int kt_ = (KT);                                                       \
-    const bool k_ok_ = kt_ * kBK + a_chunk * 8 < g.K;                           \
-    ra0 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src0 + kt_ * kBK) : zero4; \
-    ra1 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src1 + kt_ * kBK) : zero4; \
-    ra2 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src2 + kt_ * kBK) : zero4; \
-    ra3 = k_ok_ ? *reinterpret_cast<const u32x4 *>(a_src3 + kt_ * kBK) : zero4; \
-    const unsigned char *bt_ = b_src + (size_t)kt_ * kTileBytes;                \
-    rb0 = *reinterpret_cast<const u32x4 *>(bt_ + 0 * 4096);                     \
-    rb1 = *reinterpret_cast<const u32x4 *>(bt_ + 1 * 4096);                     \
-    rb2 = *reinterpret_cast<const u32x4 *>(bt_ + 2 * 4096);                     \
-    rb3 = *reinterpret_cast<const u32x4 *>(bt_ + 3 * 4096);                     \
-    rb4 = *reinterpret_cast<const u32x4 *>(bt_ + 4 * 4096);                     \
-    rb5 = *reinterpret_cast<const u32x4 *>(bt_ + 5 * 4096);                     \
-    rb6 = *reinterpret_cast<const u32x4 *>(bt_ + 6 * 4096);                     \
-    rb7 = *reinterpret_cast<const u32x4 *>(bt_ + 7 * 4096);                     \
-  } while (0)
-#define MOE355_STORE_STAGE()                                          \
-  do {                                                                \
-    *reinterpret_cast<u32x4 *>(sA + a_dst0) = ra0;                    \
-    *reinterpret_cast<u32x4 *>(sA + a_dst1) = ra1;                    \
-    *reinterpret_cast<u32x4 *>(sA + a_dst2) = ra2;                    \
-    *reinterpret_cast<u32x4 *>(sA + a_dst3) = ra3;                    \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 0 * 4096) = rb0;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 1 * 4096) = rb1;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 2 * 4096) = rb2;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 3 * 4096) = rb3;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 4 * 4096) = rb4;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 5 * 4096) = rb5;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 6 * 4096) = rb6;       \
-    *reinterpret_cast<u32x4 *>(sB + tid * 16 + 7 * 4096) = rb7;       \
-  } while (0)
-
-  f32x16 acc[2][4];
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-    for (int ni = 0; ni < 4; ++ni)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-  // 32-row blocks of this wave that contain at least one valid row
-  const bool act0 = wm * 64 < rows;
-  const bool act1 = wm * 64 + 32 < rows;
-
-  // ---- LDS -> MFMA operand addressing ----
-  const int l31 = lane & 31, khalf = lane >> 5, sw = lane & 7;
-  const int a_row_off = (wm * 64 + l31) * 128;   // bytes; + mi * 32 rows
-  const int b_row_off = (wn * 128 + l31) * 128;  // bytes; + ni * 32 rows
-
-  MOE355_LOAD_STAGE(0);
-  for (int kt = 0; kt < g.n_ktiles; ++kt) {
-    MOE355_STORE_STAGE();
-    __syncthreads();
-    if (kt + 1 < g.n_ktiles) MOE355_LOAD_STAGE(kt + 1);
-    if (act0) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int slot = ((kk * 2 + khalf) ^ sw) * 16;
-        bf16x8 b[4];
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) b[ni] = *reinterpret_cast<const bf16x8 *>(sB + b_row_off + ni * 4096 + slot);
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(sA + a_row_off + slot);
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) acc[0][ni] = mfma_bf16(a0, b[ni], acc[0][ni]);
-        if (act1) {
-          const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(sA + a_row_off + 4096 + slot);
-#pragma unroll
-          for (int ni = 0; ni < 4; ++ni) acc[1][ni] = mfma_bf16(a1, b[ni], acc[1][ni]);
-        }
-      }
-    }
-    __syncthreads();
-  }
-
-  // ---- epilogue ----
-  // accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block
-#pragma unroll
-  for (int mi = 0; mi < 2; ++mi) {
-    if (!(mi == 0 ? act0 : act1)) continue;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row_l = wm * 64 + mi * 32 + (r >> 2) * 8 + khalf * 4 + (r & 3);
-      if (row_l >= rows) continue;
-      const size_t grow = (size_t)(m0 + row_l);
-      if (GATED) {
-        bf16_t *h = static_cast<bf16_t *>(g.out) + grow * g.ldo;
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const int col = nt * (kBN / 2) + wn * 64 + b * 32 + l31;
-          const float gv = acc[mi][b][r], uv = acc[mi][b + 2][r];
-          if (col < g.N) h[col] = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
-        }
-      } else {
-        float *o = static_cast<float *>(g.out) + grow * g.ldo;
-        const float w = g.row_w[grow];
-#pragma unroll
-        for (int ni = 0; ni < 4; ++ni) {
-          const int col = nt * kBN + wn * 128 + ni * 32 + l31;
-          if (col < g.N) o[col] = acc[mi][ni][r] * w;
-        }
-      }
-    }
-  }
+  if (rows > 96) gemm_bf16_tile<GATED, 4>(g, sA, nt, le, m0, rows);
+  else if (rows > 64) gemm_bf16_tile<GATED, 3>(g, sA, nt, le, m0, rows);
+  else if (rows > 32) gemm_bf16_tile<GATED, 2>(g, sA, nt, le, m0, rows);
+  else gemm_bf16_tile<GATED, 1>(g, sA, nt, le, m0, rows);
 }
 
 // ------------------------------------------------------------------------------------------------
