@@ -11,7 +11,7 @@ import os
 from typing import Optional
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libmoe355.so")
+LIB_PATH = os.environ.get("MOE355_LIB", os.path.join(_PKG, "libmoe355.so"))
 _lib: Optional[C.CDLL] = None
 
 MOE_F32 = 0

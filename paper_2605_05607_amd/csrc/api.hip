@@ -23,6 +23,8 @@ int check_shape(const moe_shape *s, Derived *out) {
   d.bm = s->dtype == MOE_BF16 ? kBM : kFBM;
   d.max_mtiles = (int)((d.P_cap + d.bm - 1) / d.bm) + d.E_loc;
   d.elt = s->dtype == MOE_BF16 ? 2 : 4;
+  d.nt1 = s->dtype == MOE_BF16 ? ceil_div(s->f, kBN / 2) : ceil_div(s->f, kFBN);
+  d.nt2 = s->dtype == MOE_BF16 ? ceil_div(s->d, kBN) : ceil_div(s->d, kFBN);
   if (out) *out = d;
   return MOE_OK;
 }
@@ -37,9 +39,8 @@ FwdLayout forward_layout(const moe_shape *s, const Derived &dv) {
   };
   const size_t rows = (size_t)(dv.P_cap > 0 ? dv.P_cap : 1);
   L.header = take(16 * sizeof(int32_t));
-  L.tile_e = take((size_t)dv.max_mtiles * sizeof(int32_t));
-  L.tile_m0 = take((size_t)dv.max_mtiles * sizeof(int32_t));
-  L.tile_rows = take((size_t)dv.max_mtiles * sizeof(int32_t));
+  L.work1 = take((size_t)dv.max_mtiles * dv.nt1 * 4 * sizeof(int32_t));
+  L.work2 = take((size_t)dv.max_mtiles * dv.nt2 * 4 * sizeof(int32_t));
   L.row_tok = take(rows * sizeof(int32_t));
   L.row_w = take(rows * sizeof(float));
   L.h = take(rows * (size_t)s->f * dv.elt);

@@ -11,9 +11,10 @@ constexpr int kWave = 64;
 constexpr int kMaxExperts = 4096;
 constexpr int kMaxTopK = 32;
 
-// GEMM macro-tile of the bf16 MFMA kernels.  BM matches the 128-token tile the paper uses both as GEMM
-// tile and as synchronisation granularity (Sec. VII-C).
-constexpr int kBM = 128;
+// GEMM macro-tile of the bf16 MFMA kernels.  The paper's tile is 128 tokens (GEMM tile = synchronisation
+// granularity, Sec. VII-C); here the M tile is 256 rows so that one pass over a weight panel does twice the
+// math per byte that has to cross the L2 -> CU path, which is what bounds the matrix cores on gfx950.
+constexpr int kBM = 256;
 constexpr int kBN = 256;
 constexpr int kBK = 64;
 // Tile of the plain fp32 kernels (small reference-grade path for fp32 layers).
@@ -29,6 +30,7 @@ struct Derived {
   int64_t P_cap;   // upper bound on local pairs: T * min(k, E_loc)
   int bm;          // M tile of the dtype's GEMM kernels
   int max_mtiles;  // upper bound on M tiles: ceil(P_cap / bm) + E_loc
+  int nt1, nt2;    // N tiles of GEMM-1 (over f) and GEMM-2 (over d)
   int elt;         // bytes per element of x / weights / y
 };
 
@@ -45,10 +47,10 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : M
 
 // ---- layout of the forward workspace (offsets in bytes, 256-byte aligned) ----
 struct FwdLayout {
-  size_t header;    // int32[16]: [0] n_mtiles, [1] P, [2] first layout row of the local segment
-  size_t tile_e;    // int32[max_mtiles]  local expert of the tile
-  size_t tile_m0;   // int32[max_mtiles]  first local row of the tile
-  size_t tile_rows; // int32[max_mtiles]  valid rows in the tile (1..bm)
+  size_t header;    // int32[16]: [0] work items of GEMM-1, [1] P, [2] first layout row of the local segment,
+                    //            [3] work items of GEMM-2
+  size_t work1;     // int4[max_mtiles * nt1]  (local expert, first local row, valid rows, N tile) per work item
+  size_t work2;     // int4[max_mtiles * nt2]
   size_t row_tok;   // int32[P_cap]       token of each local row
   size_t row_w;     // float[P_cap]       gate weight of each local row
   size_t h;         // elt  [P_cap, f]

@@ -17,31 +17,33 @@ constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS s
 
 // ------------------------------------------------------------------------------------------------
 // Weight packing (one-off).  Output tile (le, nt, kt) covers kBN output columns x kBK reduction indices and is
-// stored as the exact register images the MFMA B operand needs, so the GEMM kernel loads B straight from
-// global memory into registers with fully coalesced 16-byte loads and never stages it in LDS:
-//   tile = 4 waves x 4 k-substeps x 2 fragments x (64 lanes x 16 bytes);
-//   fragment (w, kk, j), lane l holds column n_l = w*64 + j*32 + (l & 31) at the 8 reduction indices
-//   kt*64 + kk*16 + (l >> 5)*8 + 0..7.
-// GATED tiles pair gate and up columns inside one wave: fragment j = 0 holds gate columns
-// nt*128 + w*32 + 0..31 and j = 1 the up columns of the same h columns.  Zero-padded outside the matrix.
+// the byte image of the LDS stage the GEMM kernel reads, so the kernel copies it linearly (16 bytes per lane,
+// fully coalesced):  row n_l of the tile is the 128-byte run of its 64 k values, cut into eight 16-byte
+// chunks; chunk c of row n_l sits at slot c ^ ((n_l >> 1) & 7).  The LDS of gfx950 has 64 four-byte banks, so
+// a 128-bit operand read is served 16 lanes at a time; with this swizzle the 16 rows such a group touches
+// fall on 16 different bank groups (measured: zero bank-conflict cycles).  Zero-padded outside the matrix.
+// GATED tiles pair gate and up columns inside one wave column: tile rows [wn*64, wn*64+32) are the gate
+// columns nt*128 + wn*32 + 0..31 and rows [wn*64+32, wn*64+64) the up columns of the same h columns.
 // ------------------------------------------------------------------------------------------------
 template <bool GATED>
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1,
                                                         bf16_t *__restrict__ out, int K, int N, int n_ntiles,
                                                         int n_ktiles) {
+  // grid: x = kt, y = nt, z = le;   256 threads: thread = tile row n_l, loops over the 8 chunks
   const int kt = blockIdx.x, nt = blockIdx.y, le = blockIdx.z;
+  const int n_l = threadIdx.x;
+  const int wn = n_l >> 6, j = (n_l >> 5) & 1, i = n_l & 31;
+  const bf16_t *W = (GATED && j == 1) ? W1 : W0;
+  const int col = GATED ? nt * (kBN / 2) + wn * 32 + i : nt * kBN + n_l;
   const size_t wbase = (size_t)le * K * N;
   bf16_t *tile = out + ((size_t)(le * n_ntiles + nt) * n_ktiles + kt) * (kBN * kBK);
-  for (int c = threadIdx.x; c < kBN * kBK / 8; c += blockDim.x) {
-    const int frag = c >> 6, l = c & 63;
-    const int w = frag >> 3, kk = (frag >> 1) & 3, j = frag & 1;
-    const bf16_t *W = (GATED && j == 1) ? W1 : W0;
-    const int col = GATED ? nt * (kBN / 2) + w * 32 + (l & 31) : nt * kBN + w * 64 + j * 32 + (l & 31);
-    const int k0 = kt * kBK + kk * 16 + (l >> 5) * 8;
+  for (int c = 0; c < 8; ++c) {
     bf16x8 v;
-    for (int q = 0; q < 8; ++q)
-      v[q] = (col < N && k0 + q < K) ? W[wbase + (size_t)(k0 + q) * N + col] : (bf16_t)0.0f;
-    *reinterpret_cast<bf16x8 *>(tile + (size_t)c * 8) = v;
+    for (int q = 0; q < 8; ++q) {
+      const int kk = kt * kBK + c * 8 + q;
+      v[q] = (col < N && kk < K) ? W[wbase + (size_t)kk * N + col] : (bf16_t)0.0f;
+    }
+    *reinterpret_cast<bf16x8 *>(tile + (size_t)n_l * kBK + ((c ^ ((n_l >> 1) & 7)) << 3)) = v;
   }
 }
 
@@ -51,18 +53,33 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 }
 
 // ------------------------------------------------------------------------------------------------
-// Tile table and per-row metadata of the local layout segment.
-// header[0] = number of M tiles, header[1] = P (local rows), header[2] = first layout row of the segment.
+// Work lists and per-row metadata of the local layout segment.
+// header[0] = work items of GEMM-1, header[1] = P (local rows), header[2] = first layout row of the segment,
+// header[3] = work items of GEMM-2.
+//
+// A work item is one output tile (expert, M tile, N tile).  The order of the list is what keeps the L2 useful:
+// the chip has 8 XCDs with a private 4 MiB L2 each and workgroup i runs on XCD i % 8, so every GEMM workgroup
+// maps its index to a list position such that XCD x works through the 32-item chunks x, x + 8, x + 16, ...;
+// and a chunk is a block of (up to 32 M tiles) x (32 / that many N tiles) of ONE expert, so the 32 workgroups
+// that are resident on an XCD at the same time share a few A slabs and a few weight panels instead of
+// streaming 32 different ones through the L2.
 // ------------------------------------------------------------------------------------------------
+constexpr int kChunk = 32;  // work items that are resident on one XCD at a time (one per CU)
+
+__device__ __forceinline__ int chunked_item(int block) {
+  const int xcd = block & 7, j = block >> 3;
+  return ((j / kChunk) * 8 + xcd) * kChunk + (j % kChunk);
+}
+
 __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict__ offsets,
                                                        const int32_t *__restrict__ perm,
                                                        const float *__restrict__ topk_w, int T, int k, int e_lo,
-                                                       int E_loc, int bm, int P_cap, int max_mtiles,
-                                                       int32_t *__restrict__ header, int32_t *__restrict__ tile_e,
-                                                       int32_t *__restrict__ tile_m0,
-                                                       int32_t *__restrict__ tile_rows,
-                                                       int32_t *__restrict__ row_tok, float *__restrict__ row_w) {
-  __shared__ int scratch[17];
+                                                       int E_loc, int bm, int P_cap, int max_mtiles, int nt1, int nt2,
+                                                       int32_t *__restrict__ header, int4 *__restrict__ work1,
+                                                       int4 *__restrict__ work2, int32_t *__restrict__ row_tok,
+                                                       float *__restrict__ row_w) {
+  extern __shared__ int tile0[];  // [E_loc + 1] first M tile of each local expert, then 17 ints of scan scratch
+  int *scratch = tile0 + E_loc + 1;
   const int base = offsets[e_lo];
   const int P = max(0, min(P_cap, offsets[e_lo + E_loc] - base));
   const long long npairs = (long long)T * k;
@@ -72,49 +89,76 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     row_tok[r] = p / k;
     row_w[r] = topk_w[p];
   }
-  if (blockIdx.x != 0) return;
-  // M tiles of expert le: ceil(count / bm), listed expert after expert
+  // every block rebuilds the per-expert M-tile prefix (cheap) so that the lists can be written grid-wide
   const int ipt = (E_loc + blockDim.x - 1) / blockDim.x;
   const int lo = min(E_loc, (int)threadIdx.x * ipt);
   const int hi = min(E_loc, lo + ipt);
   int local = 0;
   for (int le = lo; le < hi; ++le) {
-    const int cnt = max(0, offsets[e_lo + le + 1] - offsets[e_lo + le]);
+    const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
     local += (cnt + bm - 1) / bm;
   }
   int total;
   int run = block_exclusive_scan(local, scratch, &total);
   for (int le = lo; le < hi; ++le) {
-    const int start = offsets[e_lo + le] - base;
-    const int cnt = max(0, offsets[e_lo + le + 1] - offsets[e_lo + le]);
-    for (int m = 0; m < cnt; m += bm) {
-      if (run < max_mtiles && start + m < P) {
-        tile_e[run] = le;
-        tile_m0[run] = start + m;
-        tile_rows[run] = min(bm, min(cnt - m, P - (start + m)));
-      }
-      ++run;
-    }
+    const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
+    tile0[le] = run;
+    run += (cnt + bm - 1) / bm;
   }
-  if (threadIdx.x == 0) {
-    header[0] = min(total, max_mtiles);
+  if (threadIdx.x == 0) tile0[E_loc] = total;
+  __syncthreads();
+  total = min(total, max_mtiles);
+  const int n1 = total * nt1, n2 = total * nt2;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    header[0] = n1;
     header[1] = P;
     header[2] = base;
+    header[3] = n2;
+  }
+  for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < n1 + n2; q += gridDim.x * blockDim.x) {
+    const bool second = q >= n1;
+    const int Nt = second ? nt2 : nt1;
+    const int qq = second ? q - n1 : q;
+    // expert that owns list position qq: largest le with tile0[le] * Nt <= qq
+    int a = 0, b = E_loc;
+    while (b - a > 1) {
+      const int mid = (a + b) >> 1;
+      if (tile0[mid] * Nt <= qq) a = mid; else b = mid;
+    }
+    const int le = a;
+    const int Mt = tile0[le + 1] - tile0[le];
+    int r = qq - tile0[le] * Nt;
+    // inside the expert: M groups of up to 32 tiles; inside an M group: N groups of 32 / (M tiles) tiles
+    const int Mg = min(Mt, kChunk);
+    const int mg = r / (Mg * Nt);
+    r -= mg * Mg * Nt;
+    const int Mcur = min(Mg, Mt - mg * Mg);
+    const int G = max(1, kChunk / Mcur);
+    const int ng = r / (Mcur * G);
+    r -= ng * Mcur * G;
+    const int Gcur = min(G, Nt - ng * G);
+    const int mt = mg * Mg + r / Gcur;
+    const int nt = ng * G + r % Gcur;
+    const int start = min(P, offsets[e_lo + le] - base);
+    const int cnt = min(P, offsets[e_lo + le + 1] - base) - start;
+    const int4 item = make_int4(le, start + mt * bm, min(bm, cnt - mt * bm), nt);
+    if (second) work2[qq] = item; else work1[qq] = item;
   }
 }
 
 // ------------------------------------------------------------------------------------------------
 // Grouped bf16 GEMM on the matrix cores.  C[rows of one expert tile, kBN/2 or kBN columns] = A * W_e.
 //   A rows   : row_map == nullptr -> A[m0 + r, :]; else A[row_map[m0 + r], :] (token gather of Dispatch).
-//              128 x 64 slabs go global -> registers -> LDS (double buffered, 16-byte chunks XOR-swizzled by
-//              row so that the operand reads of eight neighbouring rows hit different banks).
-//   B        : packed register images, global -> registers, one k-step ahead of their use.
+//   B tiles  : packed LDS images streamed linearly.
 //   GATED    : epilogue h = silu(g) * u, written as bf16   (GEMM-1)
 //   !GATED   : epilogue o = acc * row_w[row], written fp32 (GEMM-2, gate weight of Sec. III-C)
-// 256 threads = 4 waves side by side along N; every wave owns all 128 rows x 64 columns as 4 x 2 MFMA
-// 32x32x16 accumulators, so no B data is shared between waves.  NBLK = number of 32-row blocks that hold
-// valid rows (the others are skipped: small experts are weight-streaming bound and need no padding math).
-// One barrier per k-step; two workgroups per CU overlap each other's stalls.
+// Tile 256 x 256 x 64, one workgroup of 512 threads per CU.  Every operand byte enters the CU once (global ->
+// registers -> LDS) because the L2 -> CU path, not the matrix core, is what saturates first on this chip;
+// sharing goes through the LDS, which has bandwidth to spare.  8 waves = 2 (rows) x 4 (columns), each wave
+// owns 128 x 64 as 4 x 2 MFMA 32x32x16 accumulators; two waves per SIMD cover each other's LDS latency.
+// LDS is double buffered (2 x 64 KiB) with one barrier per k-step; the next slab is in flight in registers
+// while the current one is multiplied.  NB = number of 32-row blocks of this wave that hold valid rows (the
+// others are skipped: small experts are weight-streaming bound and need no padding math).
 // ------------------------------------------------------------------------------------------------
 struct GemmArgs {
   const void *A;
@@ -122,7 +166,8 @@ struct GemmArgs {
   const void *Bp;
   void *out;
   const float *row_w;
-  const int32_t *header, *tile_e, *tile_m0, *tile_rows;
+  const int32_t *n_items;  // device: number of work items of this GEMM
+  const int4 *work;        // device: work list
   int K, N, lda, ldo, n_ntiles, n_ktiles;
 };
 
@@ -130,137 +175,135 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-constexpr int kAStageBytes = kBM * kBK * 2;  // 16 KiB
+constexpr int kGemmThreads = 512;
+constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
+constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
 
-template <bool GATED, int NBLK>
-__device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *sA, int nt, int le, int m0,
-                                               int rows) {
+template <bool GATED, int NB>
+__device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
+                                               int rows, int nblk_total) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int w = tid >> 6;
+  const int w8 = tid >> 6;
+  const int wm = w8 >> 2, wn = w8 & 3;
 
-  // ---- A: global -> register staging assignment (scalars, not arrays, so nothing lands in scratch) ----
-  const int a_chunk = tid & 7;  // 16-byte chunk (8 reduction indices) inside the 64-wide k slab
+  // ---- global -> register staging (scalars, not arrays, so nothing lands in scratch) ----
+  // A: thread t stages chunk t & 7 (8 reduction indices) of rows (t >> 3) + 64 i; B: chunks t + 512 i
+  const int a_chunk = tid & 7;
+  const int a_row0 = tid >> 3;  // 0..63
   const bf16_t *a_base = static_cast<const bf16_t *>(g.A) + a_chunk * 8;
-#define MOE355_A_ROW(i)                                                                        \
-  const int a_r##i = (tid >> 3) + 32 * i;                                                      \
-  const int a_rc##i = a_r##i < rows ? a_r##i : rows - 1; /* padding rows repeat a valid row */ \
-  const bf16_t *a_src##i =                                                                     \
-      a_base + (size_t)(g.row_map ? g.row_map[m0 + a_rc##i] : m0 + a_rc##i) * g.lda;            \
-  const int a_dst##i = (a_r##i * 8 + (a_chunk ^ (a_r##i & 7))) * 16;
+#define MOE355_A_ROW(i)                                                                          \
+  const int a_rc##i = a_row0 + 64 * i < rows ? a_row0 + 64 * i : rows - 1; /* padding: a valid row */ \
+  const uint32_t a_off##i =                                                                      \
+      (uint32_t)(g.row_map ? g.row_map[m0 + a_rc##i] : m0 + a_rc##i) * (uint32_t)g.lda;
   MOE355_A_ROW(0) MOE355_A_ROW(1) MOE355_A_ROW(2) MOE355_A_ROW(3)
 #undef MOE355_A_ROW
-  u32x4 ra0, ra1, ra2, ra3;
+  // LDS destination of row a_row0; row + 64 i lies 8192 bytes further (64 i keeps the swizzle bits)
+  const int a_dst = (a_row0 * 8 + (a_chunk ^ ((a_row0 >> 1) & 7))) * 16;
+  const unsigned char *b_src =
+      static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
+
+  u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
   const u32x4 zero4 = {0u, 0u, 0u, 0u};
-#define MOE355_LOAD_A(KT)                                                                        \
+#define MOE355_LOAD_STAGE(KT)                                                                    \
   do {                                                                                           \
     const int kt_ = (KT);                                                                        \
     const bool k_ok_ = kt_ * kBK + a_chunk * 8 < g.K;                                            \
     const int ko_ = k_ok_ ? kt_ * kBK : 0; /* branch-free: load a valid chunk, then select */    \
-    ra0 = *reinterpret_cast<const u32x4 *>(a_src0 + ko_);                                        \
-    if (NBLK > 1) ra1 = *reinterpret_cast<const u32x4 *>(a_src1 + ko_);                          \
-    if (NBLK > 2) ra2 = *reinterpret_cast<const u32x4 *>(a_src2 + ko_);                          \
-    if (NBLK > 3) ra3 = *reinterpret_cast<const u32x4 *>(a_src3 + ko_);                          \
+    ra0 = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + ko_);                               \
+    ra1 = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + ko_);                               \
+    ra2 = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + ko_);                               \
+    ra3 = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + ko_);                               \
     if (!k_ok_) ra0 = ra1 = ra2 = ra3 = zero4;                                                   \
+    const unsigned char *bt_ = b_src + (size_t)kt_ * kTileBytes;                                 \
+    rb0 = *reinterpret_cast<const u32x4 *>(bt_);                                                 \
+    rb1 = *reinterpret_cast<const u32x4 *>(bt_ + 8192);                                          \
+    rb2 = *reinterpret_cast<const u32x4 *>(bt_ + 16384);                                         \
+    rb3 = *reinterpret_cast<const u32x4 *>(bt_ + 24576);                                         \
   } while (0)
-#define MOE355_STORE_A(BUF)                                                     \
-  do {                                                                          \
-    unsigned char *s_ = sA + (BUF) * kAStageBytes;                              \
-    *reinterpret_cast<u32x4 *>(s_ + a_dst0) = ra0;                              \
-    if (NBLK > 1) *reinterpret_cast<u32x4 *>(s_ + a_dst1) = ra1;                \
-    if (NBLK > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst2) = ra2;                \
-    if (NBLK > 3) *reinterpret_cast<u32x4 *>(s_ + a_dst3) = ra3;                \
+#define MOE355_STORE_STAGE(BUF)                                                                  \
+  do {                                                                                           \
+    unsigned char *sa_ = smem + (BUF) * kStageBytes + a_dst;                                     \
+    *reinterpret_cast<u32x4 *>(sa_) = ra0;                                                       \
+    *reinterpret_cast<u32x4 *>(sa_ + 8192) = ra1;                                                \
+    *reinterpret_cast<u32x4 *>(sa_ + 16384) = ra2;                                               \
+    *reinterpret_cast<u32x4 *>(sa_ + 24576) = ra3;                                               \
+    unsigned char *sb_ = smem + (BUF) * kStageBytes + kAStageBytes + tid * 16;                   \
+    *reinterpret_cast<u32x4 *>(sb_) = rb0;                                                       \
+    *reinterpret_cast<u32x4 *>(sb_ + 8192) = rb1;                                                \
+    *reinterpret_cast<u32x4 *>(sb_ + 16384) = rb2;                                               \
+    *reinterpret_cast<u32x4 *>(sb_ + 24576) = rb3;                                               \
   } while (0)
 
-  // ---- B: this wave's 8 fragments of a k-step are 8 KiB contiguous; lane l reads 16 bytes of each ----
-  const unsigned char *b_src = static_cast<const unsigned char *>(g.Bp) +
-                               ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + w * 8192 + lane * 16;
-  bf16x8 b00, b01, b10, b11, b20, b21, b30, b31;  // b<kk><j>
-#define MOE355_LOAD_B(KK, KT)                                                                        \
-  do {                                                                                               \
-    const unsigned char *p_ = b_src + (size_t)(KT) * kTileBytes + (KK) * 2048;                       \
-    b##KK##0 = *reinterpret_cast<const bf16x8 *>(p_);                                                \
-    b##KK##1 = *reinterpret_cast<const bf16x8 *>(p_ + 1024);                                         \
-  } while (0)
-
-  f32x16 acc[NBLK][2];
+  f32x16 acc[NB > 0 ? NB : 1][2];
 #pragma unroll
-  for (int mi = 0; mi < NBLK; ++mi)
+  for (int mi = 0; mi < NB; ++mi)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][j][r] = 0.f;
 
-  // ---- LDS -> MFMA A operand addressing: lane l reads row l & 31 of a 32-row block, k half l >> 5 ----
-  const int l31 = lane & 31, khalf = lane >> 5, sw = lane & 7;
-  const int a_row_off = l31 * 128;
+  // ---- LDS -> MFMA operand addressing: lane l reads row l & 31 of a 32-row block, k half l >> 5 ----
+  const int l31 = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
+  const int a_rd = (wm * 128 + l31) * 128;                  // + mi * 4096
+  const int b_rd = kAStageBytes + (wn * 64 + l31) * 128;    // + j * 4096
 
   const int KT = g.n_ktiles;
-  MOE355_LOAD_A(0);
-  MOE355_LOAD_B(0, 0); MOE355_LOAD_B(1, 0); MOE355_LOAD_B(2, 0); MOE355_LOAD_B(3, 0);
-  MOE355_STORE_A(0);
+  const int kt_last = KT - 1;
+  MOE355_LOAD_STAGE(0);
+  MOE355_STORE_STAGE(0);
   __syncthreads();
-  MOE355_LOAD_A(KT > 1 ? 1 : 0);
-
-#define MOE355_READ_A(DST, KK)                                                                         \
-  do {                                                                                                 \
-    const int slot_ = (((KK) * 2 + khalf) ^ sw) * 16;                                                  \
-    _Pragma("unroll") for (int mi = 0; mi < NBLK; ++mi) DST[mi] =                                      \
-        *reinterpret_cast<const bf16x8 *>(sCur + a_row_off + mi * 4096 + slot_);                       \
-  } while (0)
-  // one 16-wide k-substep: this substep's MFMAs, then refill its B fragments with those of the next k-step
-#define MOE355_KSTEP(KK)                                                                               \
-  do {                                                                                                 \
-    bf16x8 a_[NBLK];                                                                                   \
-    MOE355_READ_A(a_, KK);                                                                             \
-    _Pragma("unroll") for (int mi = 0; mi < NBLK; ++mi) {                                              \
-      acc[mi][0] = mfma_bf16(a_[mi], b##KK##0, acc[mi][0]);                                            \
-      acc[mi][1] = mfma_bf16(a_[mi], b##KK##1, acc[mi][1]);                                            \
-    }                                                                                                  \
-    MOE355_LOAD_B(KK, kt_next);                                                                        \
-  } while (0)
 
   for (int kt = 0; kt < KT; ++kt) {
-    const unsigned char *sCur = sA + (kt & 1) * kAStageBytes;
-    // the reloads past the last k-step repeat the last slab: in bounds, never used
-    const int kt_next = kt + 1 < KT ? kt + 1 : kt;
-    MOE355_KSTEP(0);
-    MOE355_KSTEP(1);
-    MOE355_KSTEP(2);
-    MOE355_KSTEP(3);
-    MOE355_STORE_A((kt & 1) ^ 1);  // slab kt+1 into the buffer that was read during k-step kt-1
-    // Instruction order asked of the scheduler for the block above: the A fragments of substep kk+1 are read
-    // from LDS while the MFMAs of substep kk run, and each substep's B refill is issued right behind its
-    // MFMAs so that it keeps a whole k-step of distance to its use.
-    // (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write)
-    __builtin_amdgcn_sched_group_barrier(0x100, NBLK, 0);
+    const unsigned char *sCur = smem + (kt & 1) * kStageBytes;
+    // the reload past the last k-step repeats the last slab: in bounds, never used
+    MOE355_LOAD_STAGE(min(kt + 1, kt_last));
+    if (NB > 0) {
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, NBLK, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NBLK, 0);
-      __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+      for (int kk = 0; kk < 4; ++kk) {
+        const int slot = ((kk * 2 + khalf) ^ sw) * 16;
+        bf16x8 a_[NB > 0 ? NB : 1], b_[2];
+#pragma unroll
+        for (int mi = 0; mi < NB; ++mi) a_[mi] = *reinterpret_cast<const bf16x8 *>(sCur + a_rd + mi * 4096 + slot);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b_[j] = *reinterpret_cast<const bf16x8 *>(sCur + b_rd + j * 4096 + slot);
+#pragma unroll
+        for (int mi = 0; mi < NB; ++mi) {
+          acc[mi][0] = mfma_bf16(a_[mi], b_[0], acc[mi][0]);
+          acc[mi][1] = mfma_bf16(a_[mi], b_[1], acc[mi][1]);
+        }
+      }
     }
-    __builtin_amdgcn_sched_group_barrier(0x200, NBLK, 0);
+    MOE355_STORE_STAGE((kt & 1) ^ 1);  // slab kt+1 into the buffer that was read during k-step kt-1
+    // Instruction order asked of the scheduler for the block above (masks: 0x008 MFMA, 0x020 VMEM read,
+    // 0x100 DS read, 0x200 DS write): all global loads first, the operand reads of substep kk+1 under the
+    // MFMAs of substep kk, the LDS stores of the next slab last.
+    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);
+    if (NB > 0) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
+      }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x200, 8, 0);
     __syncthreads();
-    MOE355_LOAD_A(kt + 2 < KT ? kt + 2 : kt_next);
   }
-#undef MOE355_READ_A
-#undef MOE355_KSTEP
-#undef MOE355_LOAD_B
-#undef MOE355_LOAD_A
-#undef MOE355_STORE_A
+#undef MOE355_LOAD_STAGE
+#undef MOE355_STORE_STAGE
 
   // ---- epilogue ----
   // accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block
 #pragma unroll
-  for (int mi = 0; mi < NBLK; ++mi) {
+  for (int mi = 0; mi < NB; ++mi) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int row_l = mi * 32 + (r >> 2) * 8 + khalf * 4 + (r & 3);
+      const int row_l = wm * 128 + mi * 32 + (r >> 2) * 8 + khalf * 4 + (r & 3);
       if (row_l >= rows) continue;
       const size_t grow = (size_t)(m0 + row_l);
       if (GATED) {
-        const int col = nt * (kBN / 2) + w * 32 + l31;
+        const int col = nt * (kBN / 2) + wn * 32 + l31;
         const float gv = acc[mi][0][r], uv = acc[mi][1][r];
         if (col < g.N)
           static_cast<bf16_t *>(g.out)[grow * g.ldo + col] = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
@@ -269,7 +312,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         const float wgt = g.row_w[grow];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          const int col = nt * kBN + w * 64 + j * 32 + l31;
+          const int col = nt * kBN + wn * 64 + j * 32 + l31;
           if (col < g.N) o[col] = acc[mi][j][r] * wgt;
         }
       }
@@ -278,18 +321,23 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 }
 
 template <bool GATED>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) unsigned char sA[2 * kAStageBytes];
-  const int mt = blockIdx.y;
-  if (mt >= g.header[0]) return;
-  const int nt = blockIdx.x;
-  const int le = g.tile_e[mt];
-  const int m0 = g.tile_m0[mt];
-  const int rows = g.tile_rows[mt];
-  if (rows > 96) gemm_bf16_tile<GATED, 4>(g, sA, nt, le, m0, rows);
-  else if (rows > 64) gemm_bf16_tile<GATED, 3>(g, sA, nt, le, m0, rows);
-  else if (rows > 32) gemm_bf16_tile<GATED, 2>(g, sA, nt, le, m0, rows);
-  else gemm_bf16_tile<GATED, 1>(g, sA, nt, le, m0, rows);
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  const int q = chunked_item(blockIdx.x);
+  if (q >= *g.n_items) return;
+  const int4 item = g.work[q];
+  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w;
+  const int nblk_total = (rows + 31) >> 5;                        // 1..8
+  const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
+  const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
+  // wave-uniform dispatch: every variant executes the same sequence of barriers
+  switch (nb) {
+    case 0: gemm_bf16_tile<GATED, 0>(g, smem, nt, le, m0, rows, nblk_total); break;
+    case 1: gemm_bf16_tile<GATED, 1>(g, smem, nt, le, m0, rows, nblk_total); break;
+    case 2: gemm_bf16_tile<GATED, 2>(g, smem, nt, le, m0, rows, nblk_total); break;
+    case 3: gemm_bf16_tile<GATED, 3>(g, smem, nt, le, m0, rows, nblk_total); break;
+    default: gemm_bf16_tile<GATED, 4>(g, smem, nt, le, m0, rows, nblk_total); break;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -300,12 +348,10 @@ template <bool GATED>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
   __shared__ float sA[kFBM][kFBK + 1];
   __shared__ float sB[GATED ? 2 : 1][kFBK][kFBN];
-  const int mt = blockIdx.y;
-  if (mt >= g.header[0]) return;
-  const int nt = blockIdx.x;
-  const int le = g.tile_e[mt];
-  const int m0 = g.tile_m0[mt];
-  const int rows = g.tile_rows[mt];
+  const int q = chunked_item(blockIdx.x);
+  if (q >= *g.n_items) return;
+  const int4 item = g.work[q];
+  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w;
   const int tid = threadIdx.x;
   const int ty = tid >> 4, tx = tid & 15;
   const float *A = static_cast<const float *>(g.A);
@@ -504,7 +550,8 @@ __global__ __launch_bounds__(256) void cast_rows_kernel(const float *__restrict_
 // Host-side launch helpers
 // ------------------------------------------------------------------------------------------------
 struct Ws {
-  int32_t *header, *tile_e, *tile_m0, *tile_rows, *row_tok;
+  int32_t *header, *row_tok;
+  int4 *work1, *work2;
   float *row_w;
   void *h;
   float *o;
@@ -514,9 +561,8 @@ static Ws carve(void *workspace, const FwdLayout &L) {
   unsigned char *b = static_cast<unsigned char *>(workspace);
   Ws w;
   w.header = reinterpret_cast<int32_t *>(b + L.header);
-  w.tile_e = reinterpret_cast<int32_t *>(b + L.tile_e);
-  w.tile_m0 = reinterpret_cast<int32_t *>(b + L.tile_m0);
-  w.tile_rows = reinterpret_cast<int32_t *>(b + L.tile_rows);
+  w.work1 = reinterpret_cast<int4 *>(b + L.work1);
+  w.work2 = reinterpret_cast<int4 *>(b + L.work2);
   w.row_tok = reinterpret_cast<int32_t *>(b + L.row_tok);
   w.row_w = reinterpret_cast<float *>(b + L.row_w);
   w.h = b + L.h;
@@ -527,9 +573,9 @@ static Ws carve(void *workspace, const FwdLayout &L) {
 static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch *tb, const float *topk_w,
                        const Ws &w, hipStream_t st) {
   const int blocks = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (dv.P_cap + 255) / 256));
-  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), 0, st, tb->offsets, tb->perm, topk_w, s->T, s->k,
-                     dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles, w.header, w.tile_e, w.tile_m0,
-                     w.tile_rows, w.row_tok, w.row_w);
+  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), (size_t)(dv.E_loc + 1 + 17) * sizeof(int), st,
+                     tb->offsets, tb->perm, topk_w, s->T, s->k, dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles,
+                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w);
   return launch_status();
 }
 
@@ -543,29 +589,42 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
   };
   GemmArgs g1{};
   g1.A = a1; g1.row_map = a1_map; g1.Bp = packed_gu; g1.out = w.h; g1.row_w = nullptr;
-  g1.header = w.header; g1.tile_e = w.tile_e; g1.tile_m0 = w.tile_m0; g1.tile_rows = w.tile_rows;
+  g1.n_items = w.header + 0; g1.work = w.work1;
   g1.K = s->d; g1.N = s->f; g1.lda = a1_ld; g1.ldo = s->f;
   GemmArgs g2 = g1;
   g2.A = w.h; g2.row_map = nullptr; g2.Bp = packed_down; g2.out = w.o; g2.row_w = w.row_w;
   g2.K = s->f; g2.N = s->d; g2.lda = s->f; g2.ldo = s->d;
+  g2.n_items = w.header + 3; g2.work = w.work2;
+  const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dv.max_mtiles * nt + 255) / 256 * 256)); };
   if (s->dtype == MOE_BF16) {
+    // the two LDS stages (128 KiB) exceed the default dynamic limit; raising it is a per-function attribute
+    static const bool lds_ok = [] {
+      const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<true>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+      const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<false>),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
+      return e1 == hipSuccess && e2 == hipSuccess;
+    }();
+    if (!lds_ok) return MOE_ERR_HIP;
     g1.n_ntiles = ceil_div(s->f, kBN / 2); g1.n_ktiles = ceil_div(s->d, kBK);
     g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kBK);
-    hipLaunchKernelGGL(gemm_bf16_kernel<true>, dim3(g1.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g1);
+    hipLaunchKernelGGL(gemm_bf16_kernel<true>, grid_of(dv.nt1), dim3(kGemmThreads), 2 * kStageBytes, st,
+                       g1);
     int rc = launch_status();
     mark(2);
     if (rc != MOE_OK) return rc;
-    hipLaunchKernelGGL(gemm_bf16_kernel<false>, dim3(g2.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g2);
+    hipLaunchKernelGGL(gemm_bf16_kernel<false>, grid_of(dv.nt2), dim3(kGemmThreads), 2 * kStageBytes, st,
+                       g2);
     mark(3);
     return launch_status();
   }
   g1.n_ntiles = ceil_div(s->f, kFBN); g1.n_ktiles = dv.E_loc;
   g2.n_ntiles = ceil_div(s->d, kFBN); g2.n_ktiles = dv.E_loc;
-  hipLaunchKernelGGL(gemm_f32_kernel<true>, dim3(g1.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g1);
+  hipLaunchKernelGGL(gemm_f32_kernel<true>, grid_of(dv.nt1), dim3(256), 0, st, g1);
   int rc = launch_status();
   mark(2);
   if (rc != MOE_OK) return rc;
-  hipLaunchKernelGGL(gemm_f32_kernel<false>, dim3(g2.n_ntiles, dv.max_mtiles), dim3(256), 0, st, g2);
+  hipLaunchKernelGGL(gemm_f32_kernel<false>, grid_of(dv.nt2), dim3(256), 0, st, g2);
   mark(3);
   return launch_status();
 }
@@ -633,7 +692,7 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   const size_t need = fused ? moe_forward_workspace_bytes(shape) : moe_unfused_workspace_bytes(shape);
   if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MOE_ERR_INVALID_ARG;
-  if (dv.max_mtiles > 65535) return MOE_ERR_UNSUPPORTED;
+  if ((int64_t)dv.max_mtiles * std::max(dv.nt1, dv.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
   if (shape->T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
   begin_launches();
