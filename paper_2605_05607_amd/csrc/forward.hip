@@ -57,7 +57,9 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 // header[0] = work items of GEMM-1, header[1] = P (local rows), header[2] = first layout row of the segment,
 // header[3] = work items of GEMM-2.
 //
-// A work item is one output tile (expert, M tile, N tile).  The order of the list is what keeps the L2 useful:
+// A work item is one output tile (expert, M tile, N tile).  Full M tiles come first and the partial tile of each
+// expert (its last rows) afterwards, largest first, so that the launch ends with its shortest items.
+// The order of the list is also what keeps the L2 useful:
 // the chip has 8 XCDs with a private 4 MiB L2 each and workgroup i runs on XCD i % 8, so every GEMM workgroup
 // maps its index to a list position such that XCD x works through the 32-item chunks x, x + 8, x + 16, ...;
 // and a chunk is a block of (up to 32 M tiles) x (32 / that many N tiles) of ONE expert, so the 32 workgroups
@@ -78,8 +80,13 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
                                                        int32_t *__restrict__ header, int4 *__restrict__ work1,
                                                        int4 *__restrict__ work2, int32_t *__restrict__ row_tok,
                                                        float *__restrict__ row_w) {
-  extern __shared__ int tile0[];  // [E_loc + 1] first M tile of each local expert, then 17 ints of scan scratch
-  int *scratch = tile0 + E_loc + 1;
+  // LDS: full0[E_loc + 1] first full M tile of each expert | part[E_loc] rows of its partial tile (0 = none) |
+  //      order[E_loc] experts with a partial tile, largest first | 17 ints of scan scratch
+  extern __shared__ int lds[];
+  int *full0 = lds;
+  int *part = full0 + E_loc + 1;
+  int *order = part + E_loc;
+  int *scratch = order + E_loc;
   const int base = offsets[e_lo];
   const int P = max(0, min(P_cap, offsets[e_lo + E_loc] - base));
   const long long npairs = (long long)T * k;
@@ -89,26 +96,45 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     row_tok[r] = p / k;
     row_w[r] = topk_w[p];
   }
-  // every block rebuilds the per-expert M-tile prefix (cheap) so that the lists can be written grid-wide
+  // Every block rebuilds the small per-expert tables (cheap) so that the lists can be written grid-wide.
+  // An expert with cnt rows has cnt / bm full tiles and, if cnt % bm != 0, one partial tile.
   const int ipt = (E_loc + blockDim.x - 1) / blockDim.x;
   const int lo = min(E_loc, (int)threadIdx.x * ipt);
   const int hi = min(E_loc, lo + ipt);
-  int local = 0;
+  int local_full = 0, local_part = 0;
   for (int le = lo; le < hi; ++le) {
     const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
-    local += (cnt + bm - 1) / bm;
+    part[le] = cnt % bm;
+    local_full += cnt / bm;
+    local_part += (cnt % bm) != 0;
   }
-  int total;
-  int run = block_exclusive_scan(local, scratch, &total);
+  int n_full, n_part;
+  int run = block_exclusive_scan(local_full, scratch, &n_full);
   for (int le = lo; le < hi; ++le) {
     const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
-    tile0[le] = run;
-    run += (cnt + bm - 1) / bm;
+    full0[le] = run;
+    run += cnt / bm;
   }
-  if (threadIdx.x == 0) tile0[E_loc] = total;
+  if (threadIdx.x == 0) full0[E_loc] = n_full;
+  (void)block_exclusive_scan(local_part, scratch, &n_part);
   __syncthreads();
-  total = min(total, max_mtiles);
-  const int n1 = total * nt1, n2 = total * nt2;
+  // Longest-first order of the partial tiles (rank sort; for very many experts keep the expert order):
+  // the full tiles are listed first and the partial ones by decreasing size, so that the tail of the launch is
+  // made of the shortest work items.
+  for (int le = lo; le < hi; ++le) {
+    if (part[le] == 0) continue;
+    int rank = 0;
+    if (E_loc <= 1024) {
+      for (int o = 0; o < E_loc; ++o) rank += part[o] > part[le] || (part[o] == part[le] && o < le);
+    } else {
+      for (int o = 0; o < le; ++o) rank += part[o] != 0;
+    }
+    order[rank] = le;
+  }
+  __syncthreads();
+  n_full = min(n_full, max_mtiles);
+  n_part = min(n_part, max_mtiles - n_full);
+  const int n1 = (n_full + n_part) * nt1, n2 = (n_full + n_part) * nt2;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     header[0] = n1;
     header[1] = P;
@@ -119,29 +145,39 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     const bool second = q >= n1;
     const int Nt = second ? nt2 : nt1;
     const int qq = second ? q - n1 : q;
-    // expert that owns list position qq: largest le with tile0[le] * Nt <= qq
-    int a = 0, b = E_loc;
-    while (b - a > 1) {
-      const int mid = (a + b) >> 1;
-      if (tile0[mid] * Nt <= qq) a = mid; else b = mid;
+    int le, mt, nt, rows;
+    if (qq < n_full * Nt) {
+      // expert that owns list position qq: largest le with full0[le] * Nt <= qq
+      int a = 0, b = E_loc;
+      while (b - a > 1) {
+        const int mid = (a + b) >> 1;
+        if (full0[mid] * Nt <= qq) a = mid; else b = mid;
+      }
+      le = a;
+      const int Mt = full0[le + 1] - full0[le];
+      int r = qq - full0[le] * Nt;
+      // inside the expert: M groups of up to 32 tiles; inside an M group: N groups of 32 / (M tiles) tiles
+      const int Mg = min(Mt, kChunk);
+      const int mg = r / (Mg * Nt);
+      r -= mg * Mg * Nt;
+      const int Mcur = min(Mg, Mt - mg * Mg);
+      const int G = max(1, kChunk / Mcur);
+      const int ng = r / (Mcur * G);
+      r -= ng * Mcur * G;
+      const int Gcur = min(G, Nt - ng * G);
+      mt = mg * Mg + r / Gcur;
+      nt = ng * G + r % Gcur;
+      rows = bm;
+    } else {
+      const int r = qq - n_full * Nt;
+      le = order[r / Nt];
+      nt = r % Nt;
+      const int cnt = min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base);
+      mt = cnt / bm;
+      rows = part[le];
     }
-    const int le = a;
-    const int Mt = tile0[le + 1] - tile0[le];
-    int r = qq - tile0[le] * Nt;
-    // inside the expert: M groups of up to 32 tiles; inside an M group: N groups of 32 / (M tiles) tiles
-    const int Mg = min(Mt, kChunk);
-    const int mg = r / (Mg * Nt);
-    r -= mg * Mg * Nt;
-    const int Mcur = min(Mg, Mt - mg * Mg);
-    const int G = max(1, kChunk / Mcur);
-    const int ng = r / (Mcur * G);
-    r -= ng * Mcur * G;
-    const int Gcur = min(G, Nt - ng * G);
-    const int mt = mg * Mg + r / Gcur;
-    const int nt = ng * G + r % Gcur;
     const int start = min(P, offsets[e_lo + le] - base);
-    const int cnt = min(P, offsets[e_lo + le + 1] - base) - start;
-    const int4 item = make_int4(le, start + mt * bm, min(bm, cnt - mt * bm), nt);
+    const int4 item = make_int4(le, start + mt * bm, rows, nt);
     if (second) work2[qq] = item; else work1[qq] = item;
   }
 }
@@ -179,7 +215,7 @@ constexpr int kGemmThreads = 512;
 constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
 constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
 
-template <bool GATED, int NB>
+template <bool GATED, int NB, int NA>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
                                                int rows, int nblk_total) {
   const int tid = threadIdx.x;
@@ -204,35 +240,48 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
 
   u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
-  const u32x4 zero4 = {0u, 0u, 0u, 0u};
-#define MOE355_LOAD_STAGE(KT)                                                                    \
+  // R is moved in three portions: {ra0, ra1, rb0}, {ra2, ra3, rb1}, {rb2, rb3}
+  // k tail: a chunk past K is replaced by chunk 0 of the same row (valid memory, finite data); the packed B
+  // tile is zero there, so it contributes nothing and no select has to wait on the load
+#define MOE355_A_OFF(KT) ((KT) * kBK + a_chunk * 8 < g.K ? (KT) * kBK : -a_chunk * 8)
+  // NA = row loads per thread that reach valid rows (1: rows < 64, 2: rows < 128, 4: all); the others are skipped
+#define MOE355_LOAD_A01(KT)                                                                      \
   do {                                                                                           \
-    const int kt_ = (KT);                                                                        \
-    const bool k_ok_ = kt_ * kBK + a_chunk * 8 < g.K;                                            \
-    const int ko_ = k_ok_ ? kt_ * kBK : 0; /* branch-free: load a valid chunk, then select */    \
-    ra0 = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + ko_);                               \
-    ra1 = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + ko_);                               \
-    ra2 = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + ko_);                               \
-    ra3 = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + ko_);                               \
-    if (!k_ok_) ra0 = ra1 = ra2 = ra3 = zero4;                                                   \
-    const unsigned char *bt_ = b_src + (size_t)kt_ * kTileBytes;                                 \
-    rb0 = *reinterpret_cast<const u32x4 *>(bt_);                                                 \
-    rb1 = *reinterpret_cast<const u32x4 *>(bt_ + 8192);                                          \
-    rb2 = *reinterpret_cast<const u32x4 *>(bt_ + 16384);                                         \
-    rb3 = *reinterpret_cast<const u32x4 *>(bt_ + 24576);                                         \
+    ra0 = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + MOE355_A_OFF(KT));                  \
+    if (NA > 1) ra1 = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + MOE355_A_OFF(KT));      \
   } while (0)
-#define MOE355_STORE_STAGE(BUF)                                                                  \
+#define MOE355_LOAD_A23(KT)                                                                      \
   do {                                                                                           \
-    unsigned char *sa_ = smem + (BUF) * kStageBytes + a_dst;                                     \
-    *reinterpret_cast<u32x4 *>(sa_) = ra0;                                                       \
-    *reinterpret_cast<u32x4 *>(sa_ + 8192) = ra1;                                                \
-    *reinterpret_cast<u32x4 *>(sa_ + 16384) = ra2;                                               \
-    *reinterpret_cast<u32x4 *>(sa_ + 24576) = ra3;                                               \
-    unsigned char *sb_ = smem + (BUF) * kStageBytes + kAStageBytes + tid * 16;                   \
-    *reinterpret_cast<u32x4 *>(sb_) = rb0;                                                       \
-    *reinterpret_cast<u32x4 *>(sb_ + 8192) = rb1;                                                \
-    *reinterpret_cast<u32x4 *>(sb_ + 16384) = rb2;                                               \
-    *reinterpret_cast<u32x4 *>(sb_ + 24576) = rb3;                                               \
+    if (NA > 2) ra2 = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + MOE355_A_OFF(KT));      \
+    if (NA > 2) ra3 = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + MOE355_A_OFF(KT));      \
+  } while (0)
+#define MOE355_LOAD_B0(KT) rb0 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes)
+#define MOE355_LOAD_B1(KT) rb1 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 8192)
+#define MOE355_LOAD_B01(KT) do { MOE355_LOAD_B0(KT); MOE355_LOAD_B1(KT); } while (0)
+#define MOE355_LOAD_B23(KT)                                                                      \
+  do {                                                                                           \
+    rb2 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 16384);           \
+    rb3 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 24576);           \
+  } while (0)
+#define MOE355_STORE_P0(BUF)                                                                     \
+  do {                                                                                           \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                              \
+    *reinterpret_cast<u32x4 *>(s_ + a_dst) = ra0;                                                \
+    if (NA > 1) *reinterpret_cast<u32x4 *>(s_ + a_dst + 8192) = ra1;                             \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16) = rb0;                              \
+  } while (0)
+#define MOE355_STORE_P1(BUF)                                                                     \
+  do {                                                                                           \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                              \
+    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 16384) = ra2;                            \
+    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 24576) = ra3;                            \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 8192) = rb1;                       \
+  } while (0)
+#define MOE355_STORE_P2(BUF)                                                                     \
+  do {                                                                                           \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                              \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 16384) = rb2;                      \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 24576) = rb3;                      \
   } while (0)
 
   f32x16 acc[NB > 0 ? NB : 1][2];
@@ -248,50 +297,101 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   const int a_rd = (wm * 128 + l31) * 128;                  // + mi * 4096
   const int b_rd = kAStageBytes + (wn * 64 + l31) * 128;    // + j * 4096
 
+  constexpr int NF = NB > 0 ? NB : 1;
+  bf16x8 fa0[NF], fb0[2], fa1[NF], fb1[2];  // operand fragments of two consecutive k-substeps
+#define MOE355_READ_FRAGS(FA, FB, STAGE, KK)                                                           \
+  do {                                                                                                 \
+    const int slot_ = (((KK) * 2 + khalf) ^ sw) * 16;                                                  \
+    _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) FA[mi] =                                         \
+        *reinterpret_cast<const bf16x8 *>((STAGE) + a_rd + mi * 4096 + slot_);                         \
+    if (NB > 0) {                                                                                      \
+      FB[0] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + slot_);                               \
+      FB[1] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + 4096 + slot_);                        \
+    }                                                                                                  \
+  } while (0)
+#define MOE355_MFMAS(FA, FB)                                                                           \
+  do {                                                                                                 \
+    _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) {                                                \
+      acc[mi][0] = mfma_bf16(FA[mi], FB[0], acc[mi][0]);                                               \
+      acc[mi][1] = mfma_bf16(FA[mi], FB[1], acc[mi][1]);                                               \
+    }                                                                                                  \
+  } while (0)
+
+  // Pipeline.  At the top of k-step kt: LDS stage kt & 1 holds slab kt, the registers R hold slab kt + 1 (its
+  // loads were issued one k-step ago, in three portions), and fa0 / fb0 hold the operands of substep 0.
+  // Substeps 0..2 each multiply, fetch the next substep's operands, move one portion of R into the other stage
+  // and reissue that portion's loads for slab kt + 2, so the global loads, the LDS stores and the LDS reads are
+  // all spread under the MFMAs instead of forming a burst around the barrier.  The single barrier sits before
+  // substep 3, whose operands are already in registers; substep 3 also fetches substep 0 of the next slab.
   const int KT = g.n_ktiles;
   const int kt_last = KT - 1;
-  MOE355_LOAD_STAGE(0);
-  MOE355_STORE_STAGE(0);
+  MOE355_LOAD_A01(0); MOE355_LOAD_A23(0); MOE355_LOAD_B01(0); MOE355_LOAD_B23(0);
+  MOE355_STORE_P0(0); MOE355_STORE_P1(0); MOE355_STORE_P2(0);
+  {
+    const int k1 = min(1, kt_last);  // reloads past the last k-step repeat the last slab: in bounds, never used
+    MOE355_LOAD_A01(k1); MOE355_LOAD_A23(k1); MOE355_LOAD_B01(k1); MOE355_LOAD_B23(k1);
+  }
   __syncthreads();
+  MOE355_READ_FRAGS(fa0, fb0, smem, 0);
 
   for (int kt = 0; kt < KT; ++kt) {
     const unsigned char *sCur = smem + (kt & 1) * kStageBytes;
-    // the reload past the last k-step repeats the last slab: in bounds, never used
-    MOE355_LOAD_STAGE(min(kt + 1, kt_last));
-    if (NB > 0) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int slot = ((kk * 2 + khalf) ^ sw) * 16;
-        bf16x8 a_[NB > 0 ? NB : 1], b_[2];
-#pragma unroll
-        for (int mi = 0; mi < NB; ++mi) a_[mi] = *reinterpret_cast<const bf16x8 *>(sCur + a_rd + mi * 4096 + slot);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) b_[j] = *reinterpret_cast<const bf16x8 *>(sCur + b_rd + j * 4096 + slot);
-#pragma unroll
-        for (int mi = 0; mi < NB; ++mi) {
-          acc[mi][0] = mfma_bf16(a_[mi], b_[0], acc[mi][0]);
-          acc[mi][1] = mfma_bf16(a_[mi], b_[1], acc[mi][1]);
-        }
-      }
-    }
-    MOE355_STORE_STAGE((kt & 1) ^ 1);  // slab kt+1 into the buffer that was read during k-step kt-1
-    // Instruction order asked of the scheduler for the block above (masks: 0x008 MFMA, 0x020 VMEM read,
-    // 0x100 DS read, 0x200 DS write): all global loads first, the operand reads of substep kk+1 under the
-    // MFMAs of substep kk, the LDS stores of the next slab last.
-    __builtin_amdgcn_sched_group_barrier(0x020, 8, 0);
+    const int nxt = (kt & 1) ^ 1;
+    const int k2 = min(kt + 2, kt_last);
+    // substep 0
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 1);
+    MOE355_MFMAS(fa0, fb0);
+    MOE355_STORE_P0(nxt);
+    MOE355_LOAD_A01(k2); MOE355_LOAD_B0(k2);
+    // substep 1
+    MOE355_READ_FRAGS(fa0, fb0, sCur, 2);
+    MOE355_MFMAS(fa1, fb1);
+    MOE355_STORE_P1(nxt);
+    MOE355_LOAD_A23(k2); MOE355_LOAD_B1(k2);
+    // substep 2
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 3);
+    MOE355_MFMAS(fa0, fb0);
+    MOE355_STORE_P2(nxt);
+    MOE355_LOAD_B23(k2);
+    // requested instruction order (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write)
     if (NB > 0) {
       __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        if (kk < 3) __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
-      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x200, 8, 0);
+    __builtin_amdgcn_sched_group_barrier(0x200, NA > 1 ? 3 : 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, NA > 1 ? 3 : 2, 0);
+    if (NB > 0) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x200, NA > 2 ? 3 : 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, NA > 2 ? 3 : 1, 0);
+    if (NB > 0) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
     __syncthreads();
+    // substep 3, and substep 0 operands of the next slab
+    MOE355_READ_FRAGS(fa0, fb0, smem + nxt * kStageBytes, 0);
+    MOE355_MFMAS(fa1, fb1);
+    if (NB > 0) {
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
+    }
   }
-#undef MOE355_LOAD_STAGE
-#undef MOE355_STORE_STAGE
+#undef MOE355_READ_FRAGS
+#undef MOE355_MFMAS
+#undef MOE355_LOAD_A01
+#undef MOE355_LOAD_A23
+#undef MOE355_LOAD_B0
+#undef MOE355_LOAD_B1
+#undef MOE355_LOAD_B01
+#undef MOE355_LOAD_B23
+#undef MOE355_STORE_P0
+#undef MOE355_STORE_P1
+#undef MOE355_STORE_P2
 
   // ---- epilogue ----
   // accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block
@@ -331,13 +431,16 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmAr
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
   // wave-uniform dispatch: every variant executes the same sequence of barriers
-  switch (nb) {
-    case 0: gemm_bf16_tile<GATED, 0>(g, smem, nt, le, m0, rows, nblk_total); break;
-    case 1: gemm_bf16_tile<GATED, 1>(g, smem, nt, le, m0, rows, nblk_total); break;
-    case 2: gemm_bf16_tile<GATED, 2>(g, smem, nt, le, m0, rows, nblk_total); break;
-    case 3: gemm_bf16_tile<GATED, 3>(g, smem, nt, le, m0, rows, nblk_total); break;
-    default: gemm_bf16_tile<GATED, 4>(g, smem, nt, le, m0, rows, nblk_total); break;
+#define MOE355_TILE(NB_, NA_) gemm_bf16_tile<GATED, NB_, NA_>(g, smem, nt, le, m0, rows, nblk_total)
+  if (nblk_total <= 2) {
+    if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
+  } else if (nblk_total <= 4) {
+    if (nb == 4) MOE355_TILE(4, 2); else if (nb == 3) MOE355_TILE(3, 2); else MOE355_TILE(0, 2);
+  } else {
+    if (nb == 4) MOE355_TILE(4, 4); else if (nb == 3) MOE355_TILE(3, 4); else if (nb == 2) MOE355_TILE(2, 4);
+    else MOE355_TILE(1, 4);
   }
+#undef MOE355_TILE
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -573,7 +676,7 @@ static Ws carve(void *workspace, const FwdLayout &L) {
 static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch *tb, const float *topk_w,
                        const Ws &w, hipStream_t st) {
   const int blocks = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (dv.P_cap + 255) / 256));
-  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), (size_t)(dv.E_loc + 1 + 17) * sizeof(int), st,
+  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), (size_t)(3 * dv.E_loc + 1 + 17) * sizeof(int), st,
                      tb->offsets, tb->perm, topk_w, s->T, s->k, dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles,
                      dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w);
   return launch_status();
