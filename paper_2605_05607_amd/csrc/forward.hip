@@ -214,6 +214,7 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
 constexpr int kGemmThreads = 512;
 constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
 constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
+constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue patch (fits 8 x in the stages)
 
 template <bool GATED, int NB, int NA>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
@@ -394,29 +395,60 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 #undef MOE355_STORE_P2
 
   // ---- epilogue ----
-  // accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block
+  // Accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block, i.e. a lane
+  // owns one column.  Each wave turns its blocks around through a private LDS patch (the stages are dead now)
+  // so that the global stores are 16 bytes per lane along a row instead of one element per lane.
+  __syncthreads();  // every wave has finished reading the stages
+  unsigned char *patch = smem + w8 * kPatchBytes;
 #pragma unroll
   for (int mi = 0; mi < NB; ++mi) {
+    const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
+    if (GATED) {
+      // h block: 32 rows x 32 columns bf16, row pitch 80 bytes (keeps the two half-waves on different banks)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int row_l = wm * 128 + mi * 32 + (r >> 2) * 8 + khalf * 4 + (r & 3);
-      if (row_l >= rows) continue;
-      const size_t grow = (size_t)(m0 + row_l);
-      if (GATED) {
-        const int col = nt * (kBN / 2) + wn * 32 + l31;
+      for (int r = 0; r < 16; ++r) {
+        const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const float gv = acc[mi][0][r], uv = acc[mi][1][r];
-        if (col < g.N)
-          static_cast<bf16_t *>(g.out)[grow * g.ldo + col] = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
-      } else {
-        float *o = static_cast<float *>(g.out) + grow * g.ldo;
-        const float wgt = g.row_w[grow];
+        *reinterpret_cast<bf16_t *>(patch + rl * 80 + l31 * 2) = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const int col = nt * kBN + wn * 64 + j * 32 + l31;
-          if (col < g.N) o[col] = acc[mi][j][r] * wgt;
-        }
+      for (int it = 0; it < 2; ++it) {
+        const int c = it * 64 + lane;        // 16-byte chunk: 4 chunks per row
+        const int rl = c >> 2, cc = c & 3;
+        const int row_l = blk_row0 + rl;
+        const int col = nt * (kBN / 2) + wn * 32 + cc * 8;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + rl * 80 + cc * 16);
+        if (row_l < rows && col < g.N)
+          *reinterpret_cast<u32x4 *>(static_cast<bf16_t *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+      }
+    } else {
+      // o block: 32 rows x 64 columns fp32, row pitch 288 bytes
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+        const int row_l = blk_row0 + rl;
+        const float wgt = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
+        *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = acc[mi][0][r] * wgt;
+        *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) = acc[mi][1][r] * wgt;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int rl = it * 4 + (lane >> 4), cc = lane & 15;  // 16 chunks of 16 bytes per row
+        const int row_l = blk_row0 + rl;
+        const int col = nt * kBN + wn * 64 + cc * 4;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + rl * 288 + cc * 16);
+        if (row_l < rows && col < g.N)
+          *reinterpret_cast<u32x4 *>(static_cast<float *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the patch is reused by the next block
   }
 }
 
