@@ -35,6 +35,30 @@ def algorithmic_work(cfg, idx, counts_local):
     return P, U_tok, ne, g1, g2, cb
 
 
+def kernel_source_hash():
+    """sha256 over the kernel sources; stored counter readings are only valid for the sources they were taken on."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2605_05607_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        with open(os.path.join(csrc, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def stored_traffic(cfg_name):
+    """HBM bytes per launch of GEMM-1 from the committed rocprofv3 counter readings (FETCH_SIZE and WRITE_SIZE in KiB,
+    each scaled by what the same counter reads for a plain 1 GiB copy); None if the kernels changed since."""
+    path = os.path.join(ROOT, "profiles", f"traffic_gemm1_{cfg_name}.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    if rec.get("source_sha256") != kernel_source_hash():
+        return None
+    return (rec["fetch_size_kib"] * rec["fetch_scale"] + rec["write_size_kib"] * rec["write_scale"]) * 1024.0
+
+
 def cpu_baseline(cfg, w, budget_s=12.0):
     """Oracle (as it stands) on a bounded random token sample; tokens/s on the host cores."""
     import numpy as np
@@ -72,6 +96,8 @@ def main():
     ap.add_argument("--config", default="deepseek_v3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override T (sweeps); 0 = the config's T")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a 1 GiB device-to-device copy (reference point for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the layer; this build has no multi-GPU path (--gpus must be 1)",
@@ -80,6 +106,17 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.copy_calibration:
+        torch.cuda.set_device(0)
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": dst.numel() * 4, "launches": 5}))
+        return
 
     from paper_2605_05607_amd import binding as B
     from paper_2605_05607_amd import layer as L
@@ -135,7 +172,9 @@ def main():
         roof = {"bound": "mfma", "achieved": g1["flops"] / (g1_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = None if args.tokens else stored_traffic(cfg.name)
+    roof["traffic_unit"] = "bytes per launch"
+    roof["algorithmic"] = g1["bytes"] if roof["bound"] == "hbm" else g1["flops"]
     roof["kernel"] = "gemm_bf16_kernel<true> (GEMM-1: gathered gate/up GEMM + SwiGLU)"
     roof["avg_launch_ms"] = float(g1_ms)
 

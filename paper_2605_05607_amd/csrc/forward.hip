@@ -62,11 +62,12 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 // The order of the list is also what keeps the L2 useful:
 // the chip has 8 XCDs with a private 4 MiB L2 each and workgroup i runs on XCD i % 8, so every GEMM workgroup
 // maps its index to a list position such that XCD x works through the 32-item chunks x, x + 8, x + 16, ...;
-// and a chunk is a block of (up to 32 M tiles) x (32 / that many N tiles) of ONE expert, so the 32 workgroups
+// and a chunk is a block of (up to 8 M tiles) x (32 / that many N tiles) of ONE expert, so the 32 workgroups
 // that are resident on an XCD at the same time share a few A slabs and a few weight panels instead of
 // streaming 32 different ones through the L2.
 // ------------------------------------------------------------------------------------------------
 constexpr int kChunk = 32;  // work items that are resident on one XCD at a time (one per CU)
+constexpr int kChunkM = 8;  // M tiles per chunk (at most)
 
 __device__ __forceinline__ int chunked_item(int block) {
   const int xcd = block & 7, j = block >> 3;
@@ -156,8 +157,10 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       le = a;
       const int Mt = full0[le + 1] - full0[le];
       int r = qq - full0[le] * Nt;
-      // inside the expert: M groups of up to 32 tiles; inside an M group: N groups of 32 / (M tiles) tiles
-      const int Mg = min(Mt, kChunk);
+      // inside the expert: M groups of up to 8 tiles; inside an M group: N groups of 32 / (M tiles) tiles.
+      // (A slab and B panel of a tile are equally large, so the bytes a chunk pulls into its L2 are smallest
+      // when the chunk is close to square: 8 x 4 rather than 32 x 1.)
+      const int Mg = min(Mt, kChunkM);
       const int mg = r / (Mg * Nt);
       r -= mg * Mg * Nt;
       const int Mcur = min(Mg, Mt - mg * Mg);
