@@ -58,7 +58,8 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 // header[3] = work items of GEMM-2.
 //
 // A work item is one output tile (expert, M tile, N tile).  Full M tiles come first and the partial tile of each
-// expert (its last rows) afterwards, largest first, so that the launch ends with its shortest items.
+// expert (its last rows) afterwards, largest first, so that the launch ends with its shortest items; partial
+// tiles of at most 64 rows (pure weight streaming) are mixed into the full tiles (see the list order below).
 // The order of the list is also what keeps the L2 useful:
 // the chip has 8 XCDs with a private 4 MiB L2 each and workgroup i runs on XCD i % 8, so every GEMM workgroup
 // maps its index to a list position such that XCD x works through the 32-item chunks x, x + 8, x + 16, ...;
@@ -69,10 +70,24 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 constexpr int kChunk = 32;  // work items that are resident on one XCD at a time (one per CU)
 constexpr int kChunkM = 8;  // M tiles per chunk (at most)
 
-__device__ __forceinline__ int chunked_item(int block) {
+// List position of workgroup `block` (or -1): XCD x = block % 8 takes whole 32-item chunks x, x + 8, ... while
+// complete rounds of 8 chunks last; the remaining items (fewer than 256) are cut into 8 equal contiguous pieces so
+// that every XCD gets the same number of items to within one.
+__device__ __forceinline__ int chunked_item(int block, int n_items) {
   const int xcd = block & 7, j = block >> 3;
-  return ((j / kChunk) * 8 + xcd) * kChunk + (j % kChunk);
+  const int full_rows = n_items / (8 * kChunk);
+  if (j < full_rows * kChunk) return ((j / kChunk) * 8 + xcd) * kChunk + (j % kChunk);
+  const int rem = n_items - full_rows * 8 * kChunk;
+  const int jj = j - full_rows * kChunk;
+  const int piece = rem / 8, extra = rem % 8;
+  const int size = piece + (xcd < extra);
+  if (jj >= size) return -1;
+  return full_rows * 8 * kChunk + xcd * piece + min(xcd, extra) + jj;
 }
+
+// Rows up to which a partial tile counts as "streaming": its cost is reading the expert's weights from HBM, not
+// the matrix cores.
+constexpr int kStreamRows = 64;
 
 __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict__ offsets,
                                                        const int32_t *__restrict__ perm,
@@ -82,7 +97,8 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
                                                        int4 *__restrict__ work2, int32_t *__restrict__ row_tok,
                                                        float *__restrict__ row_w) {
   // LDS: full0[E_loc + 1] first full M tile of each expert | part[E_loc] rows of its partial tile (0 = none) |
-  //      order[E_loc] experts with a partial tile, largest first | 17 ints of scan scratch
+  //      order[E_loc] partial tiles: first the large ones (> kStreamRows rows), largest first, then the
+  //      streaming ones, largest first | 17 ints of scan scratch
   extern __shared__ int lds[];
   int *full0 = lds;
   int *part = full0 + E_loc + 1;
@@ -102,14 +118,15 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
   const int ipt = (E_loc + blockDim.x - 1) / blockDim.x;
   const int lo = min(E_loc, (int)threadIdx.x * ipt);
   const int hi = min(E_loc, lo + ipt);
-  int local_full = 0, local_part = 0;
+  int local_full = 0, local_big = 0, local_small = 0;
   for (int le = lo; le < hi; ++le) {
     const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
     part[le] = cnt % bm;
     local_full += cnt / bm;
-    local_part += (cnt % bm) != 0;
+    local_big += (cnt % bm) > kStreamRows;
+    local_small += (cnt % bm) != 0 && (cnt % bm) <= kStreamRows;
   }
-  int n_full, n_part;
+  int n_full, n_big, n_small;
   int run = block_exclusive_scan(local_full, scratch, &n_full);
   for (int le = lo; le < hi; ++le) {
     const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
@@ -117,25 +134,28 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     run += cnt / bm;
   }
   if (threadIdx.x == 0) full0[E_loc] = n_full;
-  (void)block_exclusive_scan(local_part, scratch, &n_part);
+  (void)block_exclusive_scan(local_big, scratch, &n_big);
+  (void)block_exclusive_scan(local_small, scratch, &n_small);
   __syncthreads();
-  // Longest-first order of the partial tiles (rank sort; for very many experts keep the expert order):
-  // the full tiles are listed first and the partial ones by decreasing size, so that the tail of the launch is
-  // made of the shortest work items.
+  // rank sort inside the two classes of partial tiles (for very many experts keep the expert order)
   for (int le = lo; le < hi; ++le) {
-    if (part[le] == 0) continue;
+    const int mine = part[le];
+    if (mine == 0) continue;
+    const bool small = mine <= kStreamRows;
     int rank = 0;
-    if (E_loc <= 1024) {
-      for (int o = 0; o < E_loc; ++o) rank += part[o] > part[le] || (part[o] == part[le] && o < le);
-    } else {
-      for (int o = 0; o < le; ++o) rank += part[o] != 0;
+    for (int o = 0; o < E_loc; ++o) {
+      const int po = part[o];
+      if (po == 0 || (po <= kStreamRows) != small) continue;
+      rank += E_loc <= 1024 ? (po > mine || (po == mine && o < le)) : (o < le);
     }
-    order[rank] = le;
+    order[(small ? n_big : 0) + rank] = le;
   }
   __syncthreads();
   n_full = min(n_full, max_mtiles);
-  n_part = min(n_part, max_mtiles - n_full);
-  const int n1 = (n_full + n_part) * nt1, n2 = (n_full + n_part) * nt2;
+  n_big = min(n_big, max_mtiles - n_full);
+  n_small = min(n_small, max_mtiles - n_full - n_big);
+  const int n_tiles = n_full + n_big + n_small;
+  const int n1 = n_tiles * nt1, n2 = n_tiles * nt2;
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     header[0] = n1;
     header[1] = P;
@@ -146,17 +166,36 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     const bool second = q >= n1;
     const int Nt = second ? nt2 : nt1;
     const int qq = second ? q - n1 : q;
+    // List order.  Classes: F = full tiles, B = big partial tiles, S = streaming partial tiles.
+    //   [ mixed chunks: each 32-item chunk holds 8 items of S, then 24 items of F, so that some CUs of every XCD
+    //     stream weights from HBM while the others multiply; only when S is at least half as large as F,
+    //     otherwise the few S items would just push full tiles into an extra round ]
+    //   [ rest of F ] [ B, largest first ] [ rest of S ]          -- the launch ends with its shortest items
+    const int nF = n_full * Nt, nS = n_small * Nt, nB = n_big * Nt;
+    constexpr int nsc = 8, nfc = kChunk - nsc;
+    const int n_mix = (nF > 0 && 2 * nS >= nF) ? min(nF / nfc, nS / nsc) : 0;
+    int cls, idx;  // class 0 = F, 1 = B, 2 = S; idx = position inside the class list
+    if (qq < n_mix * kChunk) {
+      const int c = qq / kChunk, sl = qq % kChunk;
+      if (sl < nsc) { cls = 2; idx = c * nsc + sl; } else { cls = 0; idx = c * nfc + (sl - nsc); }
+    } else {
+      int r = qq - n_mix * kChunk;
+      const int f_rem = nF - n_mix * nfc;
+      if (r < f_rem) { cls = 0; idx = n_mix * nfc + r; }
+      else if ((r -= f_rem) < nB) { cls = 1; idx = r; }
+      else { cls = 2; idx = n_mix * nsc + (r - nB); }
+    }
     int le, mt, nt, rows;
-    if (qq < n_full * Nt) {
-      // expert that owns list position qq: largest le with full0[le] * Nt <= qq
+    if (cls == 0) {
+      // expert that owns F position idx: largest le with full0[le] * Nt <= idx
       int a = 0, b = E_loc;
       while (b - a > 1) {
         const int mid = (a + b) >> 1;
-        if (full0[mid] * Nt <= qq) a = mid; else b = mid;
+        if (full0[mid] * Nt <= idx) a = mid; else b = mid;
       }
       le = a;
       const int Mt = full0[le + 1] - full0[le];
-      int r = qq - full0[le] * Nt;
+      int r = idx - full0[le] * Nt;
       // inside the expert: M groups of up to 8 tiles; inside an M group: N groups of 32 / (M tiles) tiles.
       // (A slab and B panel of a tile are equally large, so the bytes a chunk pulls into its L2 are smallest
       // when the chunk is close to square: 8 x 4 rather than 32 x 1.)
@@ -172,9 +211,8 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       nt = ng * G + r % Gcur;
       rows = bm;
     } else {
-      const int r = qq - n_full * Nt;
-      le = order[r / Nt];
-      nt = r % Nt;
+      le = order[(cls == 2 ? n_big : 0) + idx / Nt];
+      nt = idx % Nt;
       const int cnt = min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base);
       mt = cnt / bm;
       rows = part[le];
@@ -219,7 +257,7 @@ constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
 constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
 constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue patch (fits 8 x in the stages)
 
-template <bool GATED, int NB, int NA>
+template <bool GATED, int NB, int NA, int DEPTH>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
                                                int rows, int nblk_total) {
   const int tid = threadIdx.x;
@@ -243,49 +281,52 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   const unsigned char *b_src =
       static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
 
-  u32x4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
-  // R is moved in three portions: {ra0, ra1, rb0}, {ra2, ra3, rb1}, {rb2, rb3}
+  // Register slab sets.  Set x always exists; set y is used when DEPTH == 2 (two slabs in flight: tiles with at
+  // most 64 rows are pure weight streaming, their accumulators are small, and what limits them is the number of
+  // bytes a CU keeps in flight towards HBM).
+  u32x4 ra0x, ra1x, ra2x, ra3x, rb0x, rb1x, rb2x, rb3x;
+  u32x4 ra0y, ra1y, ra2y, ra3y, rb0y, rb1y, rb2y, rb3y;
+  // A slab is moved in three portions: {ra0, ra1, rb0}, {ra2, ra3, rb1}, {rb2, rb3}
   // k tail: a chunk past K is replaced by chunk 0 of the same row (valid memory, finite data); the packed B
   // tile is zero there, so it contributes nothing and no select has to wait on the load
 #define MOE355_A_OFF(KT) ((KT) * kBK + a_chunk * 8 < g.K ? (KT) * kBK : -a_chunk * 8)
   // NA = row loads per thread that reach valid rows (1: rows < 64, 2: rows < 128, 4: all); the others are skipped
-#define MOE355_LOAD_A01(KT)                                                                      \
-  do {                                                                                           \
-    ra0 = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + MOE355_A_OFF(KT));                  \
-    if (NA > 1) ra1 = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + MOE355_A_OFF(KT));      \
+#define MOE355_LOAD_P0(S, KT)                                                                       \
+  do {                                                                                              \
+    ra0##S = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + MOE355_A_OFF(KT));                  \
+    if (NA > 1) ra1##S = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + MOE355_A_OFF(KT));      \
+    rb0##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes);                   \
   } while (0)
-#define MOE355_LOAD_A23(KT)                                                                      \
-  do {                                                                                           \
-    if (NA > 2) ra2 = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + MOE355_A_OFF(KT));      \
-    if (NA > 2) ra3 = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + MOE355_A_OFF(KT));      \
+#define MOE355_LOAD_P1(S, KT)                                                                       \
+  do {                                                                                              \
+    if (NA > 2) ra2##S = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + MOE355_A_OFF(KT));      \
+    if (NA > 2) ra3##S = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + MOE355_A_OFF(KT));      \
+    rb1##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 8192);            \
   } while (0)
-#define MOE355_LOAD_B0(KT) rb0 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes)
-#define MOE355_LOAD_B1(KT) rb1 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 8192)
-#define MOE355_LOAD_B01(KT) do { MOE355_LOAD_B0(KT); MOE355_LOAD_B1(KT); } while (0)
-#define MOE355_LOAD_B23(KT)                                                                      \
-  do {                                                                                           \
-    rb2 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 16384);           \
-    rb3 = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 24576);           \
+#define MOE355_LOAD_P2(S, KT)                                                                       \
+  do {                                                                                              \
+    rb2##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 16384);           \
+    rb3##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 24576);           \
   } while (0)
-#define MOE355_STORE_P0(BUF)                                                                     \
-  do {                                                                                           \
-    unsigned char *s_ = smem + (BUF) * kStageBytes;                                              \
-    *reinterpret_cast<u32x4 *>(s_ + a_dst) = ra0;                                                \
-    if (NA > 1) *reinterpret_cast<u32x4 *>(s_ + a_dst + 8192) = ra1;                             \
-    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16) = rb0;                              \
+#define MOE355_STORE_P0(S, BUF)                                                                     \
+  do {                                                                                              \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                                 \
+    *reinterpret_cast<u32x4 *>(s_ + a_dst) = ra0##S;                                                \
+    if (NA > 1) *reinterpret_cast<u32x4 *>(s_ + a_dst + 8192) = ra1##S;                             \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16) = rb0##S;                              \
   } while (0)
-#define MOE355_STORE_P1(BUF)                                                                     \
-  do {                                                                                           \
-    unsigned char *s_ = smem + (BUF) * kStageBytes;                                              \
-    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 16384) = ra2;                            \
-    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 24576) = ra3;                            \
-    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 8192) = rb1;                       \
+#define MOE355_STORE_P1(S, BUF)                                                                     \
+  do {                                                                                              \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                                 \
+    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 16384) = ra2##S;                            \
+    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 24576) = ra3##S;                            \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 8192) = rb1##S;                       \
   } while (0)
-#define MOE355_STORE_P2(BUF)                                                                     \
-  do {                                                                                           \
-    unsigned char *s_ = smem + (BUF) * kStageBytes;                                              \
-    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 16384) = rb2;                      \
-    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 24576) = rb3;                      \
+#define MOE355_STORE_P2(S, BUF)                                                                     \
+  do {                                                                                              \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                                 \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 16384) = rb2##S;                      \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 24576) = rb3##S;                      \
   } while (0)
 
   f32x16 acc[NB > 0 ? NB : 1][2];
@@ -321,81 +362,87 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     }                                                                                                  \
   } while (0)
 
-  // Pipeline.  At the top of k-step kt: LDS stage kt & 1 holds slab kt, the registers R hold slab kt + 1 (its
-  // loads were issued one k-step ago, in three portions), and fa0 / fb0 hold the operands of substep 0.
-  // Substeps 0..2 each multiply, fetch the next substep's operands, move one portion of R into the other stage
-  // and reissue that portion's loads for slab kt + 2, so the global loads, the LDS stores and the LDS reads are
-  // all spread under the MFMAs instead of forming a burst around the barrier.  The single barrier sits before
-  // substep 3, whose operands are already in registers; substep 3 also fetches substep 0 of the next slab.
+  // Pipeline.  At the top of k-step kt: LDS stage kt & 1 holds slab kt, a register set holds slab kt + 1 (its
+  // loads were issued DEPTH k-steps ago, in three portions), and fa0 / fb0 hold the operands of substep 0.
+  // Substeps 0..2 each multiply, fetch the next substep's operands, move one portion of the register set into the
+  // other stage and reissue that portion's loads for slab kt + 1 + DEPTH, so the global loads, the LDS stores and
+  // the LDS reads are all spread under the MFMAs instead of forming a burst around the barrier.  The single
+  // barrier sits before substep 3, whose operands are already in registers; substep 3 also fetches substep 0 of
+  // the next slab.  Reloads past the last k-step repeat the last slab: in bounds, never used.
+  // Requested instruction order (sched_group_barrier masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read,
+  // 0x200 DS write).
+#define MOE355_ORDER(NW)                                                                                \
+  do {                                                                                                 \
+    if (NB > 0) {                                                                                      \
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);                                          \
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                          \
+    }                                                                                                  \
+    if ((NW) > 0) {                                                                                    \
+      __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                            \
+      __builtin_amdgcn_sched_group_barrier(0x020, (NW), 0);                                            \
+    }                                                                                                  \
+  } while (0)
+#define MOE355_KSTEP(S, KT_, KPRE)                                                                      \
+  do {                                                                                                 \
+    const unsigned char *sCur = smem + ((KT_) & 1) * kStageBytes;                                      \
+    const int nxt = ((KT_) & 1) ^ 1;                                                                   \
+    const int kp_ = min((KPRE), kt_last);                                                              \
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 1);                                                              \
+    MOE355_MFMAS(fa0, fb0);                                                                            \
+    MOE355_STORE_P0(S, nxt);                                                                           \
+    MOE355_LOAD_P0(S, kp_);                                                                            \
+    MOE355_READ_FRAGS(fa0, fb0, sCur, 2);                                                              \
+    MOE355_MFMAS(fa1, fb1);                                                                            \
+    MOE355_STORE_P1(S, nxt);                                                                           \
+    MOE355_LOAD_P1(S, kp_);                                                                            \
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 3);                                                              \
+    MOE355_MFMAS(fa0, fb0);                                                                            \
+    MOE355_STORE_P2(S, nxt);                                                                           \
+    MOE355_LOAD_P2(S, kp_);                                                                            \
+    MOE355_ORDER(NA > 1 ? 3 : 2);                                                                      \
+    MOE355_ORDER(NA > 2 ? 3 : 1);                                                                      \
+    MOE355_ORDER(2);                                                                                   \
+    __syncthreads();                                                                                   \
+    MOE355_READ_FRAGS(fa0, fb0, smem + nxt * kStageBytes, 0);                                          \
+    MOE355_MFMAS(fa1, fb1);                                                                            \
+    MOE355_ORDER(0);                                                                                   \
+  } while (0)
+
   const int KT = g.n_ktiles;
   const int kt_last = KT - 1;
-  MOE355_LOAD_A01(0); MOE355_LOAD_A23(0); MOE355_LOAD_B01(0); MOE355_LOAD_B23(0);
-  MOE355_STORE_P0(0); MOE355_STORE_P1(0); MOE355_STORE_P2(0);
+  MOE355_LOAD_P0(x, 0); MOE355_LOAD_P1(x, 0); MOE355_LOAD_P2(x, 0);
+  MOE355_STORE_P0(x, 0); MOE355_STORE_P1(x, 0); MOE355_STORE_P2(x, 0);
   {
-    const int k1 = min(1, kt_last);  // reloads past the last k-step repeat the last slab: in bounds, never used
-    MOE355_LOAD_A01(k1); MOE355_LOAD_A23(k1); MOE355_LOAD_B01(k1); MOE355_LOAD_B23(k1);
+    const int k1 = min(1, kt_last);
+    MOE355_LOAD_P0(x, k1); MOE355_LOAD_P1(x, k1); MOE355_LOAD_P2(x, k1);
+    if (DEPTH == 2) {
+      const int k2 = min(2, kt_last);
+      MOE355_LOAD_P0(y, k2); MOE355_LOAD_P1(y, k2); MOE355_LOAD_P2(y, k2);
+    }
   }
   __syncthreads();
   MOE355_READ_FRAGS(fa0, fb0, smem, 0);
 
-  for (int kt = 0; kt < KT; ++kt) {
-    const unsigned char *sCur = smem + (kt & 1) * kStageBytes;
-    const int nxt = (kt & 1) ^ 1;
-    const int k2 = min(kt + 2, kt_last);
-    // substep 0
-    MOE355_READ_FRAGS(fa1, fb1, sCur, 1);
-    MOE355_MFMAS(fa0, fb0);
-    MOE355_STORE_P0(nxt);
-    MOE355_LOAD_A01(k2); MOE355_LOAD_B0(k2);
-    // substep 1
-    MOE355_READ_FRAGS(fa0, fb0, sCur, 2);
-    MOE355_MFMAS(fa1, fb1);
-    MOE355_STORE_P1(nxt);
-    MOE355_LOAD_A23(k2); MOE355_LOAD_B1(k2);
-    // substep 2
-    MOE355_READ_FRAGS(fa1, fb1, sCur, 3);
-    MOE355_MFMAS(fa0, fb0);
-    MOE355_STORE_P2(nxt);
-    MOE355_LOAD_B23(k2);
-    // requested instruction order (masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read, 0x200 DS write)
-    if (NB > 0) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x200, NA > 1 ? 3 : 2, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, NA > 1 ? 3 : 2, 0);
-    if (NB > 0) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x200, NA > 2 ? 3 : 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, NA > 2 ? 3 : 1, 0);
-    if (NB > 0) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(0x200, 2, 0);
-    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
-    __syncthreads();
-    // substep 3, and substep 0 operands of the next slab
-    MOE355_READ_FRAGS(fa0, fb0, smem + nxt * kStageBytes, 0);
-    MOE355_MFMAS(fa1, fb1);
-    if (NB > 0) {
-      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);
+  if (DEPTH == 1) {
+    for (int kt = 0; kt < KT; ++kt) MOE355_KSTEP(x, kt, kt + 2);
+  } else {
+    // set x carries the odd slabs, set y the even ones
+    for (int kt = 0; kt < KT; kt += 2) {
+      MOE355_KSTEP(x, kt, kt + 3);
+      if (kt + 1 < KT) MOE355_KSTEP(y, kt + 1, kt + 4);
     }
   }
+#undef MOE355_KSTEP
+#undef MOE355_ORDER
 #undef MOE355_READ_FRAGS
 #undef MOE355_MFMAS
-#undef MOE355_LOAD_A01
-#undef MOE355_LOAD_A23
-#undef MOE355_LOAD_B0
-#undef MOE355_LOAD_B1
-#undef MOE355_LOAD_B01
-#undef MOE355_LOAD_B23
+#undef MOE355_LOAD_P0
+#undef MOE355_LOAD_P1
+#undef MOE355_LOAD_P2
 #undef MOE355_STORE_P0
 #undef MOE355_STORE_P1
 #undef MOE355_STORE_P2
+#undef MOE355_A_OFF
 
   // ---- epilogue ----
   // Accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block, i.e. a lane
@@ -458,15 +505,15 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 template <bool GATED>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  const int q = chunked_item(blockIdx.x);
-  if (q >= *g.n_items) return;
+  const int q = chunked_item(blockIdx.x, *g.n_items);
+  if (q < 0) return;
   const int4 item = g.work[q];
   const int le = item.x, m0 = item.y, rows = item.z, nt = item.w;
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
   // wave-uniform dispatch: every variant executes the same sequence of barriers
-#define MOE355_TILE(NB_, NA_) gemm_bf16_tile<GATED, NB_, NA_>(g, smem, nt, le, m0, rows, nblk_total)
+#define MOE355_TILE(NB_, NA_) gemm_bf16_tile<GATED, NB_, NA_, (NA_ == 1 ? 2 : 1)>(g, smem, nt, le, m0, rows, nblk_total)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -486,8 +533,8 @@ template <bool GATED>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
   __shared__ float sA[kFBM][kFBK + 1];
   __shared__ float sB[GATED ? 2 : 1][kFBK][kFBN];
-  const int q = chunked_item(blockIdx.x);
-  if (q >= *g.n_items) return;
+  const int q = chunked_item(blockIdx.x, *g.n_items);
+  if (q < 0) return;
   const int4 item = g.work[q];
   const int le = item.x, m0 = item.y, rows = item.z, nt = item.w;
   const int tid = threadIdx.x;
