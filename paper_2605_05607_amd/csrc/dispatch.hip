@@ -2,14 +2,14 @@
 // algebraic<->layout row maps (AL Table of Sec. III-D; token id list per tile of Sec. IV-B) and the table of
 // distinct (token, rank) pairs (the redundancy of Sec. II-B; rank(e) = e / experts_per_rank, Sec. III-D).
 //
-// Three small kernels, no atomics on device memory, so the result does not depend on scheduling:
+// Two small kernels, no atomics on device memory, so the result does not depend on scheduling:
 //   1. hist : the token range is cut into <= 64 chunks, one wave per chunk counts its pairs per expert and
 //             its first-of-rank pairs per rank (LDS counters);
-//   2. scan : per expert, an exclusive wave scan across the chunks (lane = chunk) gives each chunk its
-//             starting cursor; a block scan across experts gives offsets;
-//   3. place: each wave walks its chunk again in pair order; lanes holding the same expert are found with
-//             one ballot per bit of the expert id, the popcount of the lower lanes is the rank inside the
-//             group, and the highest lane of the group advances the LDS cursor.
+//   2. place: every block first sums the chunk histograms (all chunks -> counts, earlier chunks -> its own
+//             starting cursors) and scans the counts across experts into offsets (block 0 writes them out);
+//             then its first wave walks the chunk again in pair order: lanes holding the same expert are
+//             found with one ballot per bit of the expert id, the popcount of the lower lanes is the rank
+//             inside the group, and the highest lane of the group advances the LDS cursor.
 #include "common.h"
 
 namespace moe355 {
@@ -22,15 +22,23 @@ struct PairLane {
 };
 
 // Lane -> pair assignment of one iteration: floor(64 / k) whole tokens, slot-major inside a token.
-__device__ __forceinline__ PairLane load_pair(const int32_t *__restrict__ topk_idx, int t0, int t_end, int k,
-                                              int tpi, int E, int epr) {
+__device__ __forceinline__ int load_expert(const int32_t *__restrict__ topk_idx, int t0, int t_end, int k, int tpi) {
+  const int lane = lane_id();
+  const int tl = lane / k;
+  const int t = t0 + tl;
+  return (tl < tpi && t < t_end) ? topk_idx[(size_t)t * k + (lane - tl * k)] : -1;
+}
+
+// `e` is this lane's expert id as returned by load_expert for the same t0 (fetched one iteration ahead so that
+// the walk does not wait on global memory every 64 pairs).
+__device__ __forceinline__ PairLane make_pair(int e, int t0, int t_end, int k, int tpi, int E, int epr) {
   PairLane p;
   const int lane = lane_id();
   const int tl = lane / k;
   p.j = lane - tl * k;
   p.t = t0 + tl;
   p.active = tl < tpi && p.t < t_end;
-  p.e = p.active ? topk_idx[(size_t)p.t * k + p.j] : -1;
+  p.e = p.active ? e : -1;
   p.valid = p.active && p.e >= 0 && p.e < E;
   p.r = p.valid ? p.e / epr : -1;
   return p;
@@ -72,8 +80,10 @@ __global__ __launch_bounds__(kWave) void dispatch_hist_kernel(const int32_t *__r
   const int tpi = kWave / k;
   const int t_begin = c * tpc;
   const int t_end = min(T, t_begin + tpc);
+  int e_next = load_expert(topk_idx, t_begin, t_end, k, tpi);
   for (int t0 = t_begin; t0 < t_end; t0 += tpi) {
-    const PairLane p = load_pair(topk_idx, t0, t_end, k, tpi, E, epr);
+    const PairLane p = make_pair(e_next, t0, t_end, k, tpi, E, epr);
+    e_next = load_expert(topk_idx, t0 + tpi, t_end, k, tpi);
     const uint32_t slots = same_rank_slots(p, k);
     if (p.valid) {
       atomicAdd(&cnt[p.e], 1);
@@ -81,37 +91,55 @@ __global__ __launch_bounds__(kWave) void dispatch_hist_kernel(const int32_t *__r
     }
   }
   __syncthreads();
-  for (int i = lane; i < E; i += kWave) chunk_cnt[(size_t)c * E + i] = cnt[i];
-  for (int i = lane; i < R; i += kWave) chunk_rcnt[(size_t)c * R + i] = rcnt[i];
+  // histograms are stored expert-major ([expert][chunk]) so that the placement kernel reads one expert's 64
+  // chunk counts as one contiguous 256-byte run
+  for (int i = lane; i < E; i += kWave) chunk_cnt[(size_t)i * kMaxChunks + c] = cnt[i];
+  for (int i = lane; i < R; i += kWave) chunk_rcnt[(size_t)i * kMaxChunks + c] = rcnt[i];
 }
 
-__global__ __launch_bounds__(1024) void dispatch_scan_kernel(int nch, int E, int R, int32_t *__restrict__ chunk_cnt,
-                                                             int32_t *__restrict__ chunk_rcnt,
-                                                             int32_t *__restrict__ counts,
-                                                             int32_t *__restrict__ offsets,
-                                                             int32_t *__restrict__ rank_counts,
-                                                             int32_t *__restrict__ rank_offsets) {
+constexpr int kPlaceThreads = 256;
+
+__global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(
+    const int32_t *__restrict__ topk_idx, int T, int E, int k, int R, int tpc, int nch, int ebits, int rbits,
+    const int32_t *__restrict__ chunk_cnt, const int32_t *__restrict__ chunk_rcnt, int32_t *__restrict__ counts,
+    int32_t *__restrict__ offsets, int32_t *__restrict__ rank_counts, int32_t *__restrict__ rank_offsets,
+    int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm, int32_t *__restrict__ dedup_tok,
+    uint32_t *__restrict__ dedup_mask, int32_t *__restrict__ pair_to_dedup) {
   extern __shared__ int sm[];
-  int *tot = sm;            // [E]
-  int *rtot = sm + E;       // [R]
-  int *scratch = rtot + R;  // [17]
+  int *cursor = sm;            // [E] next free layout row of each expert for this chunk
+  int *rcursor = sm + E;       // [R] next free dedup entry of each rank for this chunk
+  int *tot = rcursor + R;      // [E + R] totals over all chunks
+  int *scratch = tot + E + R;  // [17]
   const int lane = lane_id();
-  const int wave = threadIdx.x >> 6;
-  const int nwaves = blockDim.x >> 6;
-  // across chunks: exclusive scan per expert / per rank, lane = chunk
-  for (int e = wave; e < E + R; e += nwaves) {
-    int32_t *col = e < E ? chunk_cnt + e : chunk_rcnt + (e - E);
-    const int stride = e < E ? E : R;
-    const int v = lane < nch ? col[(size_t)lane * stride] : 0;
-    const int inc = wave_inclusive_scan(v);
-    if (lane < nch) col[(size_t)lane * stride] = inc - v;
-    if (lane == 63) sm[e] = inc;
+  const int c = blockIdx.x;
+  // per expert / rank: total over all chunks and the part that belongs to earlier chunks
+  for (int i = threadIdx.x; i < E + R; i += blockDim.x) {
+    const int4 *row = reinterpret_cast<const int4 *>(i < E ? chunk_cnt + (size_t)i * kMaxChunks
+                                                           : chunk_rcnt + (size_t)(i - E) * kMaxChunks);
+    int4 v[kMaxChunks / 4];
+#pragma unroll
+    for (int q = 0; q < kMaxChunks / 4; ++q) v[q] = row[q];  // 16 independent 16-byte loads
+    int total = 0, before = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxChunks / 4; ++q) {
+      const int vals[4] = {v[q].x, v[q].y, v[q].z, v[q].w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int cc = q * 4 + u;
+        const int val = cc < nch ? vals[u] : 0;  // slots of chunks that do not exist hold stale workspace bytes
+        total += val;
+        before += cc < c ? val : 0;
+      }
+    }
+    tot[i] = total;
+    sm[i] = before;
   }
   __syncthreads();
-  // across experts, then across ranks: each thread owns a run of consecutive items
+  // exclusive scan of the totals across experts, then across ranks: each thread owns a run of consecutive items
   for (int pass = 0; pass < 2; ++pass) {
     const int n = pass == 0 ? E : R;
-    const int *src = pass == 0 ? tot : rtot;
+    const int *src = pass == 0 ? tot : tot + E;
+    int *cur = pass == 0 ? cursor : rcursor;
     int32_t *cnt_out = pass == 0 ? counts : rank_counts;
     int32_t *off_out = pass == 0 ? offsets : rank_offsets;
     const int ipt = (n + blockDim.x - 1) / blockDim.x;
@@ -123,29 +151,17 @@ __global__ __launch_bounds__(1024) void dispatch_scan_kernel(int nch, int E, int
     int run = block_exclusive_scan(local, scratch, &total);
     for (int i = lo; i < hi; ++i) {
       const int v = src[i];
-      cnt_out[i] = v;
-      off_out[i] = run;
+      if (c == 0) {
+        cnt_out[i] = v;
+        off_out[i] = run;
+      }
+      cur[i] += run;
       run += v;
     }
-    if (threadIdx.x == 0) off_out[n] = total;
+    if (c == 0 && threadIdx.x == 0) off_out[n] = total;
     __syncthreads();
   }
-}
-
-__global__ __launch_bounds__(kWave) void dispatch_place_kernel(
-    const int32_t *__restrict__ topk_idx, int T, int E, int k, int R, int tpc, int ebits, int rbits,
-    const int32_t *__restrict__ chunk_cnt, const int32_t *__restrict__ chunk_rcnt,
-    const int32_t *__restrict__ offsets, const int32_t *__restrict__ rank_offsets, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv_perm, int32_t *__restrict__ dedup_tok, uint32_t *__restrict__ dedup_mask,
-    int32_t *__restrict__ pair_to_dedup) {
-  extern __shared__ int sm[];
-  int *cursor = sm;       // [E] next free layout row of each expert for this chunk
-  int *rcursor = sm + E;  // [R] next free dedup entry of each rank for this chunk
-  const int lane = lane_id();
-  const int c = blockIdx.x;
-  for (int i = lane; i < E; i += kWave) cursor[i] = offsets[i] + chunk_cnt[(size_t)c * E + i];
-  for (int i = lane; i < R; i += kWave) rcursor[i] = rank_offsets[i] + chunk_rcnt[(size_t)c * R + i];
-  __syncthreads();
+  if (threadIdx.x >= kWave) return;  // the placement walk is a single-wave job; no block barrier below
   const int epr = E / R;
   const int tpi = kWave / k;
   const int t_begin = c * tpc;
@@ -153,15 +169,18 @@ __global__ __launch_bounds__(kWave) void dispatch_place_kernel(
   const unsigned long long lower = lane == 0 ? 0ull : (~0ull >> (64 - lane));
   const long long npairs = (long long)T * k;
   const long long ndedup = (long long)T * min(k, R);
+  int e_next = load_expert(topk_idx, t_begin, t_end, k, tpi);
   for (int t0 = t_begin; t0 < t_end; t0 += tpi) {
-    const PairLane p = load_pair(topk_idx, t0, t_end, k, tpi, E, epr);
+    const PairLane p = make_pair(e_next, t0, t_end, k, tpi, E, epr);
+    e_next = load_expert(topk_idx, t0 + tpi, t_end, k, tpi);
     const size_t pid = (size_t)p.t * k + p.j;
 
     // ---- layout row of every pair (stable: lower lanes are earlier pairs) ----
     const unsigned long long grp = match_lanes(p.valid, p.e, ebits);
     int row = -1;
     if (p.valid) row = cursor[p.e] + __popcll(grp & lower);
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     if (p.valid && (lane == 63 || (grp >> (lane + 1)) == 0)) cursor[p.e] = row + 1;
     if (p.active) inv_perm[pid] = row;
     if (p.valid && row >= 0 && row < npairs) perm[row] = (int32_t)pid;
@@ -172,7 +191,8 @@ __global__ __launch_bounds__(kWave) void dispatch_place_kernel(
     const unsigned long long rgrp = match_lanes(first, p.r, rbits);
     int pos = -1;
     if (first) pos = rcursor[p.r] + __popcll(rgrp & lower);
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     if (first && (lane == 63 || (rgrp >> (lane + 1)) == 0)) rcursor[p.r] = pos + 1;
     if (first && pos >= 0 && pos < ndedup) {
       dedup_tok[pos] = p.t;
@@ -181,7 +201,8 @@ __global__ __launch_bounds__(kWave) void dispatch_place_kernel(
     const int first_slot = slots ? __builtin_ctz(slots) : 0;
     const int pos_of_first = __shfl(pos, (lane - p.j + first_slot) & 63, 64);
     if (p.active) pair_to_dedup[pid] = p.valid ? pos_of_first : -1;
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
@@ -227,17 +248,14 @@ extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_id
                        chunk_cnt, chunk_rcnt);
     if ((rc = launch_status()) != MOE_OK) return rc;
   }
-  hipLaunchKernelGGL(dispatch_scan_kernel, dim3(1), dim3(1024), sm_wave + 17 * sizeof(int), st, nch, E, R, chunk_cnt,
-                     chunk_rcnt, out->counts, out->offsets, out->rank_counts, out->rank_offsets);
+  int ebits = 0, rbits = 0;
+  while ((1 << ebits) < E) ++ebits;
+  while ((1 << rbits) < R) ++rbits;
+  // with T == 0 a single block still writes the all-zero counts and offsets
+  hipLaunchKernelGGL(dispatch_place_kernel, dim3(nch > 0 ? nch : 1), dim3(kPlaceThreads),
+                     (size_t)(2 * (E + R) + 17) * sizeof(int), st, topk_idx, T, E, k, R, tpc, nch, ebits, rbits, chunk_cnt,
+                     chunk_rcnt, out->counts, out->offsets, out->rank_counts, out->rank_offsets, out->perm,
+                     out->inv_perm, out->dedup_tok, out->dedup_mask, out->pair_to_dedup);
   if ((rc = launch_status()) != MOE_OK) return rc;
-  if (nch > 0) {
-    int ebits = 0, rbits = 0;
-    while ((1 << ebits) < E) ++ebits;
-    while ((1 << rbits) < R) ++rbits;
-    hipLaunchKernelGGL(dispatch_place_kernel, dim3(nch), dim3(kWave), sm_wave, st, topk_idx, T, E, k, R, tpc, ebits,
-                       rbits, chunk_cnt, chunk_rcnt, out->offsets, out->rank_offsets, out->perm, out->inv_perm,
-                       out->dedup_tok, out->dedup_mask, out->pair_to_dedup);
-    if ((rc = launch_status()) != MOE_OK) return rc;
-  }
   return MOE_OK;
 }
