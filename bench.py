@@ -202,6 +202,36 @@ def main():
         "combine_phase": {"hbm_gbs": cb["bytes"] / (cb_ms * 1e-3) / 1e9,
                           "hbm_frac_of_peak": cb["bytes"] / (cb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    # ---- untimed extras: Dispatch and Combine on their own (phase-split entry points) and the unfused path ----
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    b = 2 if cfg.dtype == wl.BF16 else 4
+    P_cap = cfg.T * min(cfg.k, cfg.E_loc)
+    xs = torch.empty((P_cap, cfg.d), dtype=lay.elt_dtype, device="cuda")
+    t_disp = timed(lambda: B.moe_dispatch_gather(lay.shape, x, lay.tables, xs), 20)
+    disp_bytes = U_tok * cfg.d * b + P * cfg.d * b  # each needed token row read once, every layout row written
+    out["dispatch_phase"] = {"entry": "moe_dispatch_gather", "ms": t_disp, "hbm_gbs": disp_bytes / (t_disp * 1e-3) / 1e9,
+                             "hbm_frac_of_peak": disp_bytes / (t_disp * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "bytes": disp_bytes, "bytes_without_dedup": 2 * P * cfg.d * b}
+    del xs
+    lay_u = L.MoELayer(cfg, unfused=True)
+    lay_u.packed_gate_up, lay_u.packed_down = lay.packed_gate_up, lay.packed_down
+    lay_u.route(lg)
+    lay_u.build_dispatch()
+    t_unf = timed(lambda: lay_u.forward_unfused(x), 5)
+    t_fus = timed(lambda: lay.forward(x), 5)
+    out["unfused_comparison"] = {"fused_forward_ms": t_fus, "unfused_forward_ms": t_unf,
+                                 "note": "unfused = gather copy + same grouped GEMMs + fp32 atomic scatter-add + cast"}
+    del lay_u
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w)
     print(json.dumps(out))
