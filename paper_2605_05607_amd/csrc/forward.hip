@@ -174,6 +174,8 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     const int nF = n_full * Nt, nS = n_small * Nt, nB = n_big * Nt;
     constexpr int nsc = 8, nfc = kChunk - nsc;
     const int n_mix = (nF > 0 && 2 * nS >= nF) ? min(nF / nfc, nS / nsc) : 0;
+    // F items that share operands form groups of gsz consecutive list positions; gsz follows the F share of a chunk
+    const int gsz = n_mix > 0 ? nfc : kChunk;
     int cls, idx;  // class 0 = F, 1 = B, 2 = S; idx = position inside the class list
     if (qq < n_mix * kChunk) {
       const int c = qq / kChunk, sl = qq % kChunk;
@@ -196,14 +198,14 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       le = a;
       const int Mt = full0[le + 1] - full0[le];
       int r = idx - full0[le] * Nt;
-      // inside the expert: M groups of up to 8 tiles; inside an M group: N groups of 32 / (M tiles) tiles.
+      // inside the expert: M groups of up to 8 tiles; inside an M group: N groups of gsz / (M tiles) tiles.
       // (A slab and B panel of a tile are equally large, so the bytes a chunk pulls into its L2 are smallest
       // when the chunk is close to square: 8 x 4 rather than 32 x 1.)
       const int Mg = min(Mt, kChunkM);
       const int mg = r / (Mg * Nt);
       r -= mg * Mg * Nt;
       const int Mcur = min(Mg, Mt - mg * Mg);
-      const int G = max(1, kChunk / Mcur);
+      const int G = max(1, gsz / Mcur);
       const int ng = r / (Mcur * G);
       r -= ng * Mcur * G;
       const int Gcur = min(G, Nt - ng * G);
