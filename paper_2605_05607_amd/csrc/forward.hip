@@ -880,6 +880,8 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MOE_ERR_INVALID_ARG;
   if ((int64_t)dv.max_mtiles * std::max(dv.nt1, dv.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
+  // the GEMM kernels address A rows with 32-bit element offsets (row * row length)
+  if (std::max<int64_t>(shape->T, dv.P_cap) * std::max(shape->d, shape->f) >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
   if (shape->T == 0) return MOE_OK;
   hipStream_t st = (hipStream_t)stream;
   begin_launches();

@@ -59,6 +59,16 @@ def test_unsupported_dtype_and_extent():
         == B.MOE_ERR_UNSUPPORTED
 
 
+def test_forward_rejects_extents_beyond_32bit_row_offsets():
+    lib = B.lib()
+    s = good_shape(T=1 << 20, d=8192, f=8192, k=2)
+    tb = B.moe_dispatch(*([4096] * 9))
+    need = B.moe_forward_workspace_bytes(s)
+    assert need > 0
+    assert lib.moe_fused_forward(C.byref(s), 4096, 4096, 4096, C.byref(tb), 4096, 4096, 4096, 4096, need, None) \
+        == B.MOE_ERR_UNSUPPORTED
+
+
 def test_null_pointers_and_small_workspace():
     lib = B.lib()
     s = good_shape()
