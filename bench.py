@@ -199,8 +199,6 @@ def main():
                        "hbm_frac_of_peak": (g1["bytes"] + g2["bytes"]) / ((g1_ms + g2_ms) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "mfma_ceiling_if_hbm_bound": min(1.0, (g1["flops"] + g2["flops"]) / (MFMA_BF16_PEAK_TF * 1e12)
                                                         / ((g1["bytes"] + g2["bytes"]) / (HBM_PEAK_GBS * 1e9)))},
-        "combine_phase": {"hbm_gbs": cb["bytes"] / (cb_ms * 1e-3) / 1e9,
-                          "hbm_frac_of_peak": cb["bytes"] / (cb_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
     # ---- untimed extras: Dispatch and Combine on their own (phase-split entry points) and the unfused path ----
     def timed(fn, reps):
@@ -223,6 +221,30 @@ def main():
                              "hbm_frac_of_peak": disp_bytes / (t_disp * 1e-3) / 1e9 / HBM_PEAK_GBS,
                              "bytes": disp_bytes, "bytes_without_dedup": 2 * P * cfg.d * b}
     del xs
+    # Combine on its own: every weighted row read, every token row written.  (Inside the fused call GEMM-2 writes
+    # the rows of tokens with a single local slot itself, so the fused combine kernel moves less than this.)
+    # Timed twice: on one buffer (rows partly resident in the 256 MB Infinity Cache, as they are right after GEMM-2
+    # wrote them) and rotating over buffers whose live rows together exceed that cache (every read from HBM).
+    live = max(1, P) * cfg.d * 4
+    nbuf = max(2, min(8, -(-(768 << 20) // live)))
+    bufs = [torch.randn((max(1, P), cfg.d), dtype=torch.float32, device="cuda") for _ in range(nbuf)]
+    y2 = torch.empty_like(lay.y)
+    t_warm = timed(lambda: B.moe_combine_reduce(lay.shape, bufs[0], lay.topk_idx, lay.tables, y2), 20)
+    turn = [0]
+
+    def combine_next():
+        turn[0] = (turn[0] + 1) % nbuf
+        B.moe_combine_reduce(lay.shape, bufs[turn[0]], lay.topk_idx, lay.tables, y2)
+
+    t_comb = timed(combine_next, 4 * nbuf)
+    out["combine_phase"] = {"entry": "moe_combine_reduce", "ms": t_comb, "bytes": cb["bytes"],
+                            "hbm_gbs": cb["bytes"] / (t_comb * 1e-3) / 1e9,
+                            "hbm_frac_of_peak": cb["bytes"] / (t_comb * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "ms_same_buffer": t_warm,
+                            "hbm_frac_of_peak_same_buffer": cb["bytes"] / (t_warm * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "buffers_rotated": nbuf}
+    del bufs
+    del y2
     lay_u = L.MoELayer(cfg, unfused=True)
     lay_u.packed_gate_up, lay_u.packed_down = lay.packed_gate_up, lay.packed_down
     lay_u.route(lg)

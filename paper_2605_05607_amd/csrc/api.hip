@@ -43,6 +43,7 @@ FwdLayout forward_layout(const moe_shape *s, const Derived &dv) {
   L.work2 = take((size_t)dv.max_mtiles * dv.nt2 * 4 * sizeof(int32_t));
   L.row_tok = take(rows * sizeof(int32_t));
   L.row_w = take(rows * sizeof(float));
+  L.row_sole = take(rows * sizeof(int32_t));
   L.h = take(rows * (size_t)s->f * dv.elt);
   L.o = take(rows * (size_t)s->d * sizeof(float));
   L.total = off;

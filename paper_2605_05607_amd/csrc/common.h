@@ -53,6 +53,7 @@ struct FwdLayout {
   size_t work2;     // int4[max_mtiles * nt2]
   size_t row_tok;   // int32[P_cap]       token of each local row
   size_t row_w;     // float[P_cap]       gate weight of each local row
+  size_t row_sole;  // int32[P_cap]       the row's token if it is that token's only local slot, else -1
   size_t h;         // elt  [P_cap, f]
   size_t o;         // float[P_cap, d]
   size_t total;

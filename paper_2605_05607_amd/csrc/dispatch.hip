@@ -3,13 +3,17 @@
 // distinct (token, rank) pairs (the redundancy of Sec. II-B; rank(e) = e / experts_per_rank, Sec. III-D).
 //
 // Two small kernels, no atomics on device memory, so the result does not depend on scheduling:
-//   1. hist : the token range is cut into <= 64 chunks, one wave per chunk counts its pairs per expert and
+//   1. hist : the token range is cut into <= 64 chunks, one block per chunk counts its pairs per expert and
 //             its first-of-rank pairs per rank (LDS counters);
 //   2. place: every block first sums the chunk histograms (all chunks -> counts, earlier chunks -> its own
-//             starting cursors) and scans the counts across experts into offsets (block 0 writes them out);
-//             then its first wave walks the chunk again in pair order: lanes holding the same expert are
-//             found with one ballot per bit of the expert id, the popcount of the lower lanes is the rank
-//             inside the group, and the highest lane of the group advances the LDS cursor.
+//             starting cursors) and scans the counts across experts into offsets (block 0 writes them out).
+//             The chunk is cut once more into one contiguous token range per wave; a count of those ranges
+//             (LDS) turns the chunk cursors into per-wave cursors, and every wave then walks its range in pair
+//             order: lanes holding the same expert are found with one ballot per bit of the expert id, the
+//             popcount of the lower lanes is the rank inside the group, and the highest lane of the group
+//             advances the wave's LDS cursor.
+#include <algorithm>
+
 #include "common.h"
 
 namespace moe355 {
@@ -22,6 +26,8 @@ struct PairLane {
 };
 
 // Lane -> pair assignment of one iteration: floor(64 / k) whole tokens, slot-major inside a token.
+__device__ __forceinline__ int ceil_div_dev(int a, int b) { return (a + b - 1) / b; }
+
 __device__ __forceinline__ int load_expert(const int32_t *__restrict__ topk_idx, int t0, int t_end, int k, int tpi) {
   const int lane = lane_id();
   const int tl = lane / k;
@@ -66,20 +72,11 @@ __device__ __forceinline__ unsigned long long match_lanes(bool pred, int key, in
   return m;
 }
 
-__global__ __launch_bounds__(kWave) void dispatch_hist_kernel(const int32_t *__restrict__ topk_idx, int T, int E,
-                                                              int k, int R, int tpc, int32_t *__restrict__ chunk_cnt,
-                                                              int32_t *__restrict__ chunk_rcnt) {
-  extern __shared__ int sm[];
-  int *cnt = sm;
-  int *rcnt = sm + E;
-  const int lane = lane_id();
-  const int c = blockIdx.x;
-  for (int i = lane; i < E + R; i += kWave) sm[i] = 0;
-  __syncthreads();
-  const int epr = E / R;
+// Adds the pairs of tokens [t_begin, t_end) to the LDS counters cnt[E] / rcnt[R] (one wave; the counters may
+// be shared with other waves).
+__device__ __forceinline__ void count_range(const int32_t *__restrict__ topk_idx, int t_begin, int t_end, int k,
+                                            int E, int epr, int *cnt, int *rcnt) {
   const int tpi = kWave / k;
-  const int t_begin = c * tpc;
-  const int t_end = min(T, t_begin + tpc);
   int e_next = load_expert(topk_idx, t_begin, t_end, k, tpi);
   for (int t0 = t_begin; t0 < t_end; t0 += tpi) {
     const PairLane p = make_pair(e_next, t0, t_end, k, tpi, E, epr);
@@ -90,17 +87,35 @@ __global__ __launch_bounds__(kWave) void dispatch_hist_kernel(const int32_t *__r
       if ((slots & ((1u << p.j) - 1u)) == 0) atomicAdd(&rcnt[p.r], 1);  // first slot of its (token, rank)
     }
   }
+}
+
+constexpr int kTableThreads = 512;  // block size of both kernels
+
+__global__ __launch_bounds__(kTableThreads) void dispatch_hist_kernel(const int32_t *__restrict__ topk_idx, int T,
+                                                                      int E, int k, int R, int tpc,
+                                                                      int32_t *__restrict__ chunk_cnt,
+                                                                      int32_t *__restrict__ chunk_rcnt) {
+  extern __shared__ int sm[];
+  int *cnt = sm;
+  int *rcnt = sm + E;
+  const int c = blockIdx.x;
+  const int wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+  for (int i = threadIdx.x; i < E + R; i += blockDim.x) sm[i] = 0;
+  __syncthreads();
+  const int t_begin = c * tpc;
+  const int t_end = min(T, t_begin + tpc);
+  const int tpw = ceil_div_dev(tpc, nwaves);
+  count_range(topk_idx, min(t_end, t_begin + wave * tpw), min(t_end, t_begin + (wave + 1) * tpw), k, E, E / R, cnt,
+              rcnt);
   __syncthreads();
   // histograms are stored expert-major ([expert][chunk]) so that the placement kernel reads one expert's 64
   // chunk counts as one contiguous 256-byte run
-  for (int i = lane; i < E; i += kWave) chunk_cnt[(size_t)i * kMaxChunks + c] = cnt[i];
-  for (int i = lane; i < R; i += kWave) chunk_rcnt[(size_t)i * kMaxChunks + c] = rcnt[i];
+  for (int i = threadIdx.x; i < E; i += blockDim.x) chunk_cnt[(size_t)i * kMaxChunks + c] = cnt[i];
+  for (int i = threadIdx.x; i < R; i += blockDim.x) chunk_rcnt[(size_t)i * kMaxChunks + c] = rcnt[i];
 }
 
-constexpr int kPlaceThreads = 256;
-
-__global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(
-    const int32_t *__restrict__ topk_idx, int T, int E, int k, int R, int tpc, int nch, int ebits, int rbits,
+__global__ __launch_bounds__(kTableThreads) void dispatch_place_kernel(
+    const int32_t *__restrict__ topk_idx, int T, int E, int k, int R, int tpc, int nch, int ebits, int rbits, int nwalk,
     const int32_t *__restrict__ chunk_cnt, const int32_t *__restrict__ chunk_rcnt, int32_t *__restrict__ counts,
     int32_t *__restrict__ offsets, int32_t *__restrict__ rank_counts, int32_t *__restrict__ rank_offsets,
     int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm, int32_t *__restrict__ dedup_tok,
@@ -110,8 +125,20 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(
   int *rcursor = sm + E;       // [R] next free dedup entry of each rank for this chunk
   int *tot = rcursor + R;      // [E + R] totals over all chunks
   int *scratch = tot + E + R;  // [17]
+  int *sub = scratch + 17;     // [nwalk][E + R] per walking wave: pair counts of its token range, then its cursors
   const int lane = lane_id();
+  const int wave = threadIdx.x >> 6;
   const int c = blockIdx.x;
+  const int epr = E / R;
+  // token range of this wave inside the chunk (waves >= nwalk only help with the tables)
+  const int chunk_begin = c * tpc;
+  const int chunk_end = min(T, chunk_begin + tpc);
+  const int tpw = ceil_div_dev(tpc, nwalk);
+  const int t_begin = min(chunk_end, chunk_begin + min(wave, nwalk) * tpw);
+  const int t_end = wave < nwalk ? min(chunk_end, t_begin + tpw) : t_begin;
+  for (int i = threadIdx.x; i < nwalk * (E + R); i += blockDim.x) sub[i] = 0;
+  __syncthreads();
+  if (wave < nwalk) count_range(topk_idx, t_begin, t_end, k, E, epr, sub + wave * (E + R), sub + wave * (E + R) + E);
   // per expert / rank: total over all chunks and the part that belongs to earlier chunks
   for (int i = threadIdx.x; i < E + R; i += blockDim.x) {
     const int4 *row = reinterpret_cast<const int4 *>(i < E ? chunk_cnt + (size_t)i * kMaxChunks
@@ -161,11 +188,20 @@ __global__ __launch_bounds__(kPlaceThreads) void dispatch_place_kernel(
     if (c == 0 && threadIdx.x == 0) off_out[n] = total;
     __syncthreads();
   }
-  if (threadIdx.x >= kWave) return;  // the placement walk is a single-wave job; no block barrier below
-  const int epr = E / R;
+  // chunk cursors -> per-wave cursors: wave w starts where the waves before it end
+  for (int i = threadIdx.x; i < E + R; i += blockDim.x) {
+    int run = sm[i];
+    for (int w = 0; w < nwalk; ++w) {
+      const int v = sub[w * (E + R) + i];
+      sub[w * (E + R) + i] = run;
+      run += v;
+    }
+  }
+  __syncthreads();
+  if (wave >= nwalk) return;  // each walk is a single-wave job; no block barrier below
+  cursor = sub + wave * (E + R);
+  rcursor = cursor + E;
   const int tpi = kWave / k;
-  const int t_begin = c * tpc;
-  const int t_end = min(T, t_begin + tpc);
   const unsigned long long lower = lane == 0 ? 0ull : (~0ull >> (64 - lane));
   const long long npairs = (long long)T * k;
   const long long ndedup = (long long)T * min(k, R);
@@ -244,16 +280,25 @@ extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_id
   begin_launches();
   const size_t sm_wave = (size_t)(E + R) * sizeof(int);
   if (nch > 0) {
-    hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nch), dim3(kWave), sm_wave, st, topk_idx, T, E, k, R, tpc,
+    hipLaunchKernelGGL(dispatch_hist_kernel, dim3(nch), dim3(kTableThreads), sm_wave, st, topk_idx, T, E, k, R, tpc,
                        chunk_cnt, chunk_rcnt);
     if ((rc = launch_status()) != MOE_OK) return rc;
   }
   int ebits = 0, rbits = 0;
   while ((1 << ebits) < E) ++ebits;
   while ((1 << rbits) < R) ++rbits;
+  // The placement kernel keeps (2 + walking waves) arrays of E + R counters in LDS; with the largest E and R even
+  // one walking wave needs more than the default 64 KiB of dynamic LDS, so the limit is raised once.
+  constexpr size_t kPlaceLds = 144 * 1024;
+  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&dispatch_place_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPlaceLds) == hipSuccess;
+  if (!lds_ok) return MOE_ERR_HIP;
+  const size_t fit = (kPlaceLds - 1024) / sm_wave;  // arrays that fit; at least 3 for E + R <= 8192
+  const int nwalk = (int)std::max<size_t>(1, std::min<size_t>(kTableThreads / kWave, fit > 2 ? fit - 2 : 1));
   // with T == 0 a single block still writes the all-zero counts and offsets
-  hipLaunchKernelGGL(dispatch_place_kernel, dim3(nch > 0 ? nch : 1), dim3(kPlaceThreads),
-                     (size_t)(2 * (E + R) + 17) * sizeof(int), st, topk_idx, T, E, k, R, tpc, nch, ebits, rbits, chunk_cnt,
+  hipLaunchKernelGGL(dispatch_place_kernel, dim3(nch > 0 ? nch : 1), dim3(kTableThreads),
+                     (size_t)((2 + nwalk) * (E + R) + 17) * sizeof(int), st, topk_idx, T, E, k, R, tpc, nch, ebits, rbits,
+                     nwalk, chunk_cnt,
                      chunk_rcnt, out->counts, out->offsets, out->rank_counts, out->rank_offsets, out->perm,
                      out->inv_perm, out->dedup_tok, out->dedup_mask, out->pair_to_dedup);
   if ((rc = launch_status()) != MOE_OK) return rc;

@@ -12,6 +12,8 @@ typedef __bf16 bf16_t;
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS stage image of B (32 KiB)
 
@@ -95,7 +97,9 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
                                                        int E_loc, int bm, int P_cap, int max_mtiles, int nt1, int nt2,
                                                        int32_t *__restrict__ header, int4 *__restrict__ work1,
                                                        int4 *__restrict__ work2, int32_t *__restrict__ row_tok,
-                                                       float *__restrict__ row_w) {
+                                                       float *__restrict__ row_w,
+                                                       const int32_t *__restrict__ topk_idx,
+                                                       int32_t *__restrict__ row_sole) {
   // LDS: full0[E_loc + 1] first full M tile of each expert | part[E_loc] rows of its partial tile (0 = none) |
   //      order[E_loc] partial tiles: first the large ones (> kStreamRows rows), largest first, then the
   //      streaming ones, largest first | 17 ints of scan scratch
@@ -110,8 +114,18 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
   for (int r = blockIdx.x * blockDim.x + threadIdx.x; r < P; r += gridDim.x * blockDim.x) {
     int p = perm[base + r];
     p = p < 0 ? 0 : (p >= npairs ? (int)(npairs - 1) : p);
-    row_tok[r] = p / k;
+    const int t = p / k;
+    row_tok[r] = t;
     row_w[r] = topk_w[p];
+    if (row_sole) {
+      // a row that is its token's only local slot needs no reduction: GEMM-2 writes it straight to y
+      int n_local = 0;
+      for (int j = 0; j < k; ++j) {
+        const int e = topk_idx[(size_t)t * k + j];
+        n_local += e >= e_lo && e < e_lo + E_loc;
+      }
+      row_sole[r] = n_local == 1 ? t : -1;
+    }
   }
   // Every block rebuilds the small per-expert tables (cheap) so that the lists can be written grid-wide.
   // An expert with cnt rows has cnt / bm full tiles and, if cnt % bm != 0, one partial tile.
@@ -245,6 +259,8 @@ struct GemmArgs {
   const void *Bp;
   void *out;
   const float *row_w;
+  const int32_t *row_sole;  // GEMM-2 only, may be null: token of a row that is the token's only local slot, else -1
+  void *y;                  // GEMM-2 only: layer output, target of the sole rows
   const int32_t *n_items;  // device: number of work items of this GEMM
   const int4 *work;        // device: work list
   int K, N, lda, ldo, n_ntiles, n_ktiles;
@@ -477,7 +493,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
           *reinterpret_cast<u32x4 *>(static_cast<bf16_t *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
       }
     } else {
-      // o block: 32 rows x 64 columns fp32, row pitch 288 bytes
+      // o block: 32 rows x 64 columns fp32, row pitch 288 bytes.  A row whose token has no other local slot
+      // is final already (the Combine sum would have one term): it goes to y in the output type, skipping o.
+      int sole[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row_l = blk_row0 + it * 4 + (lane >> 4);
+        sole[it] = (g.row_sole && row_l < rows) ? g.row_sole[m0 + row_l] : -1;
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
@@ -494,9 +517,17 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         const int rl = it * 4 + (lane >> 4), cc = lane & 15;  // 16 chunks of 16 bytes per row
         const int row_l = blk_row0 + rl;
         const int col = nt * kBN + wn * 64 + cc * 4;
-        const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + rl * 288 + cc * 16);
-        if (row_l < rows && col < g.N)
-          *reinterpret_cast<u32x4 *>(static_cast<float *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 16);
+        if (row_l < rows && col < g.N) {
+          if (sole[it] >= 0) {
+            bf16x4 b;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) b[q] = (bf16_t)(v[q] + 0.0f);  // + 0 as in the sum that starts from zero
+            *reinterpret_cast<bf16x4 *>(static_cast<bf16_t *>(g.y) + (size_t)sole[it] * g.ldo + col) = b;
+          } else {
+            *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+          }
+        }
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -632,7 +663,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
                                                       const int32_t *__restrict__ topk_idx,
                                                       const int32_t *__restrict__ inv_perm,
                                                       const int32_t *__restrict__ offsets, int k, int d, int e_lo,
-                                                      int E_loc, int P_cap, OutT *__restrict__ y) {
+                                                      int E_loc, int P_cap, int skip_sole,
+                                                      OutT *__restrict__ y) {
   __shared__ int srow[kMaxTopK];
   __shared__ int snum;
   const int t = blockIdx.x;
@@ -649,6 +681,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float *__restrict__ 
   }
   __syncthreads();
   const int n = snum;
+  if (n == 1 && skip_sole) return;  // GEMM-2 has written this token's row
   for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int i = 0; i < n; ++i) {
@@ -737,7 +770,7 @@ __global__ __launch_bounds__(256) void cast_rows_kernel(const float *__restrict_
 // Host-side launch helpers
 // ------------------------------------------------------------------------------------------------
 struct Ws {
-  int32_t *header, *row_tok;
+  int32_t *header, *row_tok, *row_sole;
   int4 *work1, *work2;
   float *row_w;
   void *h;
@@ -752,34 +785,38 @@ static Ws carve(void *workspace, const FwdLayout &L) {
   w.work2 = reinterpret_cast<int4 *>(b + L.work2);
   w.row_tok = reinterpret_cast<int32_t *>(b + L.row_tok);
   w.row_w = reinterpret_cast<float *>(b + L.row_w);
+  w.row_sole = reinterpret_cast<int32_t *>(b + L.row_sole);
   w.h = b + L.h;
   w.o = reinterpret_cast<float *>(b + L.o);
   return w;
 }
 
-static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch *tb, const float *topk_w,
-                       const Ws &w, hipStream_t st) {
+// sole != nullptr: also mark the rows GEMM-2 may write straight to y (see the GEMM-2 epilogue)
+static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch *tb, const int32_t *topk_idx,
+                       const float *topk_w, const Ws &w, int32_t *sole, hipStream_t st) {
   const int blocks = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (dv.P_cap + 255) / 256));
   hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), (size_t)(3 * dv.E_loc + 1 + 17) * sizeof(int), st,
                      tb->offsets, tb->perm, topk_w, s->T, s->k, dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles,
-                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w);
+                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w, topk_idx, sole);
   return launch_status();
 }
 
 // GEMM-1 (gated) then GEMM-2 on the rows described by the tile table.  a1 / a1_map select the A operand of
 // GEMM-1: the token matrix with the row -> token map (fused gather) or a materialised copy (map == nullptr).
 static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, const int32_t *a1_map, int a1_ld,
-                        const void *packed_gu, const void *packed_down, const Ws &w, hipStream_t st,
-                        void *const *events = nullptr) {
+                        const void *packed_gu, const void *packed_down, const Ws &w, const int32_t *sole, void *y,
+                        hipStream_t st, void *const *events = nullptr) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
   GemmArgs g1{};
   g1.A = a1; g1.row_map = a1_map; g1.Bp = packed_gu; g1.out = w.h; g1.row_w = nullptr;
+  g1.row_sole = nullptr; g1.y = nullptr;
   g1.n_items = w.header + 0; g1.work = w.work1;
   g1.K = s->d; g1.N = s->f; g1.lda = a1_ld; g1.ldo = s->f;
   GemmArgs g2 = g1;
   g2.A = w.h; g2.row_map = nullptr; g2.Bp = packed_down; g2.out = w.o; g2.row_w = w.row_w;
+  g2.row_sole = sole; g2.y = y;
   g2.K = s->f; g2.N = s->d; g2.lda = s->f; g2.ldo = s->d;
   g2.n_items = w.header + 3; g2.work = w.work2;
   const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dv.max_mtiles * nt + 255) / 256 * 256)); };
@@ -817,13 +854,13 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
 }
 
 static int launch_combine(const moe_shape *s, const Derived &dv, const float *rows, const int32_t *topk_idx,
-                          const moe_dispatch *tb, void *y, hipStream_t st) {
+                          const moe_dispatch *tb, void *y, bool skip_sole, hipStream_t st) {
   if (s->dtype == MOE_BF16)
     hipLaunchKernelGGL(combine_kernel<bf16_t>, dim3(s->T), dim3(256), 0, st, rows, topk_idx, tb->inv_perm,
-                       tb->offsets, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, static_cast<bf16_t *>(y));
+                       tb->offsets, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, (int)skip_sole, static_cast<bf16_t *>(y));
   else
     hipLaunchKernelGGL(combine_kernel<float>, dim3(s->T), dim3(256), 0, st, rows, topk_idx, tb->inv_perm,
-                       tb->offsets, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, static_cast<float *>(y));
+                       tb->offsets, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, (int)skip_sole, static_cast<float *>(y));
   return launch_status();
 }
 
@@ -890,13 +927,16 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
+  // fused bf16 layers: GEMM-2 writes the rows that need no reduction straight to y and Combine skips them
+  int32_t *sole = fused && shape->dtype == MOE_BF16 ? w.row_sole : nullptr;
   mark(0);
-  if ((rc = launch_prep(shape, dv, tables, topk_w, w, st)) != MOE_OK) return rc;
+  if ((rc = launch_prep(shape, dv, tables, topk_idx, topk_w, w, sole, st)) != MOE_OK) return rc;
   mark(1);
   if (fused) {
-    if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, st, events)) != MOE_OK)
+    if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, sole, y, st,
+                           events)) != MOE_OK)
       return rc;
-    rc = launch_combine(shape, dv, w.o, topk_idx, tables, y, st);
+    rc = launch_combine(shape, dv, w.o, topk_idx, tables, y, sole != nullptr, st);
     mark(4);
     return rc;
   }
@@ -909,7 +949,7 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, static_cast<const uint4 *>(x),
                      w.header, w.row_tok, row_chunks, static_cast<uint4 *>(xs));
   if ((rc = launch_status()) != MOE_OK) return rc;
-  if ((rc = launch_gemms(shape, dv, xs, nullptr, shape->d, packed_gate_up, packed_down, w, st)) != MOE_OK) return rc;
+  if ((rc = launch_gemms(shape, dv, xs, nullptr, shape->d, packed_gate_up, packed_down, w, nullptr, nullptr, st)) != MOE_OK) return rc;
   const size_t n = (size_t)shape->T * shape->d;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<float4 *>(y32), n / 4);
   hipLaunchKernelGGL(scatter_add_kernel, dim3((unsigned)rows), dim3(256), 0, st, w.o, w.header, w.row_tok, shape->d,
@@ -970,5 +1010,5 @@ extern "C" int moe_combine_reduce(const moe_shape *shape, const float *rows, con
   if (!rows || !topk_idx || !y || !tables_ok(tables)) return MOE_ERR_INVALID_ARG;
   if (shape->T == 0) return MOE_OK;
   begin_launches();
-  return launch_combine(shape, dv, rows, topk_idx, tables, y, (hipStream_t)stream);
+  return launch_combine(shape, dv, rows, topk_idx, tables, y, false, (hipStream_t)stream);
 }

@@ -1,5 +1,7 @@
 // moe_route_topk: softmax top-k routing with renormalised weights (gate of Sec. II-A; the routing is
-// produced before Dispatch, Sec. III-E).  One 64-lane wave owns one token row.
+// produced before Dispatch, Sec. III-E).  One 64-lane wave owns one token row.  Up to 512 experts the row
+// lives in registers (a contiguous run of experts per lane) and a pick costs a handful of cross-lane
+// operations; beyond that the keys go through the LDS.
 #include "common.h"
 
 namespace moe355 {
@@ -10,6 +12,93 @@ namespace moe355 {
 __device__ __forceinline__ uint32_t ordered_key(float v) {
   const uint32_t b = __float_as_uint(v + 0.0f);
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Maximum over the wave, returned in every lane: butterfly inside the rows of 16 lanes with data-parallel
+// primitives (lane ^ 1, lane ^ 2, mirrored halves, mirrored row), then the four row results are combined.
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  auto step = [](uint32_t x, uint32_t y) { return x > y ? x : y; };
+  v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  v = step(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, false));  // row_mirror
+  const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0), b = (uint32_t)__builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)v, 32), d = (uint32_t)__builtin_amdgcn_readlane((int)v, 48);
+  return step(step(a, b), step(c, d));
+}
+
+// Register variant for E <= 64 * PER: lane l owns experts [l * PER, l * PER + PER).  Ties resolve to the lower
+// expert index because a lane scans its run upwards with a strict comparison and, across lanes, the lowest
+// lane holding the wave maximum wins.
+template <int PER>
+__global__ __launch_bounds__(256) void route_topk_reg_kernel(const float *__restrict__ logits,
+                                                             int32_t *__restrict__ topk_idx,
+                                                             float *__restrict__ topk_w, int T, int E, int k) {
+  const int wave = threadIdx.x >> 6;
+  const int lane = lane_id();
+  const int t = blockIdx.x * (blockDim.x >> 6) + wave;
+  if (t >= T) return;  // whole wave leaves together
+  const float *row = logits + (size_t)t * E;
+  uint32_t key[PER];
+  float val[PER];
+  if (PER % 4 == 0 && (E & 3) == 0) {
+#pragma unroll
+    for (int q = 0; q < PER / 4; ++q) {
+      const int e0 = lane * PER + q * 4;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (e0 < E) v = *reinterpret_cast<const float4 *>(row + e0);  // E % 4 == 0: the four are inside together
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        val[q * 4 + u] = vv[u];
+        key[q * 4 + u] = e0 < E ? ordered_key(vv[u]) : 0u;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int e = lane * PER + i;
+      val[i] = e < E ? row[e] : 0.f;
+      key[i] = e < E ? ordered_key(val[i]) : 0u;
+    }
+  }
+  int my_e = 0;
+  float my_x = 0.f, first = 0.f, sum = 0.f;
+  for (int j = 0; j < k; ++j) {
+    uint32_t bk = 0;
+    int bs = 0;
+    float bv = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      if (key[i] > bk) {
+        bk = key[i];
+        bs = i;
+        bv = val[i];
+      }
+    }
+    const uint32_t top = wave_max_u32(bk);
+    const unsigned long long holders = __ballot(bk == top);
+    const int win = holders ? __builtin_ctzll(holders) : 0;
+    const int slot = __builtin_amdgcn_readlane(bs, win);
+    const float v_best = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bv), win));
+    // k <= E, so an unpicked expert always exists; the clamp only guards against non-finite input
+    int e_best = win * PER + slot;
+    e_best = e_best < E ? e_best : 0;
+#pragma unroll
+    for (int i = 0; i < PER; ++i)
+      if (lane == win && i == slot) key[i] = 0u;  // picked
+    if (j == 0) first = v_best;                    // the largest logit: softmax shift
+    const float x = expf(v_best - first);
+    sum += x;                                      // slot order
+    if (lane == j) {
+      my_e = e_best;
+      my_x = x;
+    }
+  }
+  if (lane < k) {
+    topk_idx[(size_t)t * k + lane] = my_e;
+    topk_w[(size_t)t * k + lane] = my_x / sum;
+  }
 }
 
 constexpr int kRouteWaves = 4;  // waves (token rows) per block; fewer when E is large enough to crowd the LDS
@@ -80,6 +169,18 @@ extern "C" int moe_route_topk(const moe_shape *shape, const float *logits, int32
   if (!logits || !topk_idx || !topk_w) return MOE_ERR_INVALID_ARG;
   if (shape->T == 0) return MOE_OK;
   begin_launches();
+  if (shape->E <= 512) {
+    const dim3 grid(ceil_div(shape->T, 4)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+#define MOE355_ROUTE(PER_) \
+  hipLaunchKernelGGL(route_topk_reg_kernel<PER_>, grid, block, 0, st, logits, topk_idx, topk_w, shape->T, shape->E, shape->k)
+    if (shape->E <= 64) MOE355_ROUTE(1);
+    else if (shape->E <= 128) MOE355_ROUTE(2);
+    else if (shape->E <= 256) MOE355_ROUTE(4);
+    else MOE355_ROUTE(8);
+#undef MOE355_ROUTE
+    return launch_status();
+  }
   const size_t per_wave = (size_t)(shape->E + kMaxTopK) * sizeof(uint32_t);
   int waves = kRouteWaves;
   while (waves > 1 && waves * per_wave > 48 * 1024) waves >>= 1;

@@ -40,7 +40,8 @@ SMALL = {
 # ---------------------------------------------------------------- routing + tables
 @pytest.mark.parametrize("T,E,k,R", [(1, 4, 2, 2), (63, 8, 2, 4), (64, 8, 8, 8), (257, 256, 8, 8), (1000, 128, 4, 4),
                                      (300, 16, 1, 16), (129, 32, 32, 4), (200, 6, 3, 1), (4096, 256, 8, 8),
-                                     (90, 4096, 5, 64), (70, 12, 7, 3)])
+                                     (90, 4096, 5, 64), (70, 12, 7, 3), (150, 4096, 3, 4096),
+                                     (5000, 48, 6, 8), (777, 512, 8, 8), (333, 65, 9, 5), (2100, 640, 8, 8)])
 def test_route_and_tables_bit_exact(oracle, T, E, k, R):
     say(f"route/tables T={T} E={E} k={k} R={R}")
     rng = np.random.default_rng(T * 7 + E)
@@ -91,6 +92,7 @@ def run_forward(cfg, oracle, tokens=None):
     lay.load_weights(w.W_gate, w.W_up, w.W_down)
     x = L.to_device(w.x)
     lg = L.to_device(w.logits)
+    lay.y.fill_(float("nan"))  # every row has to be written by this call, whichever kernel owns it
     lay.step(lg, x)
     torch.cuda.synchronize()
     got = G.tables_to_host(lay)
@@ -147,9 +149,16 @@ def test_forward_full_size_sampled_tokens(oracle, name, nsample):
     rng = np.random.default_rng(5)
     w0 = wl.make_workload(cfg, weights=False)
     idx0, _ = oracle.route_topk(w0.logits, cfg.k)
-    local = ((idx0 // cfg.epr >= cfg.local_rank_begin) & (idx0 // cfg.epr < cfg.local_rank_end)).any(axis=1)
-    with_local = np.nonzero(local)[0]
-    tokens = np.sort(rng.choice(with_local, size=min(nsample, with_local.size), replace=False)).astype(np.int32)
+    slots = ((idx0 // cfg.epr >= cfg.local_rank_begin) & (idx0 // cfg.epr < cfg.local_rank_end)).sum(axis=1)
+    local = slots > 0
+    # half of the sample from tokens with one local slot (written by the GEMM-2 epilogue), half from tokens with
+    # several (written by the combine kernel), as far as the routing has both kinds
+    one, many = np.nonzero(slots == 1)[0], np.nonzero(slots > 1)[0]
+    n_one = min(one.size, nsample // 2 if many.size else nsample)
+    n_many = min(many.size, nsample - n_one)
+    tokens = np.sort(np.concatenate([rng.choice(one, size=n_one, replace=False),
+                                     rng.choice(many, size=n_many, replace=False)])).astype(np.int32)
+    say(f"  sample: {n_one} tokens with one local slot, {n_many} with several")
     w, lay, x, lg, idx, tw, y, ref = run_forward(cfg, oracle, tokens=tokens)
     mx, mean = G.check_y(y[tokens], ref, cfg.dtype)
     say(f"  {name}: sampled {tokens.size} tokens, max rel {mx:.2e}, mean rel {mean:.2e}")
