@@ -254,6 +254,18 @@ def main():
     out["unfused_comparison"] = {"fused_forward_ms": t_fus, "unfused_forward_ms": t_unf,
                                  "note": "unfused = gather copy + same grouped GEMMs + fp32 atomic scatter-add + cast"}
     del lay_u
+    # Context for the matrix-core fractions: what the vendor library's dense bf16 GEMM reaches on this very box
+    # with the same kind of data (random normal), on a problem as large as this layer's GEMM-1 would be if it were
+    # one dense product.  Not part of the path, not timed into `value`.
+    if cfg.dtype == wl.BF16:
+        Mref = max(256, -(-P // 256) * 256)
+        a = torch.randn((Mref, cfg.d), dtype=torch.bfloat16, device="cuda")
+        bmat = torch.randn((cfg.d, 2 * cfg.f), dtype=torch.bfloat16, device="cuda")
+        t_ref = timed(lambda: torch.matmul(a, bmat), 10)
+        out["dense_gemm_reference"] = {"what": "torch.matmul (hipBLASLt) bf16, one dense product", "M": Mref,
+                                       "N": 2 * cfg.f, "K": cfg.d, "ms": t_ref,
+                                       "tflops": 2.0 * Mref * 2 * cfg.f * cfg.d / (t_ref * 1e-3) / 1e12}
+        del a, bmat
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w)
     print(json.dumps(out))
