@@ -83,19 +83,60 @@ def cpu_baseline(cfg, w, budget_s=12.0):
         if spent < budget_s / 8:
             batch *= 2
     total = spent + t_tables * done / cfg.T
-    return {"value": done / total, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
+    return {"value": done / total, "unit": "tokens/s", "cores": threads, "kind": "oracle", "cpu": model,
             "sample": f"{done} of {cfg.T} tokens drawn uniformly (forward {spent:.1f} s; routing+tables "
                       f"{t_tables:.2f} s for all tokens, charged pro rata)"}
+
+
+def timed_steps(lay, lg, x, K):
+    """K steps (route, tables, fused forward) between two synchronisations.  Returns wall ms per step, the mean
+    duration of the four kernels phases of the forward call (HIP events on the launch stream), the mean duration of
+    route + tables, and the per-step durations."""
+    import numpy as np
+    import torch
+
+    from paper_2605_05607_amd import binding as B
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
+    for row in ev:  # give every event a raw handle before the timed region
+        for e in row:
+            e.record()
+    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step_ev[0].record()
+    for i in range(K):
+        lay.route(lg)
+        lay.build_dispatch()
+        B.moe_fused_forward_timed(lay.shape, x, lay.topk_idx, lay.topk_w, lay.tables, lay.packed_gate_up,
+                                  lay.packed_down, lay.y, lay.forward_ws, [e.cuda_event for e in ev[i]])
+        step_ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    phase = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(4)] for i in range(K)])  # ms
+    front_ms = float(np.mean([step_ev[i].elapsed_time(ev[i][0]) for i in range(K)]))  # route + tables
+    step_ms = np.array([step_ev[i].elapsed_time(step_ev[i + 1]) for i in range(K)])
+    return wall * 1e3 / K, phase.mean(axis=0), front_ms, step_ms
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="deepseek_v3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tokens", type=int, default=0, help="override T (sweeps); 0 = the config's T")
+    ap.add_argument("--topk", type=int, default=0, help="override k (sweeps)")
+    ap.add_argument("--router", default="", help="override the router kind: normal | zipf | forced (sweeps)")
+    ap.add_argument("--zipf-s", type=float, default=-1.0, help="override the Zipf exponent of the zipf router (sweeps)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the untimed extras (phase-split entry points, "
+                    "unfused path, reference figures)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy (reference point for the HBM byte counters)")
     args = ap.parse_args()
@@ -123,8 +164,15 @@ def main():
     from paper_2605_05607_amd import workloads as wl
 
     cfg = wl.CONFIGS[args.config]
+    swept = bool(args.tokens or args.topk or args.router or args.zipf_s >= 0)
     if args.tokens:
         cfg = cfg.scaled(T=args.tokens)
+    if args.topk:
+        cfg = cfg.scaled(k=args.topk)
+    if args.router:
+        cfg = cfg.scaled(router=args.router)
+    if args.zipf_s >= 0:
+        cfg = cfg.scaled(zipf_s=args.zipf_s)
     torch.cuda.set_device(0)
     w = wl.make_workload(cfg)
     lay = L.MoELayer(cfg)
@@ -137,27 +185,7 @@ def main():
     torch.cuda.synchronize()
 
     K = args.steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(K)]
-    for row in ev:  # give every event a raw handle before the timed region
-        for e in row:
-            e.record()
-    step_ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    step_ev[0].record()
-    for i in range(K):
-        lay.route(lg)
-        lay.build_dispatch()
-        B.moe_fused_forward_timed(lay.shape, x, lay.topk_idx, lay.topk_w, lay.tables, lay.packed_gate_up,
-                                  lay.packed_down, lay.y, lay.forward_ws, [e.cuda_event for e in ev[i]])
-        step_ev[i + 1].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / K
-
-    phase = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) for j in range(4)] for i in range(K)])  # ms
-    prep_ms, g1_ms, g2_ms, cb_ms = phase.mean(axis=0)
-    front_ms = float(np.mean([step_ev[i].elapsed_time(ev[i][0]) for i in range(K)]))  # route + tables
+    ms_per_step, (prep_ms, g1_ms, g2_ms, cb_ms), front_ms, step_ms = timed_steps(lay, lg, x, K)
 
     idx = lay.topk_idx.cpu().numpy().reshape(cfg.T, cfg.k)
     counts = lay.tables.counts.cpu().numpy()
@@ -172,7 +200,7 @@ def main():
         roof = {"bound": "mfma", "achieved": g1["flops"] / (g1_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None if args.tokens else stored_traffic(cfg.name)
+    roof["traffic"] = None if swept else stored_traffic(cfg.name)
     roof["traffic_unit"] = "bytes per launch"
     roof["algorithmic"] = g1["bytes"] if roof["bound"] == "hbm" else g1["flops"]
     roof["kernel"] = "gemm_bf16_kernel<true> (GEMM-1: gathered gate/up GEMM + SwiGLU)"
@@ -189,6 +217,7 @@ def main():
                    "local_pairs_P": P, "tokens_with_local_expert": U_tok, "nonempty_local_experts": ne,
                    "rows_per_expert_max": int(counts_local.max()), "seed": cfg.seed},
         "roofline": roof,
+        "step_ms_median": float(np.median(step_ms)), "step_ms_min": float(step_ms.min()),
         "phases_ms": {"route_and_tables": front_ms, "tile_table": float(prep_ms), "gemm1": float(g1_ms),
                       "gemm2": float(g2_ms), "combine": float(cb_ms)},
         "gemm_phase": {"flops": g1["flops"] + g2["flops"],
@@ -200,6 +229,12 @@ def main():
                        "mfma_ceiling_if_hbm_bound": min(1.0, (g1["flops"] + g2["flops"]) / (MFMA_BF16_PEAK_TF * 1e12)
                                                         / ((g1["bytes"] + g2["bytes"]) / (HBM_PEAK_GBS * 1e9)))},
     }
+    out["gemm_phase"]["mfma_frac_of_ceiling"] = (out["gemm_phase"]["mfma_frac_of_peak"]
+                                                 / out["gemm_phase"]["mfma_ceiling_if_hbm_bound"])
+    if args.no_extras:
+        print(json.dumps(out))
+        return
+
     # ---- untimed extras: Dispatch and Combine on their own (phase-split entry points) and the unfused path ----
     def timed(fn, reps):
         fn()
@@ -254,6 +289,34 @@ def main():
     out["unfused_comparison"] = {"fused_forward_ms": t_fus, "unfused_forward_ms": t_unf,
                                  "note": "unfused = gather copy + same grouped GEMMs + fp32 atomic scatter-add + cast"}
     del lay_u
+    # The same layer at 8 x the tokens (for the DeepSeek-shaped workload: what one GPU of an 8-way expert-parallel
+    # group sees when every GPU contributes T tokens): enough rows per expert for the GEMMs to be compute-bound.
+    if cfg.dtype == wl.BF16 and not swept and cfg.T * 8 * cfg.d * 2 <= 1 << 30:
+        cfg8 = cfg.scaled(T=8 * cfg.T)
+        w8 = wl.make_workload(cfg8, weights=False)
+        lay8 = L.MoELayer(cfg8)
+        lay8.packed_gate_up, lay8.packed_down = lay.packed_gate_up, lay.packed_down
+        x8, lg8 = L.to_device(w8.x), L.to_device(w8.logits)
+        for _ in range(2):
+            lay8.step(lg8, x8)
+        ms8, (_, g1_8, g2_8, _), _, _ = timed_steps(lay8, lg8, x8, 8)
+        idx8 = lay8.topk_idx.cpu().numpy().reshape(cfg8.T, cfg8.k)
+        local8 = (idx8 // cfg8.epr >= cfg8.local_rank_begin) & (idx8 // cfg8.epr < cfg8.local_rank_end)
+        P8 = int(local8.sum())
+        fl8 = 6.0 * P8 * cfg8.d * cfg8.f
+        out["compute_bound_point"] = {"workload": f"{cfg.name} at T={cfg8.T} (8 x), same weights", "local_pairs_P": P8,
+                                      "ms_per_step": ms8, "tokens_per_s": cfg8.T / (ms8 * 1e-3),
+                                      "gemm_ms": float(g1_8 + g2_8),
+                                      "mfma_tflops": fl8 / ((g1_8 + g2_8) * 1e-3) / 1e12,
+                                      "mfma_frac_of_peak": fl8 / ((g1_8 + g2_8) * 1e-3) / 1e12 / MFMA_BF16_PEAK_TF}
+        del lay8, x8, lg8, w8
+    # Context for the bandwidth fractions: a plain 1 GiB device copy on this machine (reads + writes counted).
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    t_copy = timed(lambda: dst.copy_(src), 10)
+    out["copy_reference"] = {"what": "torch 1 GiB device-to-device copy", "ms": t_copy,
+                             "hbm_gbs": 2.0 * src.numel() * 4 / (t_copy * 1e-3) / 1e9}
+    del src, dst
     # Context for the matrix-core fractions: what the vendor library's dense bf16 GEMM reaches on this very box
     # with the same kind of data (random normal), on a problem as large as this layer's GEMM-1 would be if it were
     # one dense product.  Not part of the path, not timed into `value`.

@@ -80,6 +80,12 @@ CONFIGS = {
                          local_rank_end=8, dtype=BF16, router="normal", seed=1003),
     "gpt_oss": MoEConfig("gpt_oss", T=16384, d=2880, f=2880, E=128, k=4, R=4, local_rank_begin=0,
                          local_rank_end=1, dtype=BF16, router="forced", seed=1004),
+    # "Small" and "Medium" rows of the evaluation's model table (its "Large" row is deepseek_v3 above); one rank of
+    # eight is local and the load is uniform, top-k 8 (16 and 32 are the table's other columns: MoEConfig.scaled(k=...))
+    "table1_s": MoEConfig("table1_s", T=2048, d=2048, f=512, E=64, k=8, R=8, local_rank_begin=0, local_rank_end=1,
+                          dtype=BF16, router="normal", seed=1005),
+    "table1_m": MoEConfig("table1_m", T=4096, d=4096, f=1024, E=128, k=8, R=8, local_rank_begin=0, local_rank_end=1,
+                          dtype=BF16, router="normal", seed=1006),
 }
 
 

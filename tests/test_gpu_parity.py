@@ -34,6 +34,9 @@ SMALL = {
                            router="forced", seed=24),
     "f32_ragged": cfg_of(T=130, d=72, f=88, E=6, k=3, R=3, local_rank_begin=1, local_rank_end=3, dtype=wl.F32, seed=25),
     "k_tail_bf16": cfg_of(T=77, d=72, f=40, E=4, k=2, R=2, local_rank_begin=0, local_rank_end=2, seed=26),
+    # the wider top-k columns of the evaluation's model table (16 and 32 picks): many slots per token on one rank
+    "table1_like_k16": cfg_of(T=400, d=256, f=128, E=64, k=16, R=8, local_rank_begin=3, local_rank_end=4, seed=27),
+    "table1_like_k32": cfg_of(T=260, d=192, f=64, E=64, k=32, R=8, local_rank_begin=0, local_rank_end=2, seed=28),
 }
 
 
@@ -55,7 +58,7 @@ def test_route_and_tables_bit_exact(oracle, T, E, k, R):
     G.assert_tables_equal(got, oracle, logits, cfg)
 
 
-@pytest.mark.parametrize("name", ["tiny", "deepseek_v3", "qwen3", "mixtral", "gpt_oss"])
+@pytest.mark.parametrize("name", ["tiny", "deepseek_v3", "qwen3", "mixtral", "gpt_oss", "table1_s", "table1_m"])
 def test_route_and_tables_full_size_configs(oracle, name):
     say(f"route/tables full size {name}")
     cfg = wl.CONFIGS[name]
@@ -142,7 +145,8 @@ def test_forward_is_deterministic_and_leaves_inputs_alone(oracle):
 
 
 # ---------------------------------------------------------------- forward, full-size configs, sampled tokens
-@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 96), ("qwen3", 96), ("mixtral", 32), ("gpt_oss", 96)])
+@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 96), ("qwen3", 96), ("mixtral", 32), ("gpt_oss", 96),
+                                          ("table1_s", 96), ("table1_m", 96)])
 def test_forward_full_size_sampled_tokens(oracle, name, nsample):
     cfg = wl.CONFIGS[name]
     say(f"forward full size {name}")
