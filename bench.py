@@ -47,9 +47,9 @@ def kernel_source_hash():
 
 
 def stored_traffic(cfg_name):
-    """HBM bytes per launch of GEMM-1 from the committed rocprofv3 counter readings (FETCH_SIZE and WRITE_SIZE in KiB,
+    """HBM bytes per launch of the GEMM kernel from the committed rocprofv3 counter readings (FETCH_SIZE and WRITE_SIZE in KiB,
     each scaled by what the same counter reads for a plain 1 GiB copy); None if the kernels changed since."""
-    path = os.path.join(ROOT, "profiles", f"traffic_gemm1_{cfg_name}.json")
+    path = os.path.join(ROOT, "profiles", f"traffic_gemms_{cfg_name}.json")
     if not os.path.exists(path):
         return None
     with open(path) as f:
@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--topk", type=int, default=0, help="override k (sweeps)")
     ap.add_argument("--router", default="", help="override the router kind: normal | zipf | forced (sweeps)")
     ap.add_argument("--zipf-s", type=float, default=-1.0, help="override the Zipf exponent of the zipf router (sweeps)")
+    ap.add_argument("--no-8x-point", action="store_true", help="skip the extra run of the layer at 8 x the tokens")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed extras (phase-split entry points, "
                     "unfused path, reference figures)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -192,19 +193,28 @@ def main():
     counts_local = counts[cfg.first_local_expert:cfg.first_local_expert + cfg.E_loc]
     P, U_tok, ne, g1, g2, cb = algorithmic_work(cfg, idx, counts_local)
 
-    t_mfma = g1["flops"] / (MFMA_BF16_PEAK_TF * 1e12)
-    t_hbm = g1["bytes"] / (HBM_PEAK_GBS * 1e9)
+    # Dominant kernel: where the library runs GEMM-1 and GEMM-2 as one launch (resident workgroups, tile-level
+    # hand-over; see moe_forward_gemm_launches) that launch, with the algorithmic work of both GEMMs; otherwise the
+    # GEMM-1 launch.  Duration = time between the HIP events recorded before and after it on the launch stream.
+    one_launch = B.moe_forward_gemm_launches(lay.shape) == 1
+    gk_ms = float(g1_ms + g2_ms) if one_launch else float(g1_ms)
+    gk = {k: g1[k] + g2[k] for k in g1} if one_launch else g1
+    t_mfma = gk["flops"] / (MFMA_BF16_PEAK_TF * 1e12)
+    t_hbm = gk["bytes"] / (HBM_PEAK_GBS * 1e9)
     if t_hbm >= t_mfma:
-        roof = {"bound": "hbm", "achieved": g1["bytes"] / (g1_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        roof = {"bound": "hbm", "achieved": gk["bytes"] / (gk_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
     else:
-        roof = {"bound": "mfma", "achieved": g1["flops"] / (g1_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
+        roof = {"bound": "mfma", "achieved": gk["flops"] / (gk_ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TF,
                 "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = None if swept else stored_traffic(cfg.name)
     roof["traffic_unit"] = "bytes per launch"
-    roof["algorithmic"] = g1["bytes"] if roof["bound"] == "hbm" else g1["flops"]
-    roof["kernel"] = "gemm_bf16_kernel<true> (GEMM-1: gathered gate/up GEMM + SwiGLU)"
-    roof["avg_launch_ms"] = float(g1_ms)
+    roof["algorithmic"] = gk["bytes"] if roof["bound"] == "hbm" else gk["flops"]
+    roof["kernel"] = ("gemm_bf16_pipeline_kernel (gathered gate/up GEMM + SwiGLU, then down GEMM x gate weight, one "
+                      "launch)" if one_launch else
+                      ("gemm_bf16_kernel<true>" if cfg.dtype == wl.BF16 else "gemm_f32_kernel<true>")
+                      + " (GEMM-1: gathered gate/up GEMM + SwiGLU)")
+    roof["avg_launch_ms"] = gk_ms
 
     out = {
         "metric": "fused MoE layer tokens/s on 1 MI355X", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -218,8 +228,8 @@ def main():
                    "rows_per_expert_max": int(counts_local.max()), "seed": cfg.seed},
         "roofline": roof,
         "step_ms_median": float(np.median(step_ms)), "step_ms_min": float(step_ms.min()),
-        "phases_ms": {"route_and_tables": front_ms, "tile_table": float(prep_ms), "gemm1": float(g1_ms),
-                      "gemm2": float(g2_ms), "combine": float(cb_ms)},
+        "phases_ms": {"route_and_tables": front_ms, "tile_table": float(prep_ms), "gemms": float(g1_ms + g2_ms),
+                      "combine": float(cb_ms), "gemm_launches": 1 if one_launch else 2},
         "gemm_phase": {"flops": g1["flops"] + g2["flops"],
                        "mfma_tflops": (g1["flops"] + g2["flops"]) / ((g1_ms + g2_ms) * 1e-3) / 1e12,
                        "mfma_frac_of_peak": (g1["flops"] + g2["flops"]) / ((g1_ms + g2_ms) * 1e-3) / 1e12
@@ -288,10 +298,22 @@ def main():
     t_fus = timed(lambda: lay.forward(x), 5)
     out["unfused_comparison"] = {"fused_forward_ms": t_fus, "unfused_forward_ms": t_unf,
                                  "note": "unfused = gather copy + same grouped GEMMs + fp32 atomic scatter-add + cast"}
+    # The two forms of the GEMM-1 => GEMM-2 hand-over side by side (the library picks by shape), and the two GEMMs
+    # timed apart in the two-launch form.
+    ev2 = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+    for e in ev2:
+        e.record()
+    t_two = timed(lambda: lay.forward_two_launch(x), 5)
+    lay.forward_two_launch(x, [e.cuda_event for e in ev2])
+    torch.cuda.synchronize()
+    out["hand_over_comparison"] = {"default_gemm_launches": 1 if one_launch else 2, "two_launch_forward_ms": t_two,
+                                   "gemm1_ms": ev2[1].elapsed_time(ev2[2]), "gemm2_ms": ev2[2].elapsed_time(ev2[3])}
+    if cfg.dtype == wl.BF16:
+        out["hand_over_comparison"]["one_launch_forward_ms"] = timed(lambda: lay.forward_one_launch(x), 5)
     del lay_u
     # The same layer at 8 x the tokens (for the DeepSeek-shaped workload: what one GPU of an 8-way expert-parallel
     # group sees when every GPU contributes T tokens): enough rows per expert for the GEMMs to be compute-bound.
-    if cfg.dtype == wl.BF16 and not swept and cfg.T * 8 * cfg.d * 2 <= 1 << 30:
+    if cfg.dtype == wl.BF16 and not swept and not args.no_8x_point and cfg.T * 8 * cfg.d * 2 <= 1 << 30:
         cfg8 = cfg.scaled(T=8 * cfg.T)
         w8 = wl.make_workload(cfg8, weights=False)
         lay8 = L.MoELayer(cfg8)

@@ -120,7 +120,12 @@ MOE355_API int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
  * (Sec. II-A, III-C, IV-A).  x [T,d]; y [T,d], y[t] = sum over the local slots j of token t of
  * topk_w[t,j] * FFN_{e(t,j)}(x[t]); rows of tokens without a local slot are written as zeros.
  * Token rows are gathered straight into the GEMM-1 tiles (no dispatched copy of x is materialised);
- * each y row is written exactly once, without atomics.
+ * each y row is written exactly once, without atomics.  When moe_forward_gemm_launches(shape) is 1 (bf16 layers
+ * with fewer than 256 rows per expert on average, T*k < 256*E), GEMM-1 and GEMM-2 run in ONE launch of resident
+ * workgroups: a GEMM-2 tile starts as soon as the h rows of its 256-row tile are complete (per-tile readiness
+ * counters in the workspace), the one-GPU form of the tile-granular GEMM-1 => GEMM-2 hand-over of the fused
+ * kernel (Sec. IV-A, IV-B); otherwise the two GEMMs are two launches.  The result is the same either way.
+ * Int 24 of the workspace is 0 after the call unless a wait inside the resident kernel gave up (corrupt tables).
  * `tables` must come from moe_build_dispatch on the same shape and topk_idx.
  * workspace >= moe_forward_workspace_bytes(shape), 256-byte aligned; its contents are scratch.
  */
@@ -132,13 +137,35 @@ MOE355_API int moe_fused_forward(const moe_shape *shape, const void *x, const in
 /*
  * moe_fused_forward with the kernel boundaries marked for measurement: `events` points at five hipEvent_t
  * (created by the caller with timing enabled; a NULL entry is skipped) which are recorded on `stream`
- * [0] before the first kernel, [1] after the tile-table kernel, [2] after GEMM-1, [3] after GEMM-2,
- * [4] after Combine.  The kernels and their order are those of moe_fused_forward.
+ * [0] before the first kernel, [1] after the tile-table kernel, [2] after GEMM-1, [3] after GEMM-2 (recorded
+ * together, after the one launch, when moe_forward_gemm_launches(shape) is 1), [4] after Combine.
+ * The kernels and their order are those of moe_fused_forward.
  */
 MOE355_API int moe_fused_forward_timed(const moe_shape *shape, const void *x, const int32_t *topk_idx,
                                        const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
                                        const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
                                        void *stream, void *const *events);
+
+/* 1 or 2: GEMM launches of moe_fused_forward for this shape (host-only; 0 for an invalid shape). */
+MOE355_API int moe_forward_gemm_launches(const moe_shape *shape);
+
+/*
+ * moe_fused_forward with the choice between the two forms of the GEMM-1 => GEMM-2 hand-over made by the caller
+ * (comparison of the two, timing of the two GEMMs apart): _two_launch keeps a kernel boundary between the GEMMs,
+ * _one_launch runs the resident kernel with per-tile readiness counters (bf16 layers only, MOE_ERR_UNSUPPORTED
+ * otherwise).  Same arguments, workspace and result as moe_fused_forward; `events` may be NULL, otherwise five
+ * events as in moe_fused_forward_timed.
+ */
+MOE355_API int moe_fused_forward_two_launch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                            const float *topk_w, const moe_dispatch *tables,
+                                            const void *packed_gate_up, const void *packed_down, void *y,
+                                            void *workspace, size_t workspace_bytes, void *stream,
+                                            void *const *events);
+MOE355_API int moe_fused_forward_one_launch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                            const float *topk_w, const moe_dispatch *tables,
+                                            const void *packed_gate_up, const void *packed_down, void *y,
+                                            void *workspace, size_t workspace_bytes, void *stream,
+                                            void *const *events);
 
 /*
  * Phase-split entry points, used to measure Dispatch and Combine on their own (Sec. VI "pure

@@ -56,6 +56,8 @@ def lib() -> C.CDLL:
         L.moe_forward_workspace_bytes.argtypes = [sp]
         L.moe_unfused_workspace_bytes.restype = sz
         L.moe_unfused_workspace_bytes.argtypes = [sp]
+        L.moe_forward_gemm_launches.restype = i32
+        L.moe_forward_gemm_launches.argtypes = [sp]
         L.moe_packed_weight_bytes.restype = sz
         L.moe_packed_weight_bytes.argtypes = [sp, i32]
         L.moe_route_topk.restype = i32
@@ -68,8 +70,10 @@ def lib() -> C.CDLL:
             fn = getattr(L, name)
             fn.restype = i32
             fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp]
-        L.moe_fused_forward_timed.restype = i32
-        L.moe_fused_forward_timed.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
+        for name in ("moe_fused_forward_timed", "moe_fused_forward_two_launch", "moe_fused_forward_one_launch"):
+            fn = getattr(L, name)
+            fn.restype = i32
+            fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
         L.moe_dispatch_gather.restype = i32
         L.moe_dispatch_gather.argtypes = [sp, vp, dp, vp, vp]
         L.moe_combine_reduce.restype = i32
@@ -188,6 +192,33 @@ def moe_fused_forward_timed(shape, x, topk_idx, topk_w, tables, packed_gate_up, 
     _check(lib().moe_fused_forward_timed(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
                                          C.byref(tables.struct), _ptr(packed_gate_up), _ptr(packed_down), _ptr(y),
                                          _ptr(workspace), nbytes, _stream(stream), arr), "moe_fused_forward_timed")
+
+
+def moe_forward_gemm_launches(shape) -> int:
+    return int(lib().moe_forward_gemm_launches(C.byref(shape)))
+
+
+def _forward_choice(name, shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace, events,
+                    workspace_bytes, stream):
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    arr = None if events is None else (C.c_void_p * 5)(*[C.c_void_p(int(e)) if e else None for e in events])
+    _check(getattr(lib(), name)(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w), C.byref(tables.struct),
+                                _ptr(packed_gate_up), _ptr(packed_down), _ptr(y), _ptr(workspace), nbytes,
+                                _stream(stream), arr), name)
+
+
+def moe_fused_forward_two_launch(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                                 events=None, workspace_bytes=None, stream=None) -> None:
+    """`events`: None or five raw hipEvent_t handles as for moe_fused_forward_timed."""
+    _forward_choice("moe_fused_forward_two_launch", shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down,
+                    y, workspace, events, workspace_bytes, stream)
+
+
+def moe_fused_forward_one_launch(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                                 events=None, workspace_bytes=None, stream=None) -> None:
+    """`events`: None or five raw hipEvent_t handles as for moe_fused_forward_timed."""
+    _forward_choice("moe_fused_forward_one_launch", shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down,
+                    y, workspace, events, workspace_bytes, stream)
 
 
 def moe_unfused_forward(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,

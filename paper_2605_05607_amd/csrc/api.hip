@@ -38,12 +38,13 @@ FwdLayout forward_layout(const moe_shape *s, const Derived &dv) {
     return at;
   };
   const size_t rows = (size_t)(dv.P_cap > 0 ? dv.P_cap : 1);
-  L.header = take(16 * sizeof(int32_t));
+  L.header = take(32 * sizeof(int32_t));
   L.work1 = take((size_t)dv.max_mtiles * dv.nt1 * 4 * sizeof(int32_t));
   L.work2 = take((size_t)dv.max_mtiles * dv.nt2 * 4 * sizeof(int32_t));
   L.row_tok = take(rows * sizeof(int32_t));
   L.row_w = take(rows * sizeof(float));
   L.row_sole = take(rows * sizeof(int32_t));
+  L.tile_ready = take((size_t)dv.max_mtiles * sizeof(int32_t));
   L.h = take(rows * (size_t)s->f * dv.elt);
   L.o = take(rows * (size_t)s->d * sizeof(float));
   L.total = off;
@@ -58,6 +59,14 @@ extern "C" size_t moe_forward_workspace_bytes(const moe_shape *shape) {
   Derived dv;
   if (check_shape(shape, &dv) != MOE_OK) return 0;
   return forward_layout(shape, dv).total;
+}
+
+extern "C" int moe_forward_gemm_launches(const moe_shape *shape) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK) return 0;
+  // one resident launch with the tile-level hand-over when the mean number of rows per expert, T k / E, is below
+  // one M tile; a kernel boundary between the GEMMs otherwise (and always for fp32 layers)
+  return shape->dtype == MOE_BF16 && (int64_t)shape->T * shape->k < (int64_t)shape->E * kBM ? 1 : 2;
 }
 
 extern "C" size_t moe_unfused_workspace_bytes(const moe_shape *shape) {

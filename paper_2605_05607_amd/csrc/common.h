@@ -47,13 +47,15 @@ inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : M
 
 // ---- layout of the forward workspace (offsets in bytes, 256-byte aligned) ----
 struct FwdLayout {
-  size_t header;    // int32[16]: [0] work items of GEMM-1, [1] P, [2] first layout row of the local segment,
-                    //            [3] work items of GEMM-2
+  size_t header;    // int32[32]: [0] work items of GEMM-1, [1] P, [2] first layout row of the local segment,
+                    //            [3] work items of GEMM-2, [4] M tiles, [8..23] queue tickets and [24] error flag
+                    //            of the resident GEMM kernel
   size_t work1;     // int4[max_mtiles * nt1]  (local expert, first local row, valid rows, N tile) per work item
   size_t work2;     // int4[max_mtiles * nt2]
   size_t row_tok;   // int32[P_cap]       token of each local row
   size_t row_w;     // float[P_cap]       gate weight of each local row
   size_t row_sole;  // int32[P_cap]       the row's token if it is that token's only local slot, else -1
+  size_t tile_ready;  // int32[max_mtiles] GEMM-1 items finished per M tile (hand-over inside the resident kernel)
   size_t h;         // elt  [P_cap, f]
   size_t o;         // float[P_cap, d]
   size_t total;

@@ -57,9 +57,11 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 // ------------------------------------------------------------------------------------------------
 // Work lists and per-row metadata of the local layout segment.
 // header[0] = work items of GEMM-1, header[1] = P (local rows), header[2] = first layout row of the segment,
-// header[3] = work items of GEMM-2.
+// header[3] = work items of GEMM-2, header[4] = M tiles; header[8..15] / [16..23] = ticket counters of the GEMM-1 /
+// GEMM-2 queues and header[24] = error flag of the resident GEMM kernel (all cleared here).
 //
-// A work item is one output tile (expert, M tile, N tile).  Full M tiles come first and the partial tile of each
+// A work item is one output tile (expert, M tile, N tile): int4 (local expert, first local row, valid rows,
+// N tile | M-tile id << 12).  Full M tiles come first and the partial tile of each
 // expert (its last rows) afterwards, largest first, so that the launch ends with its shortest items; partial
 // tiles of at most 64 rows (pure weight streaming) are mixed into the full tiles (see the list order below).
 // The order of the list is also what keeps the L2 useful:
@@ -69,6 +71,7 @@ __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict
 // that are resident on an XCD at the same time share a few A slabs and a few weight panels instead of
 // streaming 32 different ones through the L2.
 // ------------------------------------------------------------------------------------------------
+constexpr int kTileShift = 12;  // work item .w = N tile | M-tile id << kTileShift
 constexpr int kChunk = 32;  // work items that are resident on one XCD at a time (one per CU)
 constexpr int kChunkM = 8;  // M tiles per chunk (at most)
 
@@ -99,7 +102,8 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
                                                        int4 *__restrict__ work2, int32_t *__restrict__ row_tok,
                                                        float *__restrict__ row_w,
                                                        const int32_t *__restrict__ topk_idx,
-                                                       int32_t *__restrict__ row_sole) {
+                                                       int32_t *__restrict__ row_sole,
+                                                       int32_t *__restrict__ tile_ready) {
   // LDS: full0[E_loc + 1] first full M tile of each expert | part[E_loc] rows of its partial tile (0 = none) |
   //      order[E_loc] partial tiles: first the large ones (> kStreamRows rows), largest first, then the
   //      streaming ones, largest first | 17 ints of scan scratch
@@ -175,7 +179,10 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     header[1] = P;
     header[2] = base;
     header[3] = n2;
+    header[4] = n_tiles;
+    for (int i = 8; i <= 24; ++i) header[i] = 0;
   }
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles; i += gridDim.x * blockDim.x) tile_ready[i] = 0;
   for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < n1 + n2; q += gridDim.x * blockDim.x) {
     const bool second = q >= n1;
     const int Nt = second ? nt2 : nt1;
@@ -201,7 +208,7 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       else if ((r -= f_rem) < nB) { cls = 1; idx = r; }
       else { cls = 2; idx = n_mix * nsc + (r - nB); }
     }
-    int le, mt, nt, rows;
+    int le, mt, nt, rows, tile;
     if (cls == 0) {
       // expert that owns F position idx: largest le with full0[le] * Nt <= idx
       int a = 0, b = E_loc;
@@ -226,15 +233,17 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       mt = mg * Mg + r / Gcur;
       nt = ng * G + r % Gcur;
       rows = bm;
+      tile = full0[le] + mt;
     } else {
       le = order[(cls == 2 ? n_big : 0) + idx / Nt];
+      tile = n_full + (cls == 2 ? n_big : 0) + idx / Nt;
       nt = idx % Nt;
       const int cnt = min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base);
       mt = cnt / bm;
       rows = part[le];
     }
     const int start = min(P, offsets[e_lo + le] - base);
-    const int4 item = make_int4(le, start + mt * bm, rows, nt);
+    const int4 item = make_int4(le, start + mt * bm, rows, nt | (tile << kTileShift));
     if (second) work2[qq] = item; else work1[qq] = item;
   }
 }
@@ -275,10 +284,14 @@ constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
 constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
 constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue patch (fits 8 x in the stages)
 
-template <bool GATED, int NB, int NA, int DEPTH>
+template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
                                                int rows, int nblk_total) {
-  const int tid = threadIdx.x;
+  // RESIDENT (the kernel that loops over items): the thread index goes through an empty asm so that nothing
+  // derived from it counts as loop invariant; hoisting those values across items costs more registers than the
+  // tile has to spare.
+  int tid = threadIdx.x;
+  if (RESIDENT) asm volatile("" : "+v"(tid));
   const int lane = tid & 63;
   const int w8 = tid >> 6;
   const int wm = w8 >> 2, wn = w8 & 3;
@@ -535,18 +548,16 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   }
 }
 
-template <bool GATED>
-__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  const int q = chunked_item(blockIdx.x, *g.n_items);
-  if (q < 0) return;
-  const int4 item = g.work[q];
-  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w;
+// One work item on the matrix cores.  Wave-uniform dispatch on the number of valid 32-row blocks: every variant
+// executes the same sequence of barriers.
+template <bool GATED, bool RESIDENT>
+__device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item) {
+  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
-  // wave-uniform dispatch: every variant executes the same sequence of barriers
-#define MOE355_TILE(NB_, NA_) gemm_bf16_tile<GATED, NB_, NA_, (NA_ == 1 ? 2 : 1)>(g, smem, nt, le, m0, rows, nblk_total)
+#define MOE355_TILE(NB_, NA_) \
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1)>(g, smem, nt, le, m0, rows, nblk_total)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -556,6 +567,102 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmAr
     else MOE355_TILE(1, 4);
   }
 #undef MOE355_TILE
+}
+
+// One workgroup per work item; workgroup -> item by chunked_item.
+template <bool GATED>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  const int q = chunked_item(blockIdx.x, *g.n_items);
+  if (q < 0) return;
+  gemm_bf16_item<GATED, false>(g, smem, g.work[q]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// GEMM-1 and GEMM-2 of a layer in ONE launch of resident workgroups (one per CU), the one-GPU form of the
+// tile-granular GEMM-1 => GEMM-2 hand-over of the fused kernel (Sec. IV-A, IV-B): a GEMM-2 tile starts as soon
+// as the h rows of its M tile are complete, so the CUs that run out of GEMM-1 work (a launch of a few hundred
+// tiles of ~100 us ends with many CUs idle) continue with GEMM-2 instead of waiting for a kernel boundary.
+// moe_fused_forward uses it for bf16 layers whose experts get less than one full M tile of rows on average (the
+// launches are then dominated by partial tiles and by the tail of the few large experts; measured 5 % faster on the
+// DeepSeek-shaped load); with fuller experts the ticket, fence and poll per item cost 2-6 % more than the idle
+// tail they remove, and the kernel boundary of moe_fused_forward_two_launch is used instead.
+//
+// Work distribution: both lists are cut into 8 queues exactly as a plain launch would spread them over the XCDs
+// (queue x = virtual blocks x, x + 8, ...; see chunked_item); a workgroup draws tickets from its home queue
+// (blockIdx % 8, the XCD it runs on) and, when that is empty, from the others.  It moves on to GEMM-2 only after
+// it has seen every GEMM-1 queue empty, i.e. when every GEMM-1 item is already in the hands of a running
+// workgroup; GEMM-1 items never wait, so the counter a GEMM-2 item polls is always completed by workgroups that
+// make progress: no deadlock for any number of resident workgroups and any placement.
+// Hand-over: the producers of an M tile store h, fence at device scope, and count themselves in tile_ready;
+// the consumer polls the counter, then fences before it loads h (the L2s of the XCDs are not coherent with
+// each other, the device-scope fences write back / invalidate them).
+// ------------------------------------------------------------------------------------------------
+struct PipelineArgs {
+  GemmArgs g1, g2;
+  int32_t *tickets;     // [16]: queues of GEMM-1, then of GEMM-2
+  int32_t *tile_ready;  // [M tiles] GEMM-1 items finished per M tile
+  int32_t *error;       // set if a wait gave up (cannot happen unless the lists are corrupt)
+  int nt1;              // GEMM-1 items per M tile
+};
+
+constexpr int kMaxPolls = 1 << 22;  // x ~1 us: a bound so that no wave can wait forever
+
+// All items of one GEMM that this workgroup can get hold of: home queue first, then the other queues.
+template <bool GATED>
+__device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char *smem, int *s_item,
+                                                int32_t *__restrict__ tickets, int32_t *__restrict__ tile_ready,
+                                                int32_t *__restrict__ error, int nt1) {
+  const int home = blockIdx.x & 7;
+  const int n_items = *g.n_items;
+  const int n_virtual = (n_items + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk);
+  int qsel = 0;
+  while (qsel < 8) {
+    const int queue = (home + qsel) & 7;
+    __syncthreads();  // the previous item is done with the LDS (and with *s_item)
+    if (threadIdx.x == 0) {
+      const int v = queue + 8 * atomicAdd(&tickets[queue], 1);
+      *s_item = v < n_virtual ? chunked_item(v, n_items) : -2;
+    }
+    __syncthreads();
+    const int q = *s_item;
+    if (q == -2) {  // queue exhausted
+      ++qsel;
+      continue;
+    }
+    if (q < 0) continue;  // a virtual block without an item
+    const int4 item = g.work[q];
+    const int tile = item.w >> kTileShift;
+    if (GATED) {
+      gemm_bf16_item<true, true>(g, smem, item);
+      __syncthreads();  // every thread's h stores happen before thread 0's release ...
+      if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // ... which makes them visible device-wide ...
+        atomicAdd(&tile_ready[tile], 1);                     // ... before the item is counted
+      }
+    } else {
+      if (threadIdx.x == 0) {
+        int polls = 0;
+        while (__hip_atomic_load(&tile_ready[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nt1) {
+          __builtin_amdgcn_s_sleep(32);
+          if (++polls > kMaxPolls) {
+            *error = 1;
+            break;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // order the loads of h after the counter
+      }
+      __syncthreads();
+      gemm_bf16_item<false, true>(g, smem, item);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(const PipelineArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  __shared__ int s_item;
+  gemm_bf16_drain<true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
+  gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -569,7 +676,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
   const int q = chunked_item(blockIdx.x, *g.n_items);
   if (q < 0) return;
   const int4 item = g.work[q];
-  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w;
+  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
   const int tid = threadIdx.x;
   const int ty = tid >> 4, tx = tid & 15;
   const float *A = static_cast<const float *>(g.A);
@@ -770,7 +877,7 @@ __global__ __launch_bounds__(256) void cast_rows_kernel(const float *__restrict_
 // Host-side launch helpers
 // ------------------------------------------------------------------------------------------------
 struct Ws {
-  int32_t *header, *row_tok, *row_sole;
+  int32_t *header, *row_tok, *row_sole, *tile_ready;
   int4 *work1, *work2;
   float *row_w;
   void *h;
@@ -786,6 +893,7 @@ static Ws carve(void *workspace, const FwdLayout &L) {
   w.row_tok = reinterpret_cast<int32_t *>(b + L.row_tok);
   w.row_w = reinterpret_cast<float *>(b + L.row_w);
   w.row_sole = reinterpret_cast<int32_t *>(b + L.row_sole);
+  w.tile_ready = reinterpret_cast<int32_t *>(b + L.tile_ready);
   w.h = b + L.h;
   w.o = reinterpret_cast<float *>(b + L.o);
   return w;
@@ -797,7 +905,7 @@ static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch
   const int blocks = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (dv.P_cap + 255) / 256));
   hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), (size_t)(3 * dv.E_loc + 1 + 17) * sizeof(int), st,
                      tb->offsets, tb->perm, topk_w, s->T, s->k, dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles,
-                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w, topk_idx, sole);
+                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w, topk_idx, sole, w.tile_ready);
   return launch_status();
 }
 
@@ -805,7 +913,7 @@ static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch
 // GEMM-1: the token matrix with the row -> token map (fused gather) or a materialised copy (map == nullptr).
 static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, const int32_t *a1_map, int a1_ld,
                         const void *packed_gu, const void *packed_down, const Ws &w, const int32_t *sole, void *y,
-                        hipStream_t st, void *const *events = nullptr) {
+                        hipStream_t st, void *const *events = nullptr, bool pipelined = false) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
@@ -832,6 +940,24 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
     if (!lds_ok) return MOE_ERR_HIP;
     g1.n_ntiles = ceil_div(s->f, kBN / 2); g1.n_ktiles = ceil_div(s->d, kBK);
     g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kBK);
+    if (pipelined) {
+      static const bool pipe_ok =
+          hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_pipeline_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes) == hipSuccess;
+      // one resident workgroup per CU (each takes most of a CU's LDS)
+      int dev = 0, n_cu = 0;
+      if (!pipe_ok || hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+        return MOE_ERR_HIP;
+      PipelineArgs pa;
+      pa.g1 = g1; pa.g2 = g2;
+      pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1;
+      hipLaunchKernelGGL(gemm_bf16_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
+                         pa);
+      mark(2);
+      mark(3);
+      return launch_status();
+    }
     hipLaunchKernelGGL(gemm_bf16_kernel<true>, grid_of(dv.nt1), dim3(kGemmThreads), 2 * kStageBytes, st,
                        g1);
     int rc = launch_status();
@@ -907,7 +1033,7 @@ extern "C" int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
 static int forward_common(const moe_shape *shape, const void *x, const int32_t *topk_idx, const float *topk_w,
                           const moe_dispatch *tables, const void *packed_gate_up, const void *packed_down, void *y,
                           void *workspace, size_t workspace_bytes, void *stream, bool fused,
-                          void *const *events = nullptr) {
+                          void *const *events = nullptr, int gemm_launches = 0) {
   Derived dv;
   int rc = check_shape(shape, &dv);
   if (rc != MOE_OK) return rc;
@@ -917,6 +1043,11 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MOE_ERR_INVALID_ARG;
   if ((int64_t)dv.max_mtiles * std::max(dv.nt1, dv.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
+  // gemm_launches: 0 = by shape, 1 = resident kernel with the tile-level hand-over (bf16 only), 2 = two launches
+  if (gemm_launches == 1 && shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  const bool pipelined = (gemm_launches ? gemm_launches : moe_forward_gemm_launches(shape)) == 1;
+  // a work item packs its N tile and its M-tile id into one word
+  if (std::max(dv.nt1, dv.nt2) >= 1 << kTileShift || dv.max_mtiles >= 1 << (31 - kTileShift)) return MOE_ERR_UNSUPPORTED;
   // the GEMM kernels address A rows with 32-bit element offsets (row * row length)
   if (std::max<int64_t>(shape->T, dv.P_cap) * std::max(shape->d, shape->f) >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
   if (shape->T == 0) return MOE_OK;
@@ -934,7 +1065,7 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   mark(1);
   if (fused) {
     if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, sole, y, st,
-                           events)) != MOE_OK)
+                           events, pipelined)) != MOE_OK)
       return rc;
     rc = launch_combine(shape, dv, w.o, topk_idx, tables, y, sole != nullptr, st);
     mark(4);
@@ -949,7 +1080,8 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   hipLaunchKernelGGL(gather_rows_kernel, dim3((unsigned)rows), dim3(256), 0, st, static_cast<const uint4 *>(x),
                      w.header, w.row_tok, row_chunks, static_cast<uint4 *>(xs));
   if ((rc = launch_status()) != MOE_OK) return rc;
-  if ((rc = launch_gemms(shape, dv, xs, nullptr, shape->d, packed_gate_up, packed_down, w, nullptr, nullptr, st)) != MOE_OK) return rc;
+  if ((rc = launch_gemms(shape, dv, xs, nullptr, shape->d, packed_gate_up, packed_down, w, nullptr, nullptr, st, nullptr,
+                         pipelined)) != MOE_OK) return rc;
   const size_t n = (size_t)shape->T * shape->d;
   hipLaunchKernelGGL(fill_zero_kernel, dim3(2048), dim3(256), 0, st, reinterpret_cast<float4 *>(y32), n / 4);
   hipLaunchKernelGGL(scatter_add_kernel, dim3((unsigned)rows), dim3(256), 0, st, w.o, w.header, w.row_tok, shape->d,
@@ -975,6 +1107,24 @@ extern "C" int moe_fused_forward_timed(const moe_shape *shape, const void *x, co
   if (!events) return MOE_ERR_INVALID_ARG;
   return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
                         workspace_bytes, stream, true, events);
+}
+
+extern "C" int moe_fused_forward_two_launch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                            const float *topk_w, const moe_dispatch *tables,
+                                            const void *packed_gate_up, const void *packed_down, void *y,
+                                            void *workspace, size_t workspace_bytes, void *stream,
+                                            void *const *events) {
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, events, 2);
+}
+
+extern "C" int moe_fused_forward_one_launch(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                            const float *topk_w, const moe_dispatch *tables,
+                                            const void *packed_gate_up, const void *packed_down, void *y,
+                                            void *workspace, size_t workspace_bytes, void *stream,
+                                            void *const *events) {
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, events, 1);
 }
 
 extern "C" int moe_unfused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,

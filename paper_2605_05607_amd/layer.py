@@ -62,6 +62,14 @@ class MoELayer:
         B.moe_fused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
                             self.packed_down, self.y, self.forward_ws)
 
+    def forward_two_launch(self, x, events=None) -> None:
+        B.moe_fused_forward_two_launch(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
+                                       self.packed_down, self.y, self.forward_ws, events)
+
+    def forward_one_launch(self, x, events=None) -> None:
+        B.moe_fused_forward_one_launch(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
+                                       self.packed_down, self.y, self.forward_ws, events)
+
     def forward_unfused(self, x) -> None:
         B.moe_unfused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
                               self.packed_down, self.y, self.forward_ws)

@@ -59,6 +59,14 @@ def test_unsupported_dtype_and_extent():
         == B.MOE_ERR_UNSUPPORTED
 
 
+def test_gemm_launch_rule_follows_rows_per_expert():
+    lib = B.lib()
+    assert lib.moe_forward_gemm_launches(C.byref(good_shape(T=4096, E=256, k=8, R=8))) == 1   # 128 rows per expert
+    assert lib.moe_forward_gemm_launches(C.byref(good_shape(T=8192, E=256, k=8, R=8))) == 2   # 256
+    assert lib.moe_forward_gemm_launches(C.byref(good_shape(T=8, E=8, k=2, R=1, local_rank_end=1, dtype=B.MOE_F32))) == 2
+    assert lib.moe_forward_gemm_launches(C.byref(good_shape(E=6, R=4))) == 0                 # invalid shape
+
+
 def test_forward_rejects_extents_beyond_32bit_row_offsets():
     lib = B.lib()
     s = good_shape(T=1 << 20, d=8192, f=8192, k=2)
