@@ -1,0 +1,412 @@
+// Grouped bf16 GEMMs on the matrix cores: tile, work item, the per-item kernels and the resident kernel.
+#pragma once
+#include "forward_types.h"
+
+namespace moe355 {
+
+// ------------------------------------------------------------------------------------------------
+// Grouped bf16 GEMM on the matrix cores.  C[rows of one expert tile, kBN/2 or kBN columns] = A * W_e.
+//   A rows   : row_map == nullptr -> A[m0 + r, :]; else A[row_map[m0 + r], :] (token gather of Dispatch).
+//   B tiles  : packed LDS images streamed linearly.
+//   GATED    : epilogue h = silu(g) * u, written as bf16   (GEMM-1)
+//   !GATED   : epilogue o = acc * row_w[row], written fp32 (GEMM-2, gate weight of Sec. III-C)
+// Tile 256 x 256 x 64, one workgroup of 512 threads per CU.  Every operand byte enters the CU once (global ->
+// registers -> LDS) because the L2 -> CU path, not the matrix core, is what saturates first on this chip;
+// sharing goes through the LDS, which has bandwidth to spare.  8 waves = 2 (rows) x 4 (columns), each wave
+// owns 128 x 64 as 4 x 2 MFMA 32x32x16 accumulators; two waves per SIMD cover each other's LDS latency.
+// LDS is double buffered (2 x 64 KiB) with one barrier per k-step; the next slab is in flight in registers
+// while the current one is multiplied.  NB = number of 32-row blocks of this wave that hold valid rows (the
+// others are skipped: small experts are weight-streaming bound and need no padding math).
+// ------------------------------------------------------------------------------------------------
+
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+constexpr int kGemmThreads = 512;
+constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
+constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
+constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue patch (fits 8 x in the stages)
+
+template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH>
+__device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
+                                               int rows, int nblk_total) {
+  // RESIDENT (the kernel that loops over items): the thread index goes through an empty asm so that nothing
+  // derived from it counts as loop invariant; hoisting those values across items costs more registers than the
+  // tile has to spare.
+  int tid = threadIdx.x;
+  if (RESIDENT) asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  const int w8 = tid >> 6;
+  const int wm = w8 >> 2, wn = w8 & 3;
+
+  // ---- global -> register staging (scalars, not arrays, so nothing lands in scratch) ----
+  // A: thread t stages chunk t & 7 (8 reduction indices) of rows (t >> 3) + 64 i; B: chunks t + 512 i
+  const int a_chunk = tid & 7;
+  const int a_row0 = tid >> 3;  // 0..63
+  const bf16_t *a_base = static_cast<const bf16_t *>(g.A) + a_chunk * 8;
+#define MOE355_A_ROW(i)                                                                          \
+  const int a_rc##i = a_row0 + 64 * i < rows ? a_row0 + 64 * i : rows - 1; /* padding: a valid row */ \
+  const uint32_t a_off##i =                                                                      \
+      (uint32_t)(g.row_map ? g.row_map[m0 + a_rc##i] : m0 + a_rc##i) * (uint32_t)g.lda;
+  MOE355_A_ROW(0) MOE355_A_ROW(1) MOE355_A_ROW(2) MOE355_A_ROW(3)
+#undef MOE355_A_ROW
+  // LDS destination of row a_row0; row + 64 i lies 8192 bytes further (64 i keeps the swizzle bits)
+  const int a_dst = (a_row0 * 8 + (a_chunk ^ ((a_row0 >> 1) & 7))) * 16;
+  const unsigned char *b_src =
+      static_cast<const unsigned char *>(g.Bp) + ((size_t)(le * g.n_ntiles + nt) * g.n_ktiles) * kTileBytes + tid * 16;
+
+  // Register slab sets.  Set x always exists; set y is used when DEPTH == 2 (two slabs in flight: tiles with at
+  // most 64 rows are pure weight streaming, their accumulators are small, and what limits them is the number of
+  // bytes a CU keeps in flight towards HBM).
+  u32x4 ra0x, ra1x, ra2x, ra3x, rb0x, rb1x, rb2x, rb3x;
+  u32x4 ra0y, ra1y, ra2y, ra3y, rb0y, rb1y, rb2y, rb3y;
+  // A slab is moved in three portions: {ra0, ra1, rb0}, {ra2, ra3, rb1}, {rb2, rb3}
+  // k tail: a chunk past K is replaced by chunk 0 of the same row (valid memory, finite data); the packed B
+  // tile is zero there, so it contributes nothing and no select has to wait on the load
+#define MOE355_A_OFF(KT) ((KT) * kBK + a_chunk * 8 < g.K ? (KT) * kBK : -a_chunk * 8)
+  // NA = row loads per thread that reach valid rows (1: rows < 64, 2: rows < 128, 4: all); the others are skipped
+#define MOE355_LOAD_P0(S, KT)                                                                       \
+  do {                                                                                              \
+    ra0##S = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + MOE355_A_OFF(KT));                  \
+    if (NA > 1) ra1##S = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + MOE355_A_OFF(KT));      \
+    rb0##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes);                   \
+  } while (0)
+#define MOE355_LOAD_P1(S, KT)                                                                       \
+  do {                                                                                              \
+    if (NA > 2) ra2##S = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + MOE355_A_OFF(KT));      \
+    if (NA > 2) ra3##S = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + MOE355_A_OFF(KT));      \
+    rb1##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 8192);            \
+  } while (0)
+#define MOE355_LOAD_P2(S, KT)                                                                       \
+  do {                                                                                              \
+    rb2##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 16384);           \
+    rb3##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 24576);           \
+  } while (0)
+#define MOE355_STORE_P0(S, BUF)                                                                     \
+  do {                                                                                              \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                                 \
+    *reinterpret_cast<u32x4 *>(s_ + a_dst) = ra0##S;                                                \
+    if (NA > 1) *reinterpret_cast<u32x4 *>(s_ + a_dst + 8192) = ra1##S;                             \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16) = rb0##S;                              \
+  } while (0)
+#define MOE355_STORE_P1(S, BUF)                                                                     \
+  do {                                                                                              \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                                 \
+    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 16384) = ra2##S;                            \
+    if (NA > 2) *reinterpret_cast<u32x4 *>(s_ + a_dst + 24576) = ra3##S;                            \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 8192) = rb1##S;                       \
+  } while (0)
+#define MOE355_STORE_P2(S, BUF)                                                                     \
+  do {                                                                                              \
+    unsigned char *s_ = smem + (BUF) * kStageBytes;                                                 \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 16384) = rb2##S;                      \
+    *reinterpret_cast<u32x4 *>(s_ + kAStageBytes + tid * 16 + 24576) = rb3##S;                      \
+  } while (0)
+
+  f32x16 acc[NB > 0 ? NB : 1][2];
+#pragma unroll
+  for (int mi = 0; mi < NB; ++mi)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][j][r] = 0.f;
+
+  // ---- LDS -> MFMA operand addressing: lane l reads row l & 31 of a 32-row block, k half l >> 5 ----
+  const int l31 = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
+  const int a_rd = (wm * 128 + l31) * 128;                  // + mi * 4096
+  const int b_rd = kAStageBytes + (wn * 64 + l31) * 128;    // + j * 4096
+
+  constexpr int NF = NB > 0 ? NB : 1;
+  bf16x8 fa0[NF], fb0[2], fa1[NF], fb1[2];  // operand fragments of two consecutive k-substeps
+#define MOE355_READ_FRAGS(FA, FB, STAGE, KK)                                                           \
+  do {                                                                                                 \
+    const int slot_ = (((KK) * 2 + khalf) ^ sw) * 16;                                                  \
+    _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) FA[mi] =                                         \
+        *reinterpret_cast<const bf16x8 *>((STAGE) + a_rd + mi * 4096 + slot_);                         \
+    if (NB > 0) {                                                                                      \
+      FB[0] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + slot_);                               \
+      FB[1] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + 4096 + slot_);                        \
+    }                                                                                                  \
+  } while (0)
+#define MOE355_MFMAS(FA, FB)                                                                           \
+  do {                                                                                                 \
+    _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) {                                                \
+      acc[mi][0] = mfma_bf16(FA[mi], FB[0], acc[mi][0]);                                               \
+      acc[mi][1] = mfma_bf16(FA[mi], FB[1], acc[mi][1]);                                               \
+    }                                                                                                  \
+  } while (0)
+
+  // Pipeline.  At the top of k-step kt: LDS stage kt & 1 holds slab kt, a register set holds slab kt + 1 (its
+  // loads were issued DEPTH k-steps ago, in three portions), and fa0 / fb0 hold the operands of substep 0.
+  // Substeps 0..2 each multiply, fetch the next substep's operands, move one portion of the register set into the
+  // other stage and reissue that portion's loads for slab kt + 1 + DEPTH, so the global loads, the LDS stores and
+  // the LDS reads are all spread under the MFMAs instead of forming a burst around the barrier.  The single
+  // barrier sits before substep 3, whose operands are already in registers; substep 3 also fetches substep 0 of
+  // the next slab.  Reloads past the last k-step repeat the last slab: in bounds, never used.
+  // Requested instruction order (sched_group_barrier masks: 0x008 MFMA, 0x020 VMEM read, 0x100 DS read,
+  // 0x200 DS write).
+#define MOE355_ORDER(NW)                                                                                \
+  do {                                                                                                 \
+    if (NB > 0) {                                                                                      \
+      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);                                          \
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                          \
+    }                                                                                                  \
+    if ((NW) > 0) {                                                                                    \
+      __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                            \
+      __builtin_amdgcn_sched_group_barrier(0x020, (NW), 0);                                            \
+    }                                                                                                  \
+  } while (0)
+#define MOE355_KSTEP(S, KT_, KPRE)                                                                      \
+  do {                                                                                                 \
+    const unsigned char *sCur = smem + ((KT_) & 1) * kStageBytes;                                      \
+    const int nxt = ((KT_) & 1) ^ 1;                                                                   \
+    const int kp_ = min((KPRE), kt_last);                                                              \
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 1);                                                              \
+    MOE355_MFMAS(fa0, fb0);                                                                            \
+    MOE355_STORE_P0(S, nxt);                                                                           \
+    MOE355_LOAD_P0(S, kp_);                                                                            \
+    MOE355_READ_FRAGS(fa0, fb0, sCur, 2);                                                              \
+    MOE355_MFMAS(fa1, fb1);                                                                            \
+    MOE355_STORE_P1(S, nxt);                                                                           \
+    MOE355_LOAD_P1(S, kp_);                                                                            \
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 3);                                                              \
+    MOE355_MFMAS(fa0, fb0);                                                                            \
+    MOE355_STORE_P2(S, nxt);                                                                           \
+    MOE355_LOAD_P2(S, kp_);                                                                            \
+    MOE355_ORDER(NA > 1 ? 3 : 2);                                                                      \
+    MOE355_ORDER(NA > 2 ? 3 : 1);                                                                      \
+    MOE355_ORDER(2);                                                                                   \
+    __syncthreads();                                                                                   \
+    MOE355_READ_FRAGS(fa0, fb0, smem + nxt * kStageBytes, 0);                                          \
+    MOE355_MFMAS(fa1, fb1);                                                                            \
+    MOE355_ORDER(0);                                                                                   \
+  } while (0)
+
+  const int KT = g.n_ktiles;
+  const int kt_last = KT - 1;
+  MOE355_LOAD_P0(x, 0); MOE355_LOAD_P1(x, 0); MOE355_LOAD_P2(x, 0);
+  MOE355_STORE_P0(x, 0); MOE355_STORE_P1(x, 0); MOE355_STORE_P2(x, 0);
+  {
+    const int k1 = min(1, kt_last);
+    MOE355_LOAD_P0(x, k1); MOE355_LOAD_P1(x, k1); MOE355_LOAD_P2(x, k1);
+    if (DEPTH == 2) {
+      const int k2 = min(2, kt_last);
+      MOE355_LOAD_P0(y, k2); MOE355_LOAD_P1(y, k2); MOE355_LOAD_P2(y, k2);
+    }
+  }
+  __syncthreads();
+  MOE355_READ_FRAGS(fa0, fb0, smem, 0);
+
+  if (DEPTH == 1) {
+    for (int kt = 0; kt < KT; ++kt) MOE355_KSTEP(x, kt, kt + 2);
+  } else {
+    // set x carries the odd slabs, set y the even ones
+    for (int kt = 0; kt < KT; kt += 2) {
+      MOE355_KSTEP(x, kt, kt + 3);
+      if (kt + 1 < KT) MOE355_KSTEP(y, kt + 1, kt + 4);
+    }
+  }
+#undef MOE355_KSTEP
+#undef MOE355_ORDER
+#undef MOE355_READ_FRAGS
+#undef MOE355_MFMAS
+#undef MOE355_LOAD_P0
+#undef MOE355_LOAD_P1
+#undef MOE355_LOAD_P2
+#undef MOE355_STORE_P0
+#undef MOE355_STORE_P1
+#undef MOE355_STORE_P2
+#undef MOE355_A_OFF
+
+  // ---- epilogue ----
+  // Accumulator register r of lane l holds C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 block, i.e. a lane
+  // owns one column.  Each wave turns its blocks around through a private LDS patch (the stages are dead now)
+  // so that the global stores are 16 bytes per lane along a row instead of one element per lane.
+  __syncthreads();  // every wave has finished reading the stages
+  unsigned char *patch = smem + w8 * kPatchBytes;
+#pragma unroll
+  for (int mi = 0; mi < NB; ++mi) {
+    const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
+    if (GATED) {
+      // h block: 32 rows x 32 columns bf16, row pitch 80 bytes (keeps the two half-waves on different banks)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+        const float gv = acc[mi][0][r], uv = acc[mi][1][r];
+        *reinterpret_cast<bf16_t *>(patch + rl * 80 + l31 * 2) = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {
+        const int c = it * 64 + lane;        // 16-byte chunk: 4 chunks per row
+        const int rl = c >> 2, cc = c & 3;
+        const int row_l = blk_row0 + rl;
+        const int col = nt * (kBN / 2) + wn * 32 + cc * 8;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + rl * 80 + cc * 16);
+        if (row_l < rows && col < g.N)
+          *reinterpret_cast<u32x4 *>(static_cast<bf16_t *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+      }
+    } else {
+      // o block: 32 rows x 64 columns fp32, row pitch 288 bytes.  A row whose token has no other local slot
+      // is final already (the Combine sum would have one term): it goes to y in the output type, skipping o.
+      int sole[8];
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int row_l = blk_row0 + it * 4 + (lane >> 4);
+        sole[it] = (g.row_sole && row_l < rows) ? g.row_sole[m0 + row_l] : -1;
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+        const int row_l = blk_row0 + rl;
+        const float wgt = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
+        *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = acc[mi][0][r] * wgt;
+        *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) = acc[mi][1][r] * wgt;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int rl = it * 4 + (lane >> 4), cc = lane & 15;  // 16 chunks of 16 bytes per row
+        const int row_l = blk_row0 + rl;
+        const int col = nt * kBN + wn * 64 + cc * 4;
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 16);
+        if (row_l < rows && col < g.N) {
+          if (sole[it] >= 0) {
+            bf16x4 b;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) b[q] = (bf16_t)(v[q] + 0.0f);  // + 0 as in the sum that starts from zero
+            *reinterpret_cast<bf16x4 *>(static_cast<bf16_t *>(g.y) + (size_t)sole[it] * g.ldo + col) = b;
+          } else {
+            *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the patch is reused by the next block
+  }
+}
+
+// One work item on the matrix cores.  Wave-uniform dispatch on the number of valid 32-row blocks: every variant
+// executes the same sequence of barriers.
+template <bool GATED, bool RESIDENT>
+__device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item) {
+  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
+  const int nblk_total = (rows + 31) >> 5;                        // 1..8
+  const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
+  const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
+#define MOE355_TILE(NB_, NA_) \
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1)>(g, smem, nt, le, m0, rows, nblk_total)
+  if (nblk_total <= 2) {
+    if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
+  } else if (nblk_total <= 4) {
+    if (nb == 4) MOE355_TILE(4, 2); else if (nb == 3) MOE355_TILE(3, 2); else MOE355_TILE(0, 2);
+  } else {
+    if (nb == 4) MOE355_TILE(4, 4); else if (nb == 3) MOE355_TILE(3, 4); else if (nb == 2) MOE355_TILE(2, 4);
+    else MOE355_TILE(1, 4);
+  }
+#undef MOE355_TILE
+}
+
+// One workgroup per work item; workgroup -> item by chunked_item.
+template <bool GATED>
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  const int q = chunked_item(blockIdx.x, *g.n_items);
+  if (q < 0) return;
+  gemm_bf16_item<GATED, false>(g, smem, g.work[q]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// GEMM-1 and GEMM-2 of a layer in ONE launch of resident workgroups (one per CU), the one-GPU form of the
+// tile-granular GEMM-1 => GEMM-2 hand-over of the fused kernel (Sec. IV-A, IV-B): a GEMM-2 tile starts as soon
+// as the h rows of its M tile are complete, so the CUs that run out of GEMM-1 work (a launch of a few hundred
+// tiles of ~100 us ends with many CUs idle) continue with GEMM-2 instead of waiting for a kernel boundary.
+// moe_fused_forward uses it for bf16 layers whose experts get less than one full M tile of rows on average (the
+// launches are then dominated by partial tiles and by the tail of the few large experts; measured 5 % faster on the
+// DeepSeek-shaped load); with fuller experts the ticket, fence and poll per item cost 2-6 % more than the idle
+// tail they remove, and the kernel boundary of moe_fused_forward_two_launch is used instead.
+//
+// Work distribution: both lists are cut into 8 queues exactly as a plain launch would spread them over the XCDs
+// (queue x = virtual blocks x, x + 8, ...; see chunked_item); a workgroup draws tickets from its home queue
+// (blockIdx % 8, the XCD it runs on) and, when that is empty, from the others.  It moves on to GEMM-2 only after
+// it has seen every GEMM-1 queue empty, i.e. when every GEMM-1 item is already in the hands of a running
+// workgroup; GEMM-1 items never wait, so the counter a GEMM-2 item polls is always completed by workgroups that
+// make progress: no deadlock for any number of resident workgroups and any placement.
+// Hand-over: the producers of an M tile store h, fence at device scope, and count themselves in tile_ready;
+// the consumer polls the counter, then fences before it loads h (the L2s of the XCDs are not coherent with
+// each other, the device-scope fences write back / invalidate them).
+// ------------------------------------------------------------------------------------------------
+struct PipelineArgs {
+  GemmArgs g1, g2;
+  int32_t *tickets;     // [16]: queues of GEMM-1, then of GEMM-2
+  int32_t *tile_ready;  // [M tiles] GEMM-1 items finished per M tile
+  int32_t *error;       // set if a wait gave up (cannot happen unless the lists are corrupt)
+  int nt1;              // GEMM-1 items per M tile
+};
+
+constexpr int kMaxPolls = 1 << 22;  // x ~1 us: a bound so that no wave can wait forever
+
+// All items of one GEMM that this workgroup can get hold of: home queue first, then the other queues.
+template <bool GATED>
+__device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char *smem, int *s_item,
+                                                int32_t *__restrict__ tickets, int32_t *__restrict__ tile_ready,
+                                                int32_t *__restrict__ error, int nt1) {
+  const int home = blockIdx.x & 7;
+  const int n_items = *g.n_items;
+  const int n_virtual = (n_items + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk);
+  int qsel = 0;
+  while (qsel < 8) {
+    const int queue = (home + qsel) & 7;
+    __syncthreads();  // the previous item is done with the LDS (and with *s_item)
+    if (threadIdx.x == 0) {
+      const int v = queue + 8 * atomicAdd(&tickets[queue], 1);
+      *s_item = v < n_virtual ? chunked_item(v, n_items) : -2;
+    }
+    __syncthreads();
+    const int q = *s_item;
+    if (q == -2) {  // queue exhausted
+      ++qsel;
+      continue;
+    }
+    if (q < 0) continue;  // a virtual block without an item
+    const int4 item = g.work[q];
+    const int tile = item.w >> kTileShift;
+    if (GATED) {
+      gemm_bf16_item<true, true>(g, smem, item);
+      __syncthreads();  // every thread's h stores happen before thread 0's release ...
+      if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // ... which makes them visible device-wide ...
+        atomicAdd(&tile_ready[tile], 1);                     // ... before the item is counted
+      }
+    } else {
+      if (threadIdx.x == 0) {
+        int polls = 0;
+        while (__hip_atomic_load(&tile_ready[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nt1) {
+          __builtin_amdgcn_s_sleep(32);
+          if (++polls > kMaxPolls) {
+            *error = 1;
+            break;
+          }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // order the loads of h after the counter
+      }
+      __syncthreads();
+      gemm_bf16_item<false, true>(g, smem, item);
+    }
+  }
+}
+
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(const PipelineArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  __shared__ int s_item;
+  gemm_bf16_drain<true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
+  gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
+}
+
+}  // namespace moe355
