@@ -311,6 +311,15 @@ def main():
     if cfg.dtype == wl.BF16:
         out["hand_over_comparison"]["one_launch_forward_ms"] = timed(lambda: lay.forward_one_launch(x), 5)
     del lay_u
+    # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lay.step(lg, x)
+    t_graph = timed(graph.replay, 20)
+    out["graph_replay"] = {"ms_per_step": t_graph, "tokens_per_s": cfg.T / (t_graph * 1e-3),
+                           "note": "route + tables + fused forward replayed from one captured HIP graph; `value` is "
+                                   "measured on eager launches because the per-kernel events live there"}
+    del graph
     # The same layer at 8 x the tokens (for the DeepSeek-shaped workload: what one GPU of an 8-way expert-parallel
     # group sees when every GPU contributes T tokens): enough rows per expert for the GEMMs to be compute-bound.
     if cfg.dtype == wl.BF16 and not swept and not args.no_8x_point and cfg.T * 8 * cfg.d * 2 <= 1 << 30:

@@ -260,6 +260,41 @@ def test_one_launch_forward_rejects_fp32_layers_and_launch_count_rule():
     assert B.moe_forward_gemm_launches(L.MoELayer(wl.CONFIGS["qwen3"].scaled(T=8192)).shape) == 2
 
 
+# ---------------------------------------------------------------- the whole step inside a HIP graph
+@pytest.mark.parametrize("name", ["deepseek_like", "gpt_oss_like"])
+def test_step_replays_from_a_hip_graph(oracle, name):
+    """route + tables + forward captured once and replayed: every launch takes its sizes from device memory, so a
+    replay follows whatever logits and tokens the input buffers hold at that moment.  Replays alternate with eager
+    work and are checked against eager results and the oracle."""
+    import torch
+    cfg = SMALL[name]
+    say(f"graph replay {name}")
+    w, lay, x, lg, idx, tw, y, ref = run_forward(cfg, oracle)   # eager, also warms up one-off attribute calls
+    y_first = lay.y.clone()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lay.step(lg, x)
+    # second input set: other tokens and another routing, written into the same buffers before a replay
+    w2 = wl.make_workload(cfg.scaled(seed=cfg.seed + 100))
+    x_b, lg_b = L.to_device(w2.x), L.to_device(w2.logits)
+    x_a, lg_a = x.clone(), lg.clone()
+    idx2, tw2 = oracle.route_topk(w2.logits, cfg.k)
+    ref2 = oracle.forward(w2.x, idx2, tw2, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, cfg.local_rank_begin,
+                          cfg.local_rank_end)
+    for rep in range(3):
+        for (xi, lgi, want, first) in ((x_b, lg_b, ref2, None), (x_a, lg_a, ref, y_first)):
+            x.copy_(xi)
+            lg.copy_(lgi)
+            lay.y.fill_(float("nan"))
+            lay.forward_ws.fill_(0xFF)
+            graph.replay()
+            torch.cuda.synchronize()
+            G.check_y(lay.y_host(), want, cfg.dtype)
+            if first is not None:
+                assert torch.equal(lay.y, first), "replay differs from the eager run on the same inputs"
+            assert ws_error_flag(lay) == 0
+
+
 @pytest.mark.parametrize("name", ["deepseek_like", "tiny_f32"])
 def test_unfused_path_matches_oracle(oracle, name):
     import torch
