@@ -127,7 +127,8 @@ MOE355_API int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
  * kernel (Sec. IV-A, IV-B); otherwise the two GEMMs are two launches.  The result is the same either way.
  * Int 24 of the workspace is 0 after the call unless a wait inside the resident kernel gave up (corrupt tables).
  * `tables` must come from moe_build_dispatch on the same shape and topk_idx.
- * workspace >= moe_forward_workspace_bytes(shape), 256-byte aligned; its contents are scratch.
+ * workspace >= moe_forward_workspace_bytes(shape), 256-byte aligned; its contents are scratch.  x, y and the
+ * packed weights must be 16-byte aligned (MOE_ERR_INVALID_ARG otherwise).
  */
 MOE355_API int moe_fused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
                                  const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,

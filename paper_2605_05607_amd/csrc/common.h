@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "moe355.h"
 
 namespace moe355 {
@@ -44,6 +46,18 @@ int check_shape(const moe_shape *s, Derived *out);
 // status after each launch.
 inline void begin_launches() { (void)hipGetLastError(); }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+// Raises a kernel's dynamic-LDS limit, once per device (the attribute belongs to the function on one device).
+// `done` is the call site's bit mask of devices already served.
+inline bool allow_dynamic_lds(const void *kernel, int bytes, std::atomic<uint64_t> &done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+  const uint64_t bit = uint64_t(1) << dev;
+  if (done.load(std::memory_order_acquire) & bit) return true;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+  done.fetch_or(bit, std::memory_order_release);
+  return true;
+}
 
 // ---- layout of the forward workspace (offsets in bytes, 256-byte aligned) ----
 struct FwdLayout {

@@ -288,11 +288,11 @@ extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_id
   while ((1 << ebits) < E) ++ebits;
   while ((1 << rbits) < R) ++rbits;
   // The placement kernel keeps (2 + walking waves) arrays of E + R counters in LDS; with the largest E and R even
-  // one walking wave needs more than the default 64 KiB of dynamic LDS, so the limit is raised once.
+  // one walking wave needs more than the default 64 KiB of dynamic LDS, so the limit is raised (once per device).
   constexpr size_t kPlaceLds = 144 * 1024;
-  static const bool lds_ok = hipFuncSetAttribute(reinterpret_cast<const void *>(&dispatch_place_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPlaceLds) == hipSuccess;
-  if (!lds_ok) return MOE_ERR_HIP;
+  static std::atomic<uint64_t> done{0};
+  if (!allow_dynamic_lds(reinterpret_cast<const void *>(&dispatch_place_kernel), (int)kPlaceLds, done))
+    return MOE_ERR_HIP;
   const size_t fit = (kPlaceLds - 1024) / sm_wave;  // arrays that fit; at least 3 for E + R <= 8192
   const int nwalk = (int)std::max<size_t>(1, std::min<size_t>(kTableThreads / kWave, fit > 2 ? fit - 2 : 1));
   // with T == 0 a single block still writes the all-zero counts and offsets

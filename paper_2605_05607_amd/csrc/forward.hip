@@ -69,23 +69,17 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
   const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dv.max_mtiles * nt + 255) / 256 * 256)); };
   if (s->dtype == MOE_BF16) {
     // the two LDS stages (128 KiB) exceed the default dynamic limit; raising it is a per-function attribute
-    static const bool lds_ok = [] {
-      const hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<true>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-      const hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_kernel<false>),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes);
-      return e1 == hipSuccess && e2 == hipSuccess;
-    }();
-    if (!lds_ok) return MOE_ERR_HIP;
+    static std::atomic<uint64_t> done1{0}, done2{0}, done_pipe{0};
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<true>), 2 * kStageBytes, done1) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<false>), 2 * kStageBytes, done2) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_pipeline_kernel), 2 * kStageBytes, done_pipe))
+      return MOE_ERR_HIP;
     g1.n_ntiles = ceil_div(s->f, kBN / 2); g1.n_ktiles = ceil_div(s->d, kBK);
     g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kBK);
     if (pipelined) {
-      static const bool pipe_ok =
-          hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_bf16_pipeline_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kStageBytes) == hipSuccess;
       // one resident workgroup per CU (each takes most of a CU's LDS)
       int dev = 0, n_cu = 0;
-      if (!pipe_ok || hipGetDevice(&dev) != hipSuccess ||
+      if (hipGetDevice(&dev) != hipSuccess ||
           hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
         return MOE_ERR_HIP;
       PipelineArgs pa;
@@ -181,6 +175,10 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   const size_t need = fused ? moe_forward_workspace_bytes(shape) : moe_unfused_workspace_bytes(shape);
   if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MOE_ERR_INVALID_ARG;
+  // rows are moved 16 bytes at a time
+  if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(y) | reinterpret_cast<uintptr_t>(packed_gate_up) |
+       reinterpret_cast<uintptr_t>(packed_down)) % 16 != 0)
+    return MOE_ERR_INVALID_ARG;
   if ((int64_t)dv.max_mtiles * std::max(dv.nt1, dv.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
   // gemm_launches: 0 = by shape, 1 = resident kernel with the tile-level hand-over (bf16 only), 2 = two launches
   if (gemm_launches == 1 && shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;

@@ -379,6 +379,9 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
     const int tile = item.w >> kTileShift;
     if (GATED) {
       gemm_bf16_item<true, true>(g, smem, item);
+      // every wave first waits until its own h stores have been acknowledged (vmcnt(0); gfx9 encoding with the
+      // other counters left at their maxima), so that the one write-back below cannot overtake any of them
+      __builtin_amdgcn_s_waitcnt(0x0F70);
       __syncthreads();  // every thread's h stores happen before thread 0's release ...
       if (threadIdx.x == 0) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // ... which makes them visible device-wide ...

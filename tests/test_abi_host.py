@@ -59,6 +59,18 @@ def test_unsupported_dtype_and_extent():
         == B.MOE_ERR_UNSUPPORTED
 
 
+def test_forward_rejects_misaligned_rows():
+    lib = B.lib()
+    s = good_shape()
+    tb = B.moe_dispatch(*([4096] * 9))
+    need = B.moe_forward_workspace_bytes(s)
+    ok = [4096, 4096, 4096, C.byref(tb), 4096, 4096, 4096]     # x, topk_idx, topk_w, tables, gate_up, down, y
+    for pos in (0, 4, 5, 6):
+        args = list(ok)
+        args[pos] = 4096 + 8
+        assert lib.moe_fused_forward(C.byref(s), *args, 4096, need, None) == B.MOE_ERR_INVALID_ARG
+
+
 def test_gemm_launch_rule_follows_rows_per_expert():
     lib = B.lib()
     assert lib.moe_forward_gemm_launches(C.byref(good_shape(T=4096, E=256, k=8, R=8))) == 1   # 128 rows per expert
