@@ -385,6 +385,10 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
       __syncthreads();  // every thread's h stores happen before thread 0's release ...
       if (threadIdx.x == 0) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // ... which makes them visible device-wide ...
+        // The write-back the fence issues has to be complete before the counter moves.  The compiler does not put
+        // a wait between the two here (it has just waited for the stores in front of the barrier and does not
+        // count the write-back as outstanding), so the wait is spelled out: vmcnt(0).
+        __builtin_amdgcn_s_waitcnt(0x0F70);
         atomicAdd(&tile_ready[tile], 1);                     // ... before the item is counted
       }
     } else {
@@ -398,6 +402,7 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
           }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // order the loads of h after the counter
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // the invalidate is complete before the barrier lets the others load
       }
       __syncthreads();
       gemm_bf16_item<false, true>(g, smem, item);

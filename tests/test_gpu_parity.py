@@ -225,6 +225,15 @@ def test_one_and_two_launch_forward_match_oracle_and_each_other(oracle, name):
             # same tiles, same arithmetic per tile: bit-identical whichever way the GEMMs are launched
             assert torch.equal(lay.y, y_auto)
             assert ws_error_flag(lay) == 0, "a wait inside the resident kernel gave up"
+    # The hand-over inside the resident kernel, many times over a workspace whose previous contents (h included)
+    # are trashed before every call: a GEMM-2 tile that reads h before its producers' rows are visible would see
+    # the trash (a repeat over an untouched workspace would see the previous call's identical h and hide it).
+    for rep in range(40):
+        lay.y.fill_(float("nan"))
+        lay.forward_ws.fill_(0xFF if rep % 2 else 0x3C)
+        lay.forward_one_launch(x)
+        torch.cuda.synchronize()
+        assert torch.equal(lay.y, y_auto), f"hand-over call {rep} differs"
 
 
 @pytest.mark.parametrize("name", ["deepseek_v3", "qwen3"])
