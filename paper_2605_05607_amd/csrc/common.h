@@ -78,8 +78,8 @@ FwdLayout forward_layout(const moe_shape *s, const Derived &dv);
 
 // ---- packed weight geometry ----
 // bf16: gate/up as [E_loc][ceil(f/128)][ceil(d/64)] tiles of 256 x 64 elements (128 gate + 128 up columns
-// of the same 128 h columns), down as [E_loc][ceil(d/256)][ceil(f/64)] tiles of 256 x 64; every tile is the
-// byte image of the LDS stage the GEMM kernel reads (16-byte chunks XOR-swizzled by row), zero-padded.
+// of the same 128 h columns), down as [E_loc][ceil(d/256)][ceil(f/64)] tiles of 256 x 64; inside a tile the
+// values are stored in matrix-core operand order (see pack_kernels.h), zero-padded.
 // fp32: plain copies (gate then up, then down).
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 

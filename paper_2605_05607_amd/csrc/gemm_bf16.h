@@ -115,7 +115,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // ---- LDS -> MFMA operand addressing: lane l reads row l & 31 of a 32-row block, k half l >> 5 ----
   const int l31 = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
   const int a_rd = (wm * 128 + l31) * 128;                  // + mi * 4096
-  const int b_rd = kAStageBytes + (wn * 64 + l31) * 128;    // + j * 4096
+  const int b_rd = kAStageBytes + wn * 8192 + lane * 16;    // + j * 4096 + kk * 1024: operands are stored per lane
 
   constexpr int NF = NB > 0 ? NB : 1;
   bf16x8 fa0[NF], fb0[2], fa1[NF], fb1[2];  // operand fragments of two consecutive k-substeps
@@ -125,8 +125,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) FA[mi] =                                         \
         *reinterpret_cast<const bf16x8 *>((STAGE) + a_rd + mi * 4096 + slot_);                         \
     if (NB > 0) {                                                                                      \
-      FB[0] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + slot_);                               \
-      FB[1] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + 4096 + slot_);                        \
+      FB[0] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + (KK) * 1024);                         \
+      FB[1] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + 4096 + (KK) * 1024);                  \
     }                                                                                                  \
   } while (0)
 #define MOE355_MFMAS(FA, FB)                                                                           \

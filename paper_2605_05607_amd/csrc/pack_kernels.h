@@ -5,14 +5,15 @@
 namespace moe355 {
 
 // ------------------------------------------------------------------------------------------------
-// Weight packing (one-off).  Output tile (le, nt, kt) covers kBN output columns x kBK reduction indices and is
-// the byte image of the LDS stage the GEMM kernel reads, so the kernel copies it linearly (16 bytes per lane,
-// fully coalesced):  row n_l of the tile is the 128-byte run of its 64 k values, cut into eight 16-byte
-// chunks; chunk c of row n_l sits at slot c ^ ((n_l >> 1) & 7).  The LDS of gfx950 has 64 four-byte banks, so
-// a 128-bit operand read is served 16 lanes at a time; with this swizzle the 16 rows such a group touches
-// fall on 16 different bank groups (measured: zero bank-conflict cycles).  Zero-padded outside the matrix.
-// GATED tiles pair gate and up columns inside one wave column: tile rows [wn*64, wn*64+32) are the gate
-// columns nt*128 + wn*32 + 0..31 and rows [wn*64+32, wn*64+64) the up columns of the same h columns.
+// Weight packing (one-off).  Output tile (le, nt, kt) covers kBN output columns x kBK reduction indices (32 KiB)
+// and is stored in the order the matrix-core instruction consumes it: for every block cb of 32 columns and every
+// 16-wide reduction step kk, the 64 lanes' B operands of v_mfma_f32_32x32x16_bf16 lie next to each other, lane l
+// holding the 8 values B[column cb*32 + l%32][k = kk*16 + (l/32)*8 .. +8] at byte ((cb*4 + kk)*64 + l)*16.
+// The GEMM kernels copy a tile linearly into the LDS (16 bytes per lane, fully coalesced) and a wave reads an
+// operand as one contiguous KiB (no bank conflicts); a wave can equally load an operand straight from global
+// memory with one coalesced 1 KiB access.  Zero-padded outside the matrix.
+// GATED tiles pair gate and up columns inside one wave column: blocks cb = 2 wn and 2 wn + 1 are the gate and the
+// up columns nt*128 + wn*32 + 0..31 of the same h columns.
 // ------------------------------------------------------------------------------------------------
 template <bool GATED>
 __global__ __launch_bounds__(256) void pack_bf16_kernel(const bf16_t *__restrict__ W0, const bf16_t *__restrict__ W1,
@@ -32,7 +33,8 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const bf16_t *__restrict
       const int kk = kt * kBK + c * 8 + q;
       v[q] = (col < N && kk < K) ? W[wbase + (size_t)kk * N + col] : (bf16_t)0.0f;
     }
-    *reinterpret_cast<bf16x8 *>(tile + (size_t)n_l * kBK + ((c ^ ((n_l >> 1) & 7)) << 3)) = v;
+    // chunk c = 2 kk + k-half; column block cb = n_l >> 5
+    *reinterpret_cast<bf16x8 *>(tile + ((((n_l >> 5) * 4 + (c >> 1)) * 64 + (c & 1) * 32 + (n_l & 31)) << 3)) = v;
   }
 }
 
