@@ -7,7 +7,7 @@ namespace moe355 {
 // ------------------------------------------------------------------------------------------------
 // Grouped bf16 GEMM on the matrix cores.  C[rows of one expert tile, kBN/2 or kBN columns] = A * W_e.
 //   A rows   : row_map == nullptr -> A[m0 + r, :]; else A[row_map[m0 + r], :] (token gather of Dispatch).
-//   B tiles  : packed LDS images streamed linearly.
+//   B tiles  : packed in operand order (pack_kernels.h), streamed linearly into the LDS and read linearly from it.
 //   GATED    : epilogue h = silu(g) * u, written as bf16   (GEMM-1)
 //   !GATED   : epilogue o = acc * row_w[row], written fp32 (GEMM-2, gate weight of Sec. III-C)
 // Tile 256 x 256 x 64, one workgroup of 512 threads per CU.  Every operand byte enters the CU once (global ->
