@@ -327,10 +327,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmAr
 // tile-granular GEMM-1 => GEMM-2 hand-over of the fused kernel (Sec. IV-A, IV-B): a GEMM-2 tile starts as soon
 // as the h rows of its M tile are complete, so the CUs that run out of GEMM-1 work (a launch of a few hundred
 // tiles of ~100 us ends with many CUs idle) continue with GEMM-2 instead of waiting for a kernel boundary.
-// moe_fused_forward uses it for bf16 layers whose experts get less than one full M tile of rows on average (the
-// launches are then dominated by partial tiles and by the tail of the few large experts; measured 5 % faster on the
-// DeepSeek-shaped load); with fuller experts the ticket, fence and poll per item cost 2-6 % more than the idle
-// tail they remove, and the kernel boundary of moe_fused_forward_two_launch is used instead.
+// moe_fused_forward uses it for bf16 layers whose experts get less than one full M tile of rows on average: the
+// launches are then dominated by partial tiles and, under skewed routing, by the tail of the few large experts
+// (measured 5 % faster than two launches on the DeepSeek-shaped skewed load, 1 % slower on the same shape with
+// uniform routing).  With fuller experts a whole step is 1-3 % slower than with two launches (7-9 % on layers of
+// 0.1-0.2 ms), and the kernel boundary of moe_fused_forward_two_launch is used instead.
 //
 // Work distribution: both lists are cut into 8 queues exactly as a plain launch would spread them over the XCDs
 // (queue x = virtual blocks x, x + 8, ...; see chunked_item); a workgroup draws tickets from its home queue
@@ -360,21 +361,43 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
   const int home = blockIdx.x & 7;
   const int n_items = *g.n_items;
   const int n_virtual = (n_items + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk);
-  int qsel = 0;
-  while (qsel < 8) {
-    const int queue = (home + qsel) & 7;
-    __syncthreads();  // the previous item is done with the LDS (and with *s_item)
-    if (threadIdx.x == 0) {
+  int qsel = 0;  // queues tried so far, in the order home, home + 1, ... (only thread 0's copy is used)
+  // Next list position for this workgroup, or -1 when every queue is empty (thread 0 only).
+  auto draw = [&]() {
+    int q = -1;
+    while (qsel < 8) {
+      const int queue = (home + qsel) & 7;
       const int v = queue + 8 * atomicAdd(&tickets[queue], 1);
-      *s_item = v < n_virtual ? chunked_item(v, n_items) : -2;
+      if (v < n_virtual) {
+        if ((q = chunked_item(v, n_items)) >= 0) break;
+        continue;  // a virtual block without an item
+      }
+      // this queue is empty: read all counters at once and go on with the next queue that still has positions
+      // (an empty queue stays empty, so every queue is seen empty before the loop ends)
+      unsigned open_queues = 0;  // bit i: queue i still has positions
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int t = __hip_atomic_load(&tickets[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        open_queues |= (unsigned)(i + 8 * t < n_virtual) << i;
+      }
+      int next = 8;
+#pragma unroll
+      for (int i = 7; i >= 1; --i) {
+        const int s2 = qsel + i;  // candidate position in the visiting order
+        if (s2 < 8 && ((open_queues >> ((home + s2) & 7)) & 1u)) next = s2;
+      }
+      qsel = next;
     }
+    return q;
+  };
+  // (Drawing the next ticket one item ahead, to hide the latency of the atomic, was measured slower: a workgroup
+  // that holds a long item while it finishes another one keeps that item from an idle workgroup.)
+  for (;;) {
+    __syncthreads();  // the previous item is done with the LDS (and with *s_item)
+    if (threadIdx.x == 0) *s_item = draw();
     __syncthreads();
     const int q = *s_item;
-    if (q == -2) {  // queue exhausted
-      ++qsel;
-      continue;
-    }
-    if (q < 0) continue;  // a virtual block without an item
+    if (q < 0) break;  // nothing left in any queue
     const int4 item = g.work[q];
     const int tile = item.w >> kTileShift;
     if (GATED) {

@@ -255,7 +255,7 @@ def test_one_and_two_launch_forward_full_size(oracle, name):
         assert torch.equal(lay.y, y_auto) and ws_error_flag(lay) == 0
 
 
-def test_one_launch_forward_rejects_fp32_layers_and_launch_count_rule():
+def test_one_launch_forward_rejects_fp32_layers():
     cfg = SMALL["f32_ragged"]
     w = wl.make_workload(cfg)
     lay = L.MoELayer(cfg)
@@ -265,8 +265,6 @@ def test_one_launch_forward_rejects_fp32_layers_and_launch_count_rule():
         lay.forward_one_launch(L.to_device(w.x))
     assert err.value.status == B.MOE_ERR_UNSUPPORTED
     assert B.moe_forward_gemm_launches(lay.shape) == 2
-    assert B.moe_forward_gemm_launches(L.MoELayer(wl.CONFIGS["deepseek_v3"].scaled(T=8)).shape) == 1
-    assert B.moe_forward_gemm_launches(L.MoELayer(wl.CONFIGS["qwen3"].scaled(T=8192)).shape) == 2
 
 
 # ---------------------------------------------------------------- the whole step inside a HIP graph
