@@ -202,6 +202,37 @@ def test_dispatch_gather_and_combine_reduce(oracle):
         assert np.all(np.abs(y - ref) <= tol * np.maximum(1.0, np.abs(ref)))
 
 
+@pytest.mark.parametrize("name", ["deepseek_v3", "gpt_oss"])
+def test_dispatch_gather_and_combine_reduce_full_size(oracle, name):
+    """Phase-split Dispatch and Combine at the sizes bench.py times, against the oracle's own tables."""
+    import torch
+    cfg = wl.CONFIGS[name]
+    say(f"phase split full size {name}")
+    w = wl.make_workload(cfg, weights=False)
+    lay, got = G.run_tables(cfg, w.logits)
+    idx, _ = oracle.route_topk(w.logits, cfg.k)
+    counts, offsets, perm, inv = oracle.build_tables(idx, cfg.E)
+    base = int(offsets[cfg.first_local_expert])
+    P = int(offsets[cfg.first_local_expert + cfg.E_loc]) - base
+    tok_of_row = torch.from_numpy((perm[base:base + P] // cfg.k).astype(np.int64)).cuda()
+    x = L.to_device(w.x)
+    P_cap = cfg.T * min(cfg.k, cfg.E_loc)
+    xs = torch.zeros((P_cap, cfg.d), dtype=lay.elt_dtype, device="cuda")
+    B.moe_dispatch_gather(lay.shape, x, lay.tables, xs)
+    torch.cuda.synchronize()
+    assert torch.equal(xs[:P], x[tok_of_row])          # every layout row holds its token's row, bit for bit
+    assert xs[P:].abs().sum().item() == 0              # nothing beyond the local segment is touched
+    del xs
+    # Combine: integer-valued rows make the fp32 sums exact, so the result is unique whatever the order
+    g = torch.Generator(device="cuda").manual_seed(7)
+    rows = torch.randint(-8, 9, (P, cfg.d), generator=g, device="cuda").to(torch.float32)
+    lay.y.fill_(float("nan"))
+    B.moe_combine_reduce(lay.shape, rows, lay.topk_idx, lay.tables, lay.y)
+    torch.cuda.synchronize()
+    want = torch.zeros((cfg.T, cfg.d), dtype=torch.float32, device="cuda").index_add_(0, tok_of_row, rows)
+    assert torch.equal(lay.y.to(torch.float32), want)  # |sums| <= 8 k = 64: exact in bf16 as well
+
+
 # ---------------------------------------------------------------- the two forms of the GEMM-1 => GEMM-2 hand-over
 def ws_error_flag(lay):
     import torch
@@ -300,6 +331,31 @@ def test_step_replays_from_a_hip_graph(oracle, name):
             if first is not None:
                 assert torch.equal(lay.y, first), "replay differs from the eager run on the same inputs"
             assert ws_error_flag(lay) == 0
+
+
+def test_unfused_path_full_size_agrees_with_fused():
+    """The comparison path of bench.py at full size: same GEMM tiles, but an atomic fp32 scatter-add instead of the
+    ordered reduction, so it agrees with the fused result to fp32 reordering plus one bf16 rounding, not bit for bit."""
+    import torch
+    cfg = wl.CONFIGS["deepseek_v3"]
+    say("unfused full size deepseek_v3")
+    w = wl.make_workload(cfg)
+    lay = L.MoELayer(cfg, unfused=True)
+    lay.load_weights(w.W_gate, w.W_up, w.W_down)
+    x, lg = L.to_device(w.x), L.to_device(w.logits)
+    lay.route(lg)
+    lay.build_dispatch()
+    lay.forward(x)
+    torch.cuda.synchronize()
+    y_fused = lay.y.to(torch.float32).clone()
+    lay.y.fill_(float("nan"))
+    lay.forward_unfused(x)
+    torch.cuda.synchronize()
+    y_unf = lay.y.to(torch.float32)
+    assert torch.isfinite(y_unf).all()
+    scale = y_fused.abs().max().item()
+    assert (y_unf - y_fused).abs().max().item() <= 2 ** -7 * scale   # at most one bf16 ulp of the largest value
+    assert (y_unf != y_fused).float().mean().item() < 0.05            # and rarely different at all
 
 
 @pytest.mark.parametrize("name", ["deepseek_like", "tiny_f32"])
