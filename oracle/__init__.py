@@ -58,6 +58,29 @@ def max_threads() -> int:
     return int(_lib().moe_oracle_max_threads())
 
 
+def router_logits(x: np.ndarray, W_r: np.ndarray, acc: str = "f64") -> np.ndarray:
+    """Gate-network logits [T, E] (float64): x [T, d] times the rows of W_r [E, d].
+
+    float32 arrays are taken as such; uint16 arrays as bf16 bit patterns (both operands alike)."""
+    if x.dtype == np.uint16:
+        elt = ELT_BF16
+    elif x.dtype == np.float32:
+        elt = ELT_F32
+    else:
+        raise TypeError("x must be float32 or uint16 (bf16 bits)")
+    if W_r.dtype != x.dtype:
+        raise TypeError("W_r must have the element type of x")
+    x, W_r = np.ascontiguousarray(x), np.ascontiguousarray(W_r)
+    T, d = x.shape
+    E, d2 = W_r.shape
+    assert d2 == d
+    out = np.empty((T, E), dtype=np.float64)
+    lib = _lib(acc)
+    lib.moe_oracle_router_logits.argtypes = [C.c_int] * 4 + [C.c_void_p] * 3
+    _check(lib.moe_oracle_router_logits(T, d, E, elt, _p(x), _p(W_r), _p(out)), "router_logits")
+    return out
+
+
 def route_topk(logits: np.ndarray, k: int):
     logits = np.ascontiguousarray(logits, dtype=np.float32)
     T, E = logits.shape

@@ -23,7 +23,7 @@
  * exp() is evaluated in double.  Nothing is blocked, fused or reordered beyond that.
  *
  * Pins (tests/, -m "not gpu"): brute-force NumPy re-derivations on tiny inputs, a hand-worked 4-token
- * example, sum-to-one and permutation invariants, the identical-experts == dense-FFN identity, the
+ * example, the gate network against a library matrix product and unit-vector / hand-worked cases, sum-to-one and permutation invariants, the identical-experts == dense-FFN identity, the
  * closed-form expected dedup count, and the float-vs-double accumulation twin.
  */
 #include <math.h>
@@ -63,6 +63,26 @@ int moe_oracle_max_threads(void) {
 #else
   return 1;
 #endif
+}
+
+/*
+ * Gate network (Sec. II-A: the experts of a token are "selected by the gate network").  The paper does not
+ * spell the network out; the reading used is the usual bias-free linear map: logit[t][e] = sum_c x[t][c] *
+ * W_r[e][c], one row of W_r per expert, summed in ascending c.  logits is [T, E] in double.
+ */
+int moe_oracle_router_logits(int T, int d, int E, int elt, const void *x, const void *W_r, double *logits) {
+  if (T < 0 || d < 1 || E < 1 || !x || !W_r || !logits) return ORACLE_BAD_ARG;
+  if (elt != ELT_F32 && elt != ELT_BF16) return ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(static)
+  for (int t = 0; t < T; ++t) {
+    for (int e = 0; e < E; ++e) {
+      acc_t sum = 0;
+      for (int c = 0; c < d; ++c)
+        sum += (acc_t)load_elt(x, (size_t)t * d + c, elt) * (acc_t)load_elt(W_r, (size_t)e * d + c, elt);
+      logits[(size_t)t * E + e] = (double)sum;
+    }
+  }
+  return ORACLE_OK;
 }
 
 /*

@@ -58,6 +58,47 @@ def test_hand_example_forward_identical_experts(oracle):
     assert np.all(y[2] == 0.0)
 
 
+# ---------------------------------------------------------------- gate network
+def test_router_logits_hand_example(oracle):
+    # two tokens, three experts, worked by hand; a transposed operand or a swapped index changes every entry
+    x = np.array([[1, 2, 3, 4], [0, -1, 0.5, 2]], dtype=np.float32)
+    W = np.array([[1, 0, 0, 0], [0.5, 0.5, 0.5, 0.5], [-1, 2, -3, 4]], dtype=np.float32)
+    want = [[1.0, 5.0, 10.0], [0.0, 0.75, 4.5]]
+    assert oracle.router_logits(x, W).tolist() == want
+
+
+@pytest.mark.parametrize("T,d,E", [(1, 1, 1), (7, 33, 5), (40, 257, 64)])
+def test_router_logits_vs_library_matrix_product(oracle, T, d, E):
+    rng = np.random.default_rng(T * 100 + d)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    W = rng.standard_normal((E, d)).astype(np.float32)
+    ref = x.astype(np.float64) @ W.astype(np.float64).T
+    got = oracle.router_logits(x, W)
+    assert got.shape == (T, E)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12 * d)
+    # unit-vector rows pick single columns of x: catches a row/column mix-up of W_r exactly
+    sel = rng.integers(0, d, size=E)
+    U = np.zeros((E, d), dtype=np.float32)
+    U[np.arange(E), sel] = 1.0
+    assert np.array_equal(oracle.router_logits(x, U), x[:, sel].astype(np.float64))
+
+
+def test_router_logits_bf16_and_float_twin(oracle):
+    rng = np.random.default_rng(3)
+    x32 = rng.standard_normal((9, 96)).astype(np.float32)
+    W32 = rng.standard_normal((6, 96)).astype(np.float32)
+    xb, Wb = wl.f32_to_bf16_bits(x32), wl.f32_to_bf16_bits(W32)
+    # bf16 bit patterns are widened exactly: same result as handing over the widened fp32 values
+    assert np.array_equal(oracle.router_logits(xb, Wb),
+                          oracle.router_logits(wl.bf16_bits_to_f32(xb), wl.bf16_bits_to_f32(Wb)))
+    # the float-accumulating build stays within the textbook bound d * 2^-24 * sum |x w|
+    a64, a32 = oracle.router_logits(x32, W32), oracle.router_logits(x32, W32, acc="f32")
+    bound = 96 * 2.0 ** -24 * (np.abs(x32).astype(np.float64) @ np.abs(W32).astype(np.float64).T)
+    assert np.all(np.abs(a64 - a32) <= bound) and np.any(a64 != a32)
+    with pytest.raises(TypeError):
+        oracle.router_logits(x32, Wb)
+
+
 # ---------------------------------------------------------------- routing
 @pytest.mark.parametrize("T,E,k", [(50, 8, 2), (33, 16, 16), (40, 5, 1), (64, 256, 8), (17, 3, 3)])
 def test_route_vs_full_sort_and_full_softmax(oracle, T, E, k):
