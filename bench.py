@@ -311,6 +311,17 @@ def main():
     if cfg.dtype == wl.BF16:
         out["hand_over_comparison"]["one_launch_forward_ms"] = timed(lambda: lay.forward_one_launch(x), 5)
     del lay_u
+    # The gate network ahead of the routing (not part of the timed step: the logits are an input of the layer):
+    # a skinny product bound by reading x once.
+    W_r = (torch.randn((cfg.E, cfg.d), dtype=torch.float32, device="cuda") * cfg.d ** -0.5).to(lay.elt_dtype)
+    lg2 = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device="cuda")
+    ws_r = torch.empty((B.moe_router_workspace_bytes(lay.shape),), dtype=torch.uint8, device="cuda")
+    t_gate = timed(lambda: B.moe_router_logits(lay.shape, x, W_r, lg2, ws_r), 20)
+    gate_bytes = (cfg.T * cfg.d + cfg.E * cfg.d) * b + cfg.T * cfg.E * 4
+    out["router_logits"] = {"entry": "moe_router_logits", "ms": t_gate, "bytes": gate_bytes,
+                            "hbm_gbs": gate_bytes / (t_gate * 1e-3) / 1e9,
+                            "hbm_frac_of_peak": gate_bytes / (t_gate * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del W_r, lg2, ws_r
     # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

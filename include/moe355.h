@@ -90,6 +90,17 @@ MOE355_API size_t moe_forward_workspace_bytes(const moe_shape *shape);
 MOE355_API size_t moe_packed_weight_bytes(const moe_shape *shape, int which);
 
 /*
+ * Gate network ahead of the routing (Sec. II-A: the experts of a token are "selected by the gate network"; the
+ * reading used is a bias-free linear map).  logits [T,E] fp32 = x [T,d] times the rows of W_r [E,d] (one row per
+ * expert, element type of the layer), accumulated in fp32 in a fixed order: the same inputs give the same bits,
+ * and so the same routing.  x and W_r must be 16-byte aligned; workspace >= moe_router_workspace_bytes(shape)
+ * (partial sums of the parts the reduction range is cut into).  The result feeds moe_route_topk.
+ */
+MOE355_API size_t moe_router_workspace_bytes(const moe_shape *shape);
+MOE355_API int moe_router_logits(const moe_shape *shape, const void *x, const void *W_r, float *logits,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Routing (Sec. II-A: each token activates the top-k experts chosen by the gate).
  * logits [T,E] fp32.  For each token the k largest logits are selected (ties: lower expert index first)
  * and reported in descending order in topk_idx [T,k]; topk_w [T,k] is the softmax over the logits

@@ -60,6 +60,10 @@ def lib() -> C.CDLL:
         L.moe_forward_gemm_launches.argtypes = [sp]
         L.moe_packed_weight_bytes.restype = sz
         L.moe_packed_weight_bytes.argtypes = [sp, i32]
+        L.moe_router_workspace_bytes.restype = sz
+        L.moe_router_workspace_bytes.argtypes = [sp]
+        L.moe_router_logits.restype = i32
+        L.moe_router_logits.argtypes = [sp, vp, vp, vp, vp, sz, vp]
         L.moe_route_topk.restype = i32
         L.moe_route_topk.argtypes = [sp, vp, vp, vp, vp]
         L.moe_build_dispatch.restype = i32
@@ -152,6 +156,16 @@ def moe_unfused_workspace_bytes(shape: moe_shape) -> int:
 
 def moe_packed_weight_bytes(shape: moe_shape, which: int) -> int:
     return int(lib().moe_packed_weight_bytes(C.byref(shape), which))
+
+
+def moe_router_workspace_bytes(shape: moe_shape) -> int:
+    return int(lib().moe_router_workspace_bytes(C.byref(shape)))
+
+
+def moe_router_logits(shape, x, W_r, logits, workspace, workspace_bytes=None, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().moe_router_logits(C.byref(shape), _ptr(x), _ptr(W_r), _ptr(logits), _ptr(workspace), nbytes,
+                                   _stream(stream)), "moe_router_logits")
 
 
 def moe_route_topk(shape, logits, topk_idx, topk_w, stream=None) -> None:

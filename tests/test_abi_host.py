@@ -129,3 +129,22 @@ def test_t_zero_is_a_noop_on_the_host():
     s = good_shape(T=0)
     lib = B.lib()
     assert lib.moe_route_topk(C.byref(s), 4096, 4096, 4096, None) == B.MOE_OK
+
+
+def test_router_logits_arguments():
+    lib = B.lib()
+    s = good_shape()
+    need = B.moe_router_workspace_bytes(s)
+    assert need >= 256 and need % 256 == 0
+    assert B.moe_router_workspace_bytes(good_shape(E=0)) == 0
+    fake = 4096
+    assert lib.moe_router_logits(C.byref(s), None, fake, fake, fake, need, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_router_logits(C.byref(s), fake, fake, None, fake, need, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_router_logits(C.byref(s), fake + 2, fake, fake, fake, need, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_router_logits(C.byref(s), fake, fake, fake, fake, need - 1, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_router_logits(C.byref(s), fake, fake, fake, None, need, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_router_logits(C.byref(good_shape(T=0)), fake, fake, fake, fake, 1 << 20, None) == B.MOE_OK
+    # the partial sums of the parts of the reduction range fit: parts <= 8
+    for cfg in wl.CONFIGS.values():
+        sh = B.shape_of(cfg)
+        assert B.moe_router_workspace_bytes(sh) <= 8 * cfg.T * cfg.E * 4 + 512

@@ -375,3 +375,74 @@ def test_unfused_path_matches_oracle(oracle, name):
     ref = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, cfg.local_rank_begin,
                          cfg.local_rank_end)
     G.check_y(lay.y_host(), ref, cfg.dtype)
+
+
+# ---------------------------------------------------------------- gate network ahead of the routing
+def router_case(T, d, E, k, dtype, seed):
+    rng = np.random.default_rng(seed)
+    x32 = rng.standard_normal((T, d)).astype(np.float32)
+    W32 = (rng.standard_normal((E, d)) * d ** -0.5).astype(np.float32)
+    if dtype == wl.BF16:
+        return wl.f32_to_bf16_bits(x32), wl.f32_to_bf16_bits(W32)
+    return x32, W32
+
+
+def check_router(oracle, T, d, E, k, dtype, seed, rows=None):
+    import torch
+    x, W = router_case(T, d, E, k, dtype, seed)
+    cfg = cfg_of(T=T, d=d, f=8, E=E, k=k, R=1, local_rank_begin=0, local_rank_end=1, dtype=dtype)
+    s = B.shape_of(cfg)
+    xd, Wd = L.to_device(x), L.to_device(W)
+    logits = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.full((B.moe_router_workspace_bytes(s),), 0xFF, dtype=torch.uint8, device="cuda")
+    B.moe_router_logits(s, xd, Wd, logits, ws)
+    again = torch.empty_like(logits)
+    B.moe_router_logits(s, xd, Wd, again, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(logits, again), "the gate network is not reproducible"
+    got = logits.cpu().numpy().astype(np.float64)
+    sel = np.arange(T) if rows is None else rows
+    ref = oracle.router_logits(np.ascontiguousarray(x[sel]), W)
+    xf = (wl.bf16_bits_to_f32(x[sel]) if dtype == wl.BF16 else x[sel]).astype(np.float64)
+    Wf = (wl.bf16_bits_to_f32(W) if dtype == wl.BF16 else W).astype(np.float64)
+    # fp32 accumulation of d exact products (bf16) or d fused multiply-adds (fp32), in any order
+    tol = d * 2.0 ** -23 * (np.abs(xf) @ np.abs(Wf).T) + 1e-30
+    assert np.all(np.abs(got[sel] - ref) <= tol), f"max excess {(np.abs(got[sel] - ref) / tol).max():.3f}"
+    # routing on the GPU's logits: with eps the largest deviation actually seen in a token's row, two logits
+    # further apart than 2 eps keep their order, so the picks must equal the oracle's wherever the oracle's own
+    # margins (among its k + 1 largest logits) exceed 2 eps, and must be a valid top-k within 2 eps everywhere
+    idx = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    wts = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_route_topk(s, logits, idx, wts)
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()[sel]
+    ridx, _ = oracle.route_topk(ref.astype(np.float32), k)
+    order = np.argsort(-ref, axis=1, kind="stable")
+    srt = np.take_along_axis(ref, order, axis=1)
+    tmax = np.abs(got[sel] - ref).max(axis=1)
+    top = srt[:, :min(k + 1, E)]
+    safe = (top[:, :-1] - top[:, 1:]).min(axis=1) > 2 * tmax if top.shape[1] > 1 else np.ones(len(sel), bool)
+    assert np.array_equal(idx[safe], ridx[safe])
+    kth = srt[:, k - 1]
+    picked = np.take_along_axis(ref, idx.astype(np.int64), axis=1)
+    assert np.all(picked >= (kth - 2 * tmax)[:, None])
+    assert all(len(set(r)) == k for r in idx.tolist())
+    return int(safe.sum()), len(sel)
+
+
+@pytest.mark.parametrize("T,d,E,k,dtype", [(1, 8, 1, 1, wl.BF16), (70, 72, 6, 3, wl.BF16), (130, 24, 65, 4, wl.BF16),
+                                           (300, 520, 128, 8, wl.BF16), (90, 136, 300, 4, wl.BF16),
+                                           (2100, 64, 16, 2, wl.BF16), (33, 40, 12, 2, wl.F32)])
+def test_router_logits_small(oracle, T, d, E, k, dtype):
+    say(f"router logits T={T} d={d} E={E} dtype={dtype}")
+    n_safe, n = check_router(oracle, T, d, E, k, dtype, seed=T + d)
+    say(f"  {n_safe} of {n} tokens with margins above the tolerance compared index by index")
+
+
+def test_router_logits_deepseek_shape_sampled_tokens(oracle):
+    cfg = wl.CONFIGS["deepseek_v3"]
+    say("router logits at the DeepSeek shape")
+    rows = np.sort(np.random.default_rng(9).choice(cfg.T, size=192, replace=False))
+    n_safe, n = check_router(oracle, cfg.T, cfg.d, cfg.E, cfg.k, wl.BF16, seed=77, rows=rows)
+    say(f"  {n_safe} of {n} sampled tokens compared index by index")
+    assert n_safe > n // 2
