@@ -154,3 +154,97 @@ def forward(x: np.ndarray, topk_idx: np.ndarray, topk_w: np.ndarray, W_gate: np.
                                   _p(topk_w), _p(W_gate), _p(W_up), _p(W_down), _p(tokens), n_tok, _p(y)),
            "forward")
     return y
+
+
+def fp8_decode(codes: np.ndarray) -> np.ndarray:
+    """Values (float64) of E4M3 codes (uint8); NaN codes give NaN."""
+    lib = _lib()
+    lib.moe_oracle_fp8_decode.restype = C.c_double
+    lib.moe_oracle_fp8_decode.argtypes = [C.c_uint8]
+    flat = np.ascontiguousarray(codes, dtype=np.uint8).ravel()
+    table = np.array([lib.moe_oracle_fp8_decode(c) for c in range(256)], dtype=np.float64)
+    return table[flat].reshape(np.shape(codes))
+
+
+def fp8_encode(values: np.ndarray) -> np.ndarray:
+    """E4M3 codes (uint8) of float32 values: nearest, ties to even, saturating at 448."""
+    lib = _lib()
+    lib.moe_oracle_fp8_encode.restype = C.c_uint8
+    lib.moe_oracle_fp8_encode.argtypes = [C.c_float]
+    flat = np.ascontiguousarray(values, dtype=np.float32).ravel()
+    return np.array([lib.moe_oracle_fp8_encode(float(v)) for v in flat], dtype=np.uint8).reshape(np.shape(values))
+
+
+def fp8_quantize(a: np.ndarray, axis: int):
+    """Quantise a float32 array of 2 or 3 dimensions with one scale per group, a group running along ``axis`` of the
+    last two dimensions (axis=-1: one scale per row, axis=-2: one scale per column; a leading dimension is a batch).
+    Returns (codes uint8 of the same shape, scales float32 with ``axis`` removed)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if a.ndim == 2:
+        a3 = a[None]
+    elif a.ndim == 3:
+        a3 = a
+    else:
+        raise ValueError("2 or 3 dimensions")
+    B, r, c = a3.shape
+    codes = np.empty_like(a3, dtype=np.uint8)
+    lib = _lib()
+    lib.moe_oracle_fp8_quantize.argtypes = [C.c_void_p] + [C.c_int64] * 4 + [C.c_void_p, C.c_void_p]
+    if axis in (-1, a.ndim - 1):
+        scales = np.empty((B, r), dtype=np.float32)
+        _check(lib.moe_oracle_fp8_quantize(_p(a3), B * r, c, c, 1, _p(codes), _p(scales)), "fp8_quantize")
+    elif axis in (-2, a.ndim - 2):
+        scales = np.empty((B, c), dtype=np.float32)
+        for b in range(B):
+            _check(lib.moe_oracle_fp8_quantize(_p(a3[b]), c, r, 1, c, _p(codes[b]), _p(scales[b])), "fp8_quantize")
+    else:
+        raise ValueError("axis must be one of the last two")
+    if a.ndim == 2:
+        return codes[0], scales[0]
+    return codes, scales
+
+
+def _as_f32(a: np.ndarray) -> np.ndarray:
+    if a.dtype == np.uint16:
+        return (a.astype(np.uint32) << 16).view(np.float32)  # bf16 bit patterns widened exactly
+    if a.dtype == np.float32:
+        return a
+    raise TypeError("float32 or uint16 (bf16 bits)")
+
+
+def forward_fp8(x: np.ndarray, topk_idx: np.ndarray, topk_w: np.ndarray, W_gate: np.ndarray, W_up: np.ndarray,
+                W_down: np.ndarray, s_h: np.ndarray, E: int, R: int, local_rank_begin: int, local_rank_end: int,
+                tokens: Optional[np.ndarray] = None, quantized=None) -> np.ndarray:
+    """y rows (float64) of the layer with FP8 expert GEMMs (see moe_oracle.c for the scheme).  x and the weights are
+    float32 or bf16 bit patterns; s_h [E_loc] float32.  ``quantized`` may carry the result of an earlier
+    :func:`fp8_quantize_layer` call for the same x and weights."""
+    q = quantized if quantized is not None else fp8_quantize_layer(x, W_gate, W_up, W_down)
+    xq, sx, gq, sg, uq, su, dq, sd = q
+    T, d = xq.shape
+    El, _, f = gq.shape
+    topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    topk_w = np.ascontiguousarray(topk_w, dtype=np.float32)
+    s_h = np.ascontiguousarray(s_h, dtype=np.float32)
+    k = topk_idx.shape[1]
+    assert s_h.shape == (El,) and El == (local_rank_end - local_rank_begin) * (E // R)
+    if tokens is not None:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        n_tok = int(tokens.shape[0])
+    else:
+        n_tok = T
+    y = np.empty((n_tok, d), dtype=np.float64)
+    lib = _lib()
+    lib.moe_oracle_forward_fp8.argtypes = [C.c_int] * 8 + [C.c_void_p] * 12 + [C.c_int, C.c_void_p]
+    _check(lib.moe_oracle_forward_fp8(T, d, f, E, k, R, local_rank_begin, local_rank_end, _p(xq), _p(sx),
+                                      _p(topk_idx), _p(topk_w), _p(gq), _p(sg), _p(uq), _p(su), _p(dq), _p(sd),
+                                      _p(s_h), _p(tokens), n_tok, _p(y)), "forward_fp8")
+    return y
+
+
+def fp8_quantize_layer(x, W_gate, W_up, W_down):
+    """Codes and scales of the operands: x per token, every weight matrix per expert and output column."""
+    xq, sx = fp8_quantize(_as_f32(np.ascontiguousarray(x)), axis=-1)
+    gq, sg = fp8_quantize(_as_f32(np.ascontiguousarray(W_gate)), axis=-2)
+    uq, su = fp8_quantize(_as_f32(np.ascontiguousarray(W_up)), axis=-2)
+    dq, sd = fp8_quantize(_as_f32(np.ascontiguousarray(W_down)), axis=-2)
+    return xq, sx, gq, sg, uq, su, dq, sd

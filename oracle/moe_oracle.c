@@ -24,7 +24,9 @@
  *
  * Pins (tests/, -m "not gpu"): brute-force NumPy re-derivations on tiny inputs, a hand-worked 4-token
  * example, the gate network against a library matrix product and unit-vector / hand-worked cases, sum-to-one and permutation invariants, the identical-experts == dense-FFN identity, the
- * closed-form expected dedup count, and the float-vs-double accumulation twin.
+ * closed-form expected dedup count, and the float-vs-double accumulation twin; for the FP8 layer the format's
+ * definition and a library's conversions on all codes, midpoints and random values, and the layer restated with
+ * that library's conversions and float64 library products.
  */
 #include <math.h>
 #include <stdint.h>
@@ -240,6 +242,146 @@ int moe_oracle_forward(int T, int d, int f, int E, int k, int R, int lrb, int lr
             }
             const acc_t w = (acc_t)topk_w[(size_t)t * k + j];
             for (int m = 0; m < d; ++m) acc[m] += w * o[m];
+          }
+        }
+        for (int m = 0; m < d; ++m) y_out[(size_t)i * d + m] = (double)acc[m];
+      }
+    }
+    free(g); free(u); free(o); free(acc);
+  }
+  return status;
+}
+
+/* ------------------------------------------------------------------------------------------------------------
+ * FP8 expert GEMMs.  The paper's DeepSeek-V3 runs use FP8 GEMM kernels (Sec. V-A) and says nothing more about
+ * them; the reading used here:
+ *   - number format: the 8-bit E4M3 format of the OCP 8-bit floating point specification (1 sign, 4 exponent bits
+ *     with bias 7, 3 mantissa bits; no infinities; S.1111.111 is NaN; largest finite value 448; subnormals
+ *     m/8 * 2^-6), the format the matrix cores of the target read;
+ *   - conversion: round to nearest, ties to even; magnitudes above 448 saturate to 448;
+ *   - scaling: one fp32 scale per token for x (amax of the row / 448), one per output column and expert for every
+ *     weight matrix (amax over the reduction index / 448), a given (calibrated, static) scale per expert for h;
+ *     a group that is all zero gets scale 1;  code = convert(value / scale) with the division in fp32;
+ *   - GEMM-1: g, u = (sum of products of codes) * s_x[t] * s_w[le][n];  h = silu(g) * u, rounded to fp32, divided
+ *     by s_h[le] in fp32 and converted;  GEMM-2: o = (sum of products of codes) * s_h[le] * s_wd[le][m];
+ *     then the weighted sum of Sec. III-C as in the unquantised layer.
+ * ------------------------------------------------------------------------------------------------------------ */
+
+/* value of an E4M3 code (NaN codes give NaN) */
+double moe_oracle_fp8_decode(uint8_t code) {
+  const int s = code >> 7, e = (code >> 3) & 15, m = code & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m / 8.0, -6);
+  else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+  return s ? -v : v;
+}
+
+/* fp32 -> E4M3: nearest code, ties to the code with even mantissa, saturating at +-448; NaN -> S.1111.111 */
+uint8_t moe_oracle_fp8_encode(float value) {
+  const uint8_t sign = signbit(value) ? 0x80 : 0x00;
+  if (isnan(value)) return (uint8_t)(sign | 0x7F);
+  const double a = fabs((double)value);
+  if (a >= 448.0) return (uint8_t)(sign | 0x7E);
+  if (a < ldexp(1.0, -6)) {
+    /* subnormal range: multiples of 2^-9; rint() rounds ties to even in the default rounding mode */
+    const int q = (int)rint(ldexp(a, 9)); /* 0..8; 8 is the smallest normal number, code 0x08 */
+    return (uint8_t)(sign | q);
+  }
+  int ex;
+  const double fr = frexp(a, &ex); /* a = fr * 2^ex, fr in [0.5, 1) */
+  int e = ex - 1;                  /* a = (2 fr) * 2^e, 2 fr in [1, 2) */
+  int q = (int)rint((2.0 * fr - 1.0) * 8.0); /* 0..8 */
+  if (q == 8) { q = 0; ++e; }
+  return (uint8_t)(sign | ((e + 7) << 3) | q); /* a < 448 keeps (e, q) at or below (8, 6) */
+}
+
+/*
+ * Quantise n_groups groups of group_len values each: element i of group g is a[g * group_stride + i * elem_stride]
+ * (rows of a matrix: group_stride = row length, elem_stride = 1; columns: group_stride = 1, elem_stride = row
+ * length).  codes uses the same indexing, scales is [n_groups].
+ */
+int moe_oracle_fp8_quantize(const float *a, int64_t n_groups, int64_t group_len, int64_t group_stride,
+                            int64_t elem_stride, uint8_t *codes, float *scales) {
+  if (!a || !codes || !scales || n_groups < 0 || group_len < 1) return ORACLE_BAD_ARG;
+#pragma omp parallel for schedule(static)
+  for (int64_t g = 0; g < n_groups; ++g) {
+    float amax = 0.0f;
+    for (int64_t i = 0; i < group_len; ++i) {
+      const float v = fabsf(a[g * group_stride + i * elem_stride]);
+      if (v > amax) amax = v;
+    }
+    const float scale = amax > 0.0f ? amax / 448.0f : 1.0f;
+    scales[g] = scale;
+    for (int64_t i = 0; i < group_len; ++i) {
+      const float v = a[g * group_stride + i * elem_stride] / scale; /* fp32 division */
+      codes[g * group_stride + i * elem_stride] = moe_oracle_fp8_encode(v);
+    }
+  }
+  return ORACLE_OK;
+}
+
+/*
+ * Forward with FP8 operands (see the reading above).  xq [T,d] codes with s_x [T]; Wg, Wu codes [E_loc,d,f] with
+ * scales [E_loc,f]; Wd codes [E_loc,f,d] with scales [E_loc,d]; s_h [E_loc].  Everything else as moe_oracle_forward.
+ */
+int moe_oracle_forward_fp8(int T, int d, int f, int E, int k, int R, int lrb, int lre, const uint8_t *xq,
+                           const float *s_x, const int32_t *topk_idx, const float *topk_w, const uint8_t *Wg,
+                           const float *s_g, const uint8_t *Wu, const float *s_u, const uint8_t *Wd,
+                           const float *s_d, const float *s_h, const int32_t *tokens, int n_tok, double *y_out) {
+  if (T < 0 || d < 1 || f < 1 || E < 1 || k < 1 || R < 1 || E % R != 0) return ORACLE_BAD_ARG;
+  if (lrb < 0 || lre <= lrb || lre > R || n_tok < 0) return ORACLE_BAD_ARG;
+  if (!xq || !s_x || !topk_idx || !topk_w || !Wg || !s_g || !Wu || !s_u || !Wd || !s_d || !s_h || !y_out)
+    return ORACLE_BAD_ARG;
+  const int epr = E / R;
+  const int e_lo = lrb * epr, e_hi = lre * epr;
+  double value[256];
+  for (int c = 0; c < 256; ++c) value[c] = moe_oracle_fp8_decode((uint8_t)c);
+  int status = ORACLE_OK;
+#pragma omp parallel
+  {
+    acc_t *g = (acc_t *)malloc(sizeof(acc_t) * (size_t)f);
+    acc_t *u = (acc_t *)malloc(sizeof(acc_t) * (size_t)f);
+    acc_t *o = (acc_t *)malloc(sizeof(acc_t) * (size_t)d);
+    acc_t *acc = (acc_t *)malloc(sizeof(acc_t) * (size_t)d);
+    if (!g || !u || !o || !acc) {
+#pragma omp critical
+      status = ORACLE_NOMEM;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int i = 0; i < n_tok; ++i) {
+        const int t = tokens ? tokens[i] : i;
+        for (int m = 0; m < d; ++m) acc[m] = 0;
+        if (t >= 0 && t < T) {
+          for (int j = 0; j < k; ++j) {
+            const int e = topk_idx[(size_t)t * k + j];
+            if (e < e_lo || e >= e_hi) continue;
+            const size_t le = (size_t)(e - e_lo);
+            const size_t wgu = le * (size_t)d * f, wdn = le * (size_t)f * d;
+            for (int n = 0; n < f; ++n) { g[n] = 0; u[n] = 0; }
+            for (int c = 0; c < d; ++c) {
+              const acc_t xc = (acc_t)value[xq[(size_t)t * d + c]];
+              const size_t rowb = wgu + (size_t)c * f;
+              for (int n = 0; n < f; ++n) {
+                g[n] += xc * (acc_t)value[Wg[rowb + n]];
+                u[n] += xc * (acc_t)value[Wu[rowb + n]];
+              }
+            }
+            for (int n = 0; n < f; ++n) {
+              const double gv = (double)g[n] * (double)s_x[t] * (double)s_g[le * f + n];
+              const double uv = (double)u[n] * (double)s_x[t] * (double)s_u[le * f + n];
+              const float h = (float)((gv / (1.0 + exp(-gv))) * uv);
+              g[n] = (acc_t)value[moe_oracle_fp8_encode(h / s_h[le])]; /* h as the code GEMM-2 reads */
+            }
+            for (int m = 0; m < d; ++m) o[m] = 0;
+            for (int n = 0; n < f; ++n) {
+              const acc_t hn = g[n];
+              const size_t rowb = wdn + (size_t)n * d;
+              for (int m = 0; m < d; ++m) o[m] += hn * (acc_t)value[Wd[rowb + m]];
+            }
+            const double w = (double)topk_w[(size_t)t * k + j];
+            for (int m = 0; m < d; ++m)
+              acc[m] += (acc_t)(w * ((double)o[m] * (double)s_h[le] * (double)s_d[le * d + m]));
           }
         }
         for (int m = 0; m < d; ++m) y_out[(size_t)i * d + m] = (double)acc[m];

@@ -76,3 +76,50 @@ def expected_unique_ranks_per_token(E: int, R: int, k: int) -> float:
     """E[#distinct ranks hit by a uniformly random k-subset of E experts] = R (1 - C(E-E/R, k) / C(E, k))."""
     epr = E // R
     return R * (1.0 - math.comb(E - epr, k) / math.comb(E, k))
+
+
+# ---------------------------------------------------------------- FP8 (E4M3) through a library's conversions
+def e4m3_values_closed_form():
+    """The 256 code values from the format's definition: sign, 4 exponent bits with bias 7, 3 mantissa bits,
+    subnormals m/8 * 2^-6, S.1111.111 = NaN, no infinities (OCP 8-bit floating point specification, E4M3)."""
+    out = np.empty(256, dtype=np.float64)
+    for c in range(256):
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            v = math.nan
+        elif e == 0:
+            v = m / 8.0 * 2.0 ** -6
+        else:
+            v = (1.0 + m / 8.0) * 2.0 ** (e - 7)
+        out[c] = -v if s else v
+    return out
+
+
+def e4m3_round_library(v32: np.ndarray):
+    """float32 -> nearest E4M3 value and code with PyTorch's CPU conversion (round to nearest even), after the
+    saturation to +-448 that the conversion itself does not do."""
+    import torch
+    t = torch.from_numpy(np.clip(np.asarray(v32, dtype=np.float32), -448.0, 448.0)).to(torch.float8_e4m3fn)
+    return t.to(torch.float32).numpy().astype(np.float64), t.view(torch.uint8).numpy()
+
+
+def ffn_dense_fp8(x, Wg, Wu, Wd, s_h):
+    """One dense SwiGLU FFN with E4M3 operands: per-row scale for x, per-column scales for the weights, a static
+    scale for h; library conversions and float64 library matmuls."""
+    x, Wg, Wu, Wd = (np.asarray(a, dtype=np.float32) for a in (x, Wg, Wu, Wd))
+
+    def scale_of(amax):
+        amax = amax.astype(np.float32)
+        return np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+
+    sx = scale_of(np.abs(x).max(axis=1))
+    xv, _ = e4m3_round_library(x / sx[:, None])
+    sg, su, sd = (scale_of(np.abs(W).max(axis=0)) for W in (Wg, Wu, Wd))
+    gv, _ = e4m3_round_library(Wg / sg[None, :])
+    uv, _ = e4m3_round_library(Wu / su[None, :])
+    dv, _ = e4m3_round_library(Wd / sd[None, :])
+    g = (xv @ gv) * sx[:, None].astype(np.float64) * sg[None, :].astype(np.float64)
+    u = (xv @ uv) * sx[:, None].astype(np.float64) * su[None, :].astype(np.float64)
+    h32 = ((g / (1.0 + np.exp(-g))) * u).astype(np.float32)
+    hv, _ = e4m3_round_library(h32 / np.float32(s_h))
+    return (hv @ dv) * float(np.float32(s_h)) * sd[None, :].astype(np.float64)

@@ -304,3 +304,133 @@ def test_bf16_rounding_helper_is_rne():
     assert got[4] == bits(-2.5) >> 16 and got[5] == 0
     back = wl.bf16_bits_to_f32(got)
     assert np.all(np.abs(back[:5] - vals[:5]) <= np.abs(vals[:5]) * 2 ** -8)
+
+
+# ---------------------------------------------------------------- FP8 (E4M3) operands
+def test_fp8_code_values_match_the_format_definition_and_a_library(oracle):
+    """All 256 codes: against the closed form of the format and against PyTorch's CPU decoding."""
+    import torch
+    codes = np.arange(256, dtype=np.uint8)
+    got = oracle.fp8_decode(codes)
+    np.testing.assert_array_equal(got, brute.e4m3_values_closed_form())
+    lib = torch.from_numpy(codes).view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    np.testing.assert_array_equal(got, lib)
+    # the format's landmarks (OCP 8-bit floating point specification, E4M3 column of its table of encodings)
+    assert got[0x7E] == 448.0 and got[0x08] == 2.0 ** -6 and got[0x07] == 0.875 * 2.0 ** -6 and got[0x01] == 2.0 ** -9
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF]) and got[0x38] == 1.0 and got[0xB8] == -1.0
+
+
+def test_fp8_conversion_is_round_to_nearest_even_and_saturates(oracle):
+    vals = brute.e4m3_values_closed_form()
+    finite = np.array([c for c in range(256) if not math.isnan(vals[c])], dtype=np.uint8)
+    # every code value converts to its own code (-0 and +0 keep their sign)
+    np.testing.assert_array_equal(oracle.fp8_encode(vals[finite].astype(np.float32)), finite)
+    # midpoints of neighbouring positive values go to the code with the even mantissa bit
+    pos = np.arange(0, 0x7E, dtype=np.uint8)
+    mid = ((vals[pos] + vals[pos + 1]) / 2).astype(np.float32)  # exact in fp32
+    want = np.where(pos % 2 == 0, pos, pos + 1).astype(np.uint8)
+    np.testing.assert_array_equal(oracle.fp8_encode(mid), want)
+    np.testing.assert_array_equal(oracle.fp8_encode(-mid), want | 0x80)
+    # just off the midpoints: the nearer neighbour
+    np.testing.assert_array_equal(oracle.fp8_encode(np.nextafter(mid, np.float32(np.inf))), pos + 1)
+    np.testing.assert_array_equal(oracle.fp8_encode(np.nextafter(mid, np.float32(0))), pos)
+    # saturation and NaN
+    big = np.array([448.0, 449.0, 464.0, 480.0, 1e30, np.inf], dtype=np.float32)
+    np.testing.assert_array_equal(oracle.fp8_encode(big), np.full(6, 0x7E, dtype=np.uint8))
+    np.testing.assert_array_equal(oracle.fp8_encode(-big), np.full(6, 0xFE, dtype=np.uint8))
+    assert oracle.fp8_encode(np.array([np.nan], dtype=np.float32))[0] & 0x7F == 0x7F
+    # random values, several magnitudes: same codes as the library's conversion
+    rng = np.random.default_rng(5)
+    v = np.concatenate([rng.standard_normal(20000) * s for s in (1e-3, 0.02, 1.0, 30.0, 200.0)]).astype(np.float32)
+    _, lib_codes = brute.e4m3_round_library(v)
+    np.testing.assert_array_equal(oracle.fp8_encode(v), lib_codes)
+
+
+def test_fp8_quantize_rows_and_columns(oracle):
+    rng = np.random.default_rng(6)
+    a = (rng.standard_normal((7, 33)) * rng.uniform(0.01, 50, size=(7, 1))).astype(np.float32)
+    a[3] = 0.0  # an all-zero group
+    codes, scales = oracle.fp8_quantize(a, axis=-1)
+    amax = np.abs(a).max(axis=1)
+    np.testing.assert_array_equal(scales, np.where(amax > 0, amax / np.float32(448.0), np.float32(1.0)))
+    _, lib_codes = brute.e4m3_round_library(a / scales[:, None])
+    np.testing.assert_array_equal(codes, lib_codes)
+    assert np.all(codes[3] == 0) and scales[3] == 1.0
+    # the largest element of a group lands on +-448; the others within half a step (2^-4 relative for normal numbers)
+    top = np.abs(a).argmax(axis=1)
+    assert all((codes[r, top[r]] & 0x7F) == 0x7E for r in range(7) if r != 3)
+    back = oracle.fp8_decode(codes) * scales[:, None]
+    normal = np.abs(a) >= scales[:, None] * 2.0 ** -6
+    assert np.all(np.abs(back - a)[normal] <= np.abs(a)[normal] * 2.0 ** -4 * (1 + 1e-6))
+    assert np.all(np.abs(back - a)[~normal] <= scales[:, None].repeat(33, 1)[~normal] * 2.0 ** -10 * (1 + 1e-6))
+    # columns of a matrix = rows of its transpose, also with a batch dimension
+    b = rng.standard_normal((3, 12, 5)).astype(np.float32)
+    cc, sc = oracle.fp8_quantize(b, axis=-2)
+    for e in range(3):
+        cr, sr = oracle.fp8_quantize(np.ascontiguousarray(b[e].T), axis=-1)
+        np.testing.assert_array_equal(cc[e], cr.T)
+        np.testing.assert_array_equal(sc[e], sr)
+
+
+def test_fp8_forward_single_expert_vs_library_conversions(oracle):
+    """E = 1, k = 1, weight 1: the FP8 layer written with PyTorch's conversions and float64 library products."""
+    cfg = small_cfg(E=1, k=1, R=1, local_rank_begin=0, local_rank_end=1, T=12, d=24, f=20)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, 1)
+    s_h = np.array([0.013], dtype=np.float32)
+    y = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, s_h, 1, 1, 0, 1)
+    want = brute.ffn_dense_fp8(w.x, w.W_gate[0], w.W_up[0], w.W_down[0], s_h[0])
+    np.testing.assert_allclose(y, want, rtol=1e-9, atol=1e-12)
+    # a scale for h that is far too small saturates every h to +-448 s_h: the layer still matches
+    s_h = np.array([1e-6], dtype=np.float32)
+    y = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, s_h, 1, 1, 0, 1)
+    np.testing.assert_allclose(y, brute.ffn_dense_fp8(w.x, w.W_gate[0], w.W_up[0], w.W_down[0], s_h[0]),
+                               rtol=1e-9, atol=1e-15)
+
+
+def test_fp8_forward_properties(oracle):
+    cfg = small_cfg(T=40, local_rank_begin=1, local_rank_end=3)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    El = w.W_gate.shape[0]
+    s_h = (0.01 * (1 + np.arange(El) % 3)).astype(np.float32)
+    args = (cfg.E, cfg.R, 1, 3)
+    y = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, s_h, *args)
+    # close to the unquantised layer (three roundings of 2^-4 relative per product, averaged over the sums) ...
+    y0 = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, *args)
+    rel = np.linalg.norm(y - y0) / np.linalg.norm(y0)
+    assert 1e-3 < rel < 0.1
+    # ... per-column scales absorb powers of two exactly: scaling W_down's columns scales y's columns
+    factors = (2.0 ** (np.arange(w.W_down.shape[2]) % 7 - 3)).astype(np.float32)
+    y2 = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down * factors[None, None, :], s_h, *args)
+    np.testing.assert_array_equal(y2, y * factors[None, :].astype(np.float64))
+    y4 = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up * np.float32(4), w.W_down, s_h * np.float32(4), *args)
+    # u scaled by 4 and s_h by 4: the same h codes, so y is exactly 4 y
+    np.testing.assert_array_equal(y4, 4.0 * y)
+    # tokens without a local slot give zero rows; a token subset gives the same rows
+    sub = np.array([5, 0, 17], dtype=np.int32)
+    np.testing.assert_array_equal(oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, s_h, *args, tokens=sub),
+                                  y[sub])
+    epr = cfg.E // cfg.R
+    none_local = ~((idx >= epr) & (idx < 3 * epr)).any(axis=1)
+    assert np.all(y[none_local] == 0)
+
+
+def test_fp8_forward_vs_per_slot_bruteforce(oracle):
+    """Several experts and ranks: every (token, local slot) as its own one-row dense FP8 FFN (a token's scale
+    depends on its own row only), weighted and summed in slot order."""
+    cfg = small_cfg(T=24, local_rank_begin=1, local_rank_end=3)
+    w = _draw(cfg)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    El = w.W_gate.shape[0]
+    epr = cfg.E // cfg.R
+    s_h = (0.004 * (1 + np.arange(El))).astype(np.float32)
+    y = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, s_h, cfg.E, cfg.R, 1, 3)
+    want = np.zeros_like(y)
+    for t in range(cfg.T):
+        for j in range(cfg.k):
+            le = int(idx[t, j]) - epr
+            if 0 <= le < El:
+                want[t] += float(tw[t, j]) * brute.ffn_dense_fp8(w.x[t:t + 1], w.W_gate[le], w.W_up[le], w.W_down[le],
+                                                                 s_h[le])[0]
+    np.testing.assert_allclose(y, want, rtol=1e-9, atol=1e-12)
