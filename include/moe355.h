@@ -206,6 +206,37 @@ MOE355_API int moe_unfused_forward(const moe_shape *shape, const void *x, const 
                                    const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
                                    void *stream);
 
+/*
+ * FP8 form of the expert GEMMs (Sec. V-A: the DeepSeek-V3 runs use FP8 GEMM kernels; the paper gives no scheme).
+ * For bf16 layers (shape->dtype == MOE_BF16) with d % 16 == 0 and f % 16 == 0, MOE_ERR_UNSUPPORTED otherwise.
+ * Operands of both GEMMs are E4M3 codes of the OCP 8-bit floating point format (round to nearest even, saturating
+ * at +-448), products are accumulated in fp32:
+ *   x       one scale per token   = largest magnitude of the row / 448 (1 for a zero row), code = cvt(x / scale);
+ *   weights one scale per expert and output column, same rule over the reduction index;
+ *   h       code = cvt(silu(g) * u / h_scale[le]) with a given (calibrated, static) scale per local expert;
+ *   g, u = (sum of code products) * scale(token) * scale(column);  o = (sum) * h_scale[le] * scale(column) * w.
+ * y, the tables, the gate weights and the reduction are those of moe_fused_forward (y in bf16).
+ *
+ * moe_fp8_pack_weights: one-off; quantises the bf16 weights (same layouts as moe_pack_weights) and writes the
+ *   tiles followed by the column scales into buffers of moe_fp8_packed_weight_bytes(shape, 0 / 1) bytes, 16-byte
+ *   aligned.
+ * moe_fp8_quantize_rows: the activation quantiser on its own: x [rows, cols] bf16 (16-byte aligned, cols % 8 == 0)
+ *   -> codes [rows, cols] (8-byte aligned), scales [rows].  moe_fp8_fused_forward runs it on x internally.
+ * moe_fp8_fused_forward: as moe_fused_forward with the packed FP8 weights and h_scale [E_loc] (device);
+ *   workspace >= moe_fp8_forward_workspace_bytes(shape), 256-byte aligned; the two GEMMs run as one or two launches
+ *   by the rule of moe_forward_gemm_launches.  `events` may be NULL, otherwise five events as in
+ *   moe_fused_forward_timed ([1] follows the quantisation of x and the tile table).
+ */
+MOE355_API size_t moe_fp8_packed_weight_bytes(const moe_shape *shape, int which);
+MOE355_API size_t moe_fp8_forward_workspace_bytes(const moe_shape *shape);
+MOE355_API int moe_fp8_pack_weights(const moe_shape *shape, const void *W_gate, const void *W_up, const void *W_down,
+                                    void *packed_gate_up, void *packed_down, void *stream);
+MOE355_API int moe_fp8_quantize_rows(int64_t rows, int cols, const void *x, void *codes, float *scales, void *stream);
+MOE355_API int moe_fp8_fused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                     const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                     const void *packed_down, const float *h_scale, void *y, void *workspace,
+                                     size_t workspace_bytes, void *stream, void *const *events);
+
 /* Static string for a status code. */
 MOE355_API const char *moe_status_string(int status);
 

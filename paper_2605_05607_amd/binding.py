@@ -78,6 +78,16 @@ def lib() -> C.CDLL:
             fn = getattr(L, name)
             fn.restype = i32
             fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
+        L.moe_fp8_packed_weight_bytes.restype = sz
+        L.moe_fp8_packed_weight_bytes.argtypes = [sp, i32]
+        L.moe_fp8_forward_workspace_bytes.restype = sz
+        L.moe_fp8_forward_workspace_bytes.argtypes = [sp]
+        L.moe_fp8_pack_weights.restype = i32
+        L.moe_fp8_pack_weights.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        L.moe_fp8_quantize_rows.restype = i32
+        L.moe_fp8_quantize_rows.argtypes = [C.c_int64, i32, vp, vp, vp, vp]
+        L.moe_fp8_fused_forward.restype = i32
+        L.moe_fp8_fused_forward.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
         L.moe_dispatch_gather.restype = i32
         L.moe_dispatch_gather.argtypes = [sp, vp, dp, vp, vp]
         L.moe_combine_reduce.restype = i32
@@ -239,6 +249,34 @@ def moe_unfused_forward(shape, x, topk_idx, topk_w, tables, packed_gate_up, pack
                         workspace_bytes=None, stream=None) -> None:
     _forward("moe_unfused_forward", shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
              workspace_bytes, stream)
+
+
+def moe_fp8_packed_weight_bytes(shape: moe_shape, which: int) -> int:
+    return int(lib().moe_fp8_packed_weight_bytes(C.byref(shape), which))
+
+
+def moe_fp8_forward_workspace_bytes(shape: moe_shape) -> int:
+    return int(lib().moe_fp8_forward_workspace_bytes(C.byref(shape)))
+
+
+def moe_fp8_pack_weights(shape, W_gate, W_up, W_down, packed_gate_up, packed_down, stream=None) -> None:
+    _check(lib().moe_fp8_pack_weights(C.byref(shape), _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(packed_gate_up),
+                                      _ptr(packed_down), _stream(stream)), "moe_fp8_pack_weights")
+
+
+def moe_fp8_quantize_rows(rows: int, cols: int, x, codes, scales, stream=None) -> None:
+    _check(lib().moe_fp8_quantize_rows(rows, cols, _ptr(x), _ptr(codes), _ptr(scales), _stream(stream)),
+           "moe_fp8_quantize_rows")
+
+
+def moe_fp8_fused_forward(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, h_scale, y, workspace,
+                          events=None, workspace_bytes=None, stream=None) -> None:
+    """`events`: None or five raw hipEvent_t handles as for moe_fused_forward_timed."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    arr = None if events is None else (C.c_void_p * 5)(*[C.c_void_p(int(e)) if e else None for e in events])
+    _check(lib().moe_fp8_fused_forward(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w), C.byref(tables.struct),
+                                       _ptr(packed_gate_up), _ptr(packed_down), _ptr(h_scale), _ptr(y),
+                                       _ptr(workspace), nbytes, _stream(stream), arr), "moe_fp8_fused_forward")
 
 
 def moe_dispatch_gather(shape, x, tables, xs, stream=None) -> None:

@@ -5,6 +5,7 @@
 #include <algorithm>
 
 #include "combine_kernels.h"
+#include "fp8_kernels.h"
 #include "gemm_bf16.h"
 #include "gemm_f32.h"
 #include "pack_kernels.h"
@@ -48,11 +49,24 @@ static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch
   return launch_status();
 }
 
+// FP8 form of the GEMMs: quantised x with its per-token scales, the column scales that follow the packed tiles,
+// and the per-expert scale of h.
+struct Fp8Operands {
+  const uint8_t *xq;
+  const float *x_scale, *gu_scale, *down_scale, *h_scale;
+};
+
+static size_t fp8_tile_bytes(const moe_shape *s, const Derived &dv, int which) {
+  if (which == 0) return (size_t)dv.E_loc * ceil_div(s->f, kBN / 2) * ceil_div(s->d, kFp8KStep) * kTileBytes;
+  return (size_t)dv.E_loc * ceil_div(s->d, kBN) * ceil_div(s->f, kFp8KStep) * kTileBytes;
+}
+
 // GEMM-1 (gated) then GEMM-2 on the rows described by the tile table.  a1 / a1_map select the A operand of
 // GEMM-1: the token matrix with the row -> token map (fused gather) or a materialised copy (map == nullptr).
 static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, const int32_t *a1_map, int a1_ld,
                         const void *packed_gu, const void *packed_down, const Ws &w, const int32_t *sole, void *y,
-                        hipStream_t st, void *const *events = nullptr, bool pipelined = false) {
+                        hipStream_t st, void *const *events = nullptr, bool pipelined = false,
+                        const Fp8Operands *q = nullptr) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
@@ -67,6 +81,37 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
   g2.K = s->f; g2.N = s->d; g2.lda = s->f; g2.ldo = s->d;
   g2.n_items = w.header + 3; g2.work = w.work2;
   const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dv.max_mtiles * nt + 255) / 256 * 256)); };
+  if (q) {
+    static std::atomic<uint64_t> done1{0}, done2{0}, done_pipe{0};
+    if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<true, true>), 2 * kStageBytes, done1) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<false, true>), 2 * kStageBytes, done2) ||
+        !allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_fp8_pipeline_kernel), 2 * kStageBytes, done_pipe))
+      return MOE_ERR_HIP;
+    g1.A = q->xq; g1.a_scale = q->x_scale; g1.b_scale = q->gu_scale; g1.h_scale = q->h_scale;
+    g2.b_scale = q->down_scale; g2.h_scale = q->h_scale;
+    g1.n_ntiles = ceil_div(s->f, kBN / 2); g1.n_ktiles = ceil_div(s->d, kFp8KStep);
+    g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kFp8KStep);
+    if (pipelined) {
+      int dev = 0, n_cu = 0;
+      if (hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+        return MOE_ERR_HIP;
+      PipelineArgs pa;
+      pa.g1 = g1; pa.g2 = g2;
+      pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1;
+      hipLaunchKernelGGL(gemm_fp8_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st, pa);
+      mark(2);
+      mark(3);
+      return launch_status();
+    }
+    hipLaunchKernelGGL((gemm_bf16_kernel<true, true>), grid_of(dv.nt1), dim3(kGemmThreads), 2 * kStageBytes, st, g1);
+    int rc = launch_status();
+    mark(2);
+    if (rc != MOE_OK) return rc;
+    hipLaunchKernelGGL((gemm_bf16_kernel<false, true>), grid_of(dv.nt2), dim3(kGemmThreads), 2 * kStageBytes, st, g2);
+    mark(3);
+    return launch_status();
+  }
   if (s->dtype == MOE_BF16) {
     // the two LDS stages (128 KiB) exceed the default dynamic limit; raising it is a per-function attribute
     static std::atomic<uint64_t> done1{0}, done2{0}, done_pipe{0};
@@ -166,13 +211,17 @@ extern "C" int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
 static int forward_common(const moe_shape *shape, const void *x, const int32_t *topk_idx, const float *topk_w,
                           const moe_dispatch *tables, const void *packed_gate_up, const void *packed_down, void *y,
                           void *workspace, size_t workspace_bytes, void *stream, bool fused,
-                          void *const *events = nullptr, int gemm_launches = 0) {
+                          void *const *events = nullptr, int gemm_launches = 0, const float *h_scale = nullptr) {
   Derived dv;
   int rc = check_shape(shape, &dv);
   if (rc != MOE_OK) return rc;
   if (!x || !topk_idx || !topk_w || !packed_gate_up || !packed_down || !y || !tables_ok(tables))
     return MOE_ERR_INVALID_ARG;
-  const size_t need = fused ? moe_forward_workspace_bytes(shape) : moe_unfused_workspace_bytes(shape);
+  const bool fp8 = h_scale != nullptr;  // FP8 GEMMs: bf16 layers whose rows are whole 16-code chunks
+  if (fp8 && (shape->dtype != MOE_BF16 || shape->d % 16 != 0 || shape->f % 16 != 0)) return MOE_ERR_UNSUPPORTED;
+  const size_t need = fp8     ? moe_fp8_forward_workspace_bytes(shape)
+                      : fused ? moe_forward_workspace_bytes(shape)
+                              : moe_unfused_workspace_bytes(shape);
   if (!workspace || workspace_bytes < need) return MOE_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MOE_ERR_INVALID_ARG;
   // rows are moved 16 bytes at a time
@@ -198,11 +247,28 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   // fused bf16 layers: GEMM-2 writes the rows that need no reduction straight to y and Combine skips them
   int32_t *sole = fused && shape->dtype == MOE_BF16 ? w.row_sole : nullptr;
   mark(0);
+  Fp8Operands q{};
+  if (fp8) {
+    // x as codes with one scale per token, behind the tile-table part of the workspace
+    unsigned char *b = static_cast<unsigned char *>(workspace);
+    uint8_t *xq = b + L.total;
+    float *x_scale = reinterpret_cast<float *>(b + L.total + align_up((size_t)shape->T * shape->d, 256));
+    hipLaunchKernelGGL(fp8_quantize_rows_kernel, dim3((unsigned)shape->T), dim3(256), 0, st,
+                       static_cast<const uint4 *>(x), shape->d, xq, x_scale);
+    if ((rc = launch_status()) != MOE_OK) return rc;
+    q.xq = xq;
+    q.x_scale = x_scale;
+    q.gu_scale = reinterpret_cast<const float *>(static_cast<const unsigned char *>(packed_gate_up) +
+                                                 align_up(fp8_tile_bytes(shape, dv, 0), 256));
+    q.down_scale = reinterpret_cast<const float *>(static_cast<const unsigned char *>(packed_down) +
+                                                   align_up(fp8_tile_bytes(shape, dv, 1), 256));
+    q.h_scale = h_scale;
+  }
   if ((rc = launch_prep(shape, dv, tables, topk_idx, topk_w, w, sole, st)) != MOE_OK) return rc;
   mark(1);
   if (fused) {
     if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, sole, y, st,
-                           events, pipelined)) != MOE_OK)
+                           events, pipelined, fp8 ? &q : nullptr)) != MOE_OK)
       return rc;
     rc = launch_combine(shape, dv, w.o, topk_idx, tables, y, sole != nullptr, st);
     mark(4);
@@ -228,6 +294,77 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   else
     hipLaunchKernelGGL(cast_rows_kernel<float>, dim3(2048), dim3(256), 0, st, y32, static_cast<float *>(y), n / 8);
   return launch_status();
+}
+
+extern "C" size_t moe_fp8_packed_weight_bytes(const moe_shape *shape, int which) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK || (which != 0 && which != 1)) return 0;
+  const size_t scales = (size_t)dv.E_loc * (which == 0 ? 2 * (size_t)shape->f : (size_t)shape->d) * sizeof(float);
+  return align_up(fp8_tile_bytes(shape, dv, which), 256) + align_up(scales, 256);
+}
+
+extern "C" size_t moe_fp8_forward_workspace_bytes(const moe_shape *shape) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK) return 0;
+  const size_t T = (size_t)(shape->T > 0 ? shape->T : 1);
+  return forward_layout(shape, dv).total + align_up(T * shape->d, 256) + align_up(T * sizeof(float), 256);
+}
+
+extern "C" int moe_fp8_pack_weights(const moe_shape *shape, const void *W_gate, const void *W_up, const void *W_down,
+                                    void *packed_gate_up, void *packed_down, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!W_gate || !W_up || !W_down || !packed_gate_up || !packed_down) return MOE_ERR_INVALID_ARG;
+  if (shape->dtype != MOE_BF16 || shape->d % 16 != 0 || shape->f % 16 != 0) return MOE_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(packed_gate_up) | reinterpret_cast<uintptr_t>(packed_down)) % 16 != 0)
+    return MOE_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  begin_launches();
+  const int d = shape->d, f = shape->f;
+  const int nt1 = ceil_div(f, kBN / 2), kt1 = ceil_div(d, kFp8KStep);
+  const int nt2 = ceil_div(d, kBN), kt2 = ceil_div(f, kFp8KStep);
+  if (nt1 > 65535 || nt2 > 65535 || dv.E_loc > 65535) return MOE_ERR_UNSUPPORTED;
+  uint8_t *gu = static_cast<uint8_t *>(packed_gate_up), *dn = static_cast<uint8_t *>(packed_down);
+  float *s_gu = reinterpret_cast<float *>(gu + align_up(fp8_tile_bytes(shape, dv, 0), 256));  // [E_loc][2][f]
+  float *s_dn = reinterpret_cast<float *>(dn + align_up(fp8_tile_bytes(shape, dv, 1), 256));  // [E_loc][d]
+  const bf16_t *Wg = static_cast<const bf16_t *>(W_gate), *Wu = static_cast<const bf16_t *>(W_up);
+  const bf16_t *Wd = static_cast<const bf16_t *>(W_down);
+  hipLaunchKernelGGL(fp8_column_scales_kernel, dim3(ceil_div(f, 256), dv.E_loc), dim3(256), 0, st, Wg, d, f, s_gu,
+                     2 * f);
+  hipLaunchKernelGGL(fp8_column_scales_kernel, dim3(ceil_div(f, 256), dv.E_loc), dim3(256), 0, st, Wu, d, f, s_gu + f,
+                     2 * f);
+  hipLaunchKernelGGL(fp8_column_scales_kernel, dim3(ceil_div(d, 256), dv.E_loc), dim3(256), 0, st, Wd, f, d, s_dn, d);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  hipLaunchKernelGGL(pack_fp8_kernel<true>, dim3(kt1, nt1, dv.E_loc), dim3(256), 0, st, Wg, Wu, s_gu, s_gu + f, 2 * f,
+                     gu, d, f, nt1, kt1);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  hipLaunchKernelGGL(pack_fp8_kernel<false>, dim3(kt2, nt2, dv.E_loc), dim3(256), 0, st, Wd,
+                     static_cast<const bf16_t *>(nullptr), s_dn, static_cast<const float *>(nullptr), d, dn, f, d, nt2,
+                     kt2);
+  return launch_status();
+}
+
+extern "C" int moe_fp8_quantize_rows(int64_t rows, int cols, const void *x, void *codes, float *scales,
+                                     void *stream) {
+  if (rows < 0 || rows > 0x7FFFFFFF || cols < 8 || cols % 8 != 0) return MOE_ERR_INVALID_ARG;
+  if (!x || !codes || !scales) return MOE_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(x) % 16) != 0 || (reinterpret_cast<uintptr_t>(codes) % 8) != 0)
+    return MOE_ERR_INVALID_ARG;
+  if (rows == 0) return MOE_OK;
+  begin_launches();
+  hipLaunchKernelGGL(fp8_quantize_rows_kernel, dim3((unsigned)rows), dim3(256), 0, (hipStream_t)stream,
+                     static_cast<const uint4 *>(x), cols, static_cast<uint8_t *>(codes), scales);
+  return launch_status();
+}
+
+extern "C" int moe_fp8_fused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                     const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                     const void *packed_down, const float *h_scale, void *y, void *workspace,
+                                     size_t workspace_bytes, void *stream, void *const *events) {
+  if (!h_scale) return MOE_ERR_INVALID_ARG;
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, events, 0, h_scale);
 }
 
 extern "C" int moe_fused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx, const float *topk_w,

@@ -11,6 +11,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
 
+// fp32 -> E4M3 code (OCP 8-bit floating point, the format the matrix cores read): round to nearest even,
+// saturating at +-448; finite input.
+__device__ __forceinline__ uint8_t to_e4m3(float v) {
+  v = __builtin_amdgcn_fmed3f(v, 448.0f, -448.0f);
+  return (uint8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(v, v, 0, false) & 0xFF);
+}
+
 constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS stage image of B (32 KiB)
 
 constexpr int kTileShift = 12;  // work item .w = N tile | M-tile id << kTileShift
@@ -44,6 +51,10 @@ struct GemmArgs {
   const int32_t *n_items;  // device: number of work items of this GEMM
   const int4 *work;        // device: work list
   int K, N, lda, ldo, n_ntiles, n_ktiles;
+  // FP8 operands only (null otherwise)
+  const float *a_scale;  // GEMM-1: scale of every token's row of x (indexed like A's rows)
+  const float *b_scale;  // scales of the output columns: GEMM-1 [E_loc][2][N] (gate, up), GEMM-2 [E_loc][N]
+  const float *h_scale;  // [E_loc] scale of h: GEMM-1 divides by it, GEMM-2 multiplies
 };
 
 }  // namespace moe355

@@ -1,5 +1,7 @@
 // Grouped bf16 GEMMs on the matrix cores: tile, work item, the per-item kernels and the resident kernel.
 #pragma once
+#include <type_traits>
+
 #include "forward_types.h"
 
 namespace moe355 {
@@ -23,12 +25,31 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// FP8 operands (E4M3): a 16-byte fragment holds 16 reduction indices per lane and feeds two instructions of 8
+// indices per lane half each; which indices share an instruction does not matter as long as A and B agree, and
+// both use "low 8 bytes, then high 8 bytes" of the same 16-byte chunk of the reduction range.
+typedef long i64x2 __attribute__((ext_vector_type(2)));
+template <bool FP8>
+__device__ __forceinline__ f32x16 mfma_frag(bf16x8 a, bf16x8 b, f32x16 c) {
+  if constexpr (FP8) {
+    const i64x2 a2 = __builtin_bit_cast(i64x2, a), b2 = __builtin_bit_cast(i64x2, b);
+    c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[0], b2[0], c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[1], b2[1], c, 0, 0, 0);
+  } else {
+    return mfma_bf16(a, b, c);
+  }
+}
+
 constexpr int kGemmThreads = 512;
 constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
 constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
 constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue patch (fits 8 x in the stages)
 
-template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH>
+// FP8: A and the packed B hold E4M3 codes; a k-step then covers 128 reduction indices in the same 128 bytes per row,
+// so the staging, the LDS image and the fragment reads are byte for byte those of the bf16 tile.  The scales
+// (g.a_scale per token, g.b_scale per expert and output column, g.h_scale per expert) are applied in the epilogues
+// and GEMM-1 writes h as codes.
+template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
                                                int rows, int nblk_total) {
   // RESIDENT (the kernel that loops over items): the thread index goes through an empty asm so that nothing
@@ -44,7 +65,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // A: thread t stages chunk t & 7 (8 reduction indices) of rows (t >> 3) + 64 i; B: chunks t + 512 i
   const int a_chunk = tid & 7;
   const int a_row0 = tid >> 3;  // 0..63
-  const bf16_t *a_base = static_cast<const bf16_t *>(g.A) + a_chunk * 8;
+  typedef typename std::conditional<FP8, uint8_t, bf16_t>::type elt_t;
+  constexpr int EPC = FP8 ? 16 : 8;    // elements per 16-byte chunk
+  constexpr int KS = FP8 ? 128 : kBK;  // reduction indices per k-step
+  const elt_t *a_base = static_cast<const elt_t *>(g.A) + a_chunk * EPC;
 #define MOE355_A_ROW(i)                                                                          \
   const int a_rc##i = a_row0 + 64 * i < rows ? a_row0 + 64 * i : rows - 1; /* padding: a valid row */ \
   const uint32_t a_off##i =                                                                      \
@@ -64,7 +88,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // A slab is moved in three portions: {ra0, ra1, rb0}, {ra2, ra3, rb1}, {rb2, rb3}
   // k tail: a chunk past K is replaced by chunk 0 of the same row (valid memory, finite data); the packed B
   // tile is zero there, so it contributes nothing and no select has to wait on the load
-#define MOE355_A_OFF(KT) ((KT) * kBK + a_chunk * 8 < g.K ? (KT) * kBK : -a_chunk * 8)
+#define MOE355_A_OFF(KT) ((KT) * KS + a_chunk * EPC < g.K ? (KT) * KS : -a_chunk * EPC)
   // NA = row loads per thread that reach valid rows (1: rows < 64, 2: rows < 128, 4: all); the others are skipped
 #define MOE355_LOAD_P0(S, KT)                                                                       \
   do {                                                                                              \
@@ -132,8 +156,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 #define MOE355_MFMAS(FA, FB)                                                                           \
   do {                                                                                                 \
     _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) {                                                \
-      acc[mi][0] = mfma_bf16(FA[mi], FB[0], acc[mi][0]);                                               \
-      acc[mi][1] = mfma_bf16(FA[mi], FB[1], acc[mi][1]);                                               \
+      acc[mi][0] = mfma_frag<FP8>(FA[mi], FB[0], acc[mi][0]);                                          \
+      acc[mi][1] = mfma_frag<FP8>(FA[mi], FB[1], acc[mi][1]);                                          \
     }                                                                                                  \
   } while (0)
 
@@ -150,7 +174,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   do {                                                                                                 \
     if (NB > 0) {                                                                                      \
       __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);                                          \
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                          \
+      __builtin_amdgcn_sched_group_barrier(0x008, (FP8 ? 4 : 2) * NB, 0);                              \
     }                                                                                                  \
     if ((NW) > 0) {                                                                                    \
       __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                            \
@@ -228,7 +252,33 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 #pragma unroll
   for (int mi = 0; mi < NB; ++mi) {
     const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
-    if (GATED) {
+    if (GATED && FP8) {
+      // h block: 32 rows x 32 columns of E4M3 codes, row pitch 48 bytes.  g and u get the scales of their token
+      // and of their columns; h = silu(g) * u is divided by the expert's scale for h and converted.
+      const int col_h = nt * (kBN / 2) + wn * 32 + l31;
+      const float *bs = g.b_scale + (size_t)le * 2 * g.N;
+      const float sg = col_h < g.N ? bs[col_h] : 0.f, su = col_h < g.N ? bs[g.N + col_h] : 0.f;
+      const float sh = g.h_scale[le];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+        const int row_l = min(blk_row0 + rl, rows - 1);
+        const float sx = g.a_scale[g.row_map ? g.row_map[m0 + row_l] : m0 + row_l];
+        const float gv = acc[mi][0][r] * (sx * sg), uv = acc[mi][1][r] * (sx * su);
+        patch[rl * 48 + l31] = to_e4m3(((gv / (1.0f + __expf(-gv))) * uv) / sh);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      {
+        const int rl = lane >> 1, cc = lane & 1;  // 16-byte chunk: 2 chunks per row
+        const int row_l = blk_row0 + rl;
+        const int col = nt * (kBN / 2) + wn * 32 + cc * 16;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + rl * 48 + cc * 16);
+        if (row_l < rows && col < g.N)
+          *reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+      }
+    } else if (GATED) {
       // h block: 32 rows x 32 columns bf16, row pitch 80 bytes (keeps the two half-waves on different banks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -252,6 +302,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     } else {
       // o block: 32 rows x 64 columns fp32, row pitch 288 bytes.  A row whose token has no other local slot
       // is final already (the Combine sum would have one term): it goes to y in the output type, skipping o.
+      // FP8: the scale of the expert's h times the scale of the lane's two output columns
+      float cs0 = 1.f, cs1 = 1.f;
+      if (FP8) {
+        const int c0 = nt * kBN + wn * 64 + l31;
+        const float sh = g.h_scale[le];
+        cs0 = c0 < g.N ? sh * g.b_scale[(size_t)le * g.N + c0] : 0.f;
+        cs1 = c0 + 32 < g.N ? sh * g.b_scale[(size_t)le * g.N + c0 + 32] : 0.f;
+      }
       int sole[8];
 #pragma unroll
       for (int it = 0; it < 8; ++it) {
@@ -263,8 +321,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const int row_l = blk_row0 + rl;
         const float wgt = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
-        *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = acc[mi][0][r] * wgt;
-        *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) = acc[mi][1][r] * wgt;
+        *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = FP8 ? acc[mi][0][r] * cs0 * wgt : acc[mi][0][r] * wgt;
+        *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) =
+            FP8 ? acc[mi][1][r] * cs1 * wgt : acc[mi][1][r] * wgt;
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -294,14 +353,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 
 // One work item on the matrix cores.  Wave-uniform dispatch on the number of valid 32-row blocks: every variant
 // executes the same sequence of barriers.
-template <bool GATED, bool RESIDENT>
+template <bool GATED, bool RESIDENT, bool FP8 = false>
 __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item) {
   const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
 #define MOE355_TILE(NB_, NA_) \
-  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1)>(g, smem, nt, le, m0, rows, nblk_total)
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8>(g, smem, nt, le, m0, rows, nblk_total)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -314,12 +373,12 @@ __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char 
 }
 
 // One workgroup per work item; workgroup -> item by chunked_item.
-template <bool GATED>
+template <bool GATED, bool FP8 = false>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
   const int q = chunked_item(blockIdx.x, *g.n_items);
   if (q < 0) return;
-  gemm_bf16_item<GATED, false>(g, smem, g.work[q]);
+  gemm_bf16_item<GATED, false, FP8>(g, smem, g.work[q]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -354,7 +413,7 @@ struct PipelineArgs {
 constexpr int kMaxPolls = 1 << 22;  // x ~1 us: a bound so that no wave can wait forever
 
 // All items of one GEMM that this workgroup can get hold of: home queue first, then the other queues.
-template <bool GATED>
+template <bool GATED, bool FP8 = false>
 __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char *smem, int *s_item,
                                                 int32_t *__restrict__ tickets, int32_t *__restrict__ tile_ready,
                                                 int32_t *__restrict__ error, int nt1) {
@@ -401,7 +460,7 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
     const int4 item = g.work[q];
     const int tile = item.w >> kTileShift;
     if (GATED) {
-      gemm_bf16_item<true, true>(g, smem, item);
+      gemm_bf16_item<true, true, FP8>(g, smem, item);
       // every wave first waits until its own h stores have been acknowledged (vmcnt(0); gfx9 encoding with the
       // other counters left at their maxima), so that the one write-back below cannot overtake any of them
       __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -428,7 +487,7 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
         __builtin_amdgcn_s_waitcnt(0x0F70);  // the invalidate is complete before the barrier lets the others load
       }
       __syncthreads();
-      gemm_bf16_item<false, true>(g, smem, item);
+      gemm_bf16_item<false, true, FP8>(g, smem, item);
     }
   }
 }
@@ -438,6 +497,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(con
   __shared__ int s_item;
   gemm_bf16_drain<true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
   gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
+}
+
+// The same resident kernel on E4M3 operands.
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_fp8_pipeline_kernel(const PipelineArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  __shared__ int s_item;
+  gemm_bf16_drain<true, true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
+  gemm_bf16_drain<false, true>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
 }
 
 }  // namespace moe355

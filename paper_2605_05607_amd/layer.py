@@ -52,6 +52,23 @@ class MoELayer:
         torch.cuda.synchronize()
         del g, u, d
 
+    def load_weights_fp8(self, W_gate: np.ndarray, W_up: np.ndarray, W_down: np.ndarray, h_scale: np.ndarray) -> None:
+        """Quantise and pack the weights for the FP8 form of the GEMMs; h_scale [E_loc] is the static scale of h."""
+        import torch
+        s = self.shape
+        self.fp8_gate_up = torch.empty(B.moe_fp8_packed_weight_bytes(s, 0), dtype=torch.uint8, device=self.device)
+        self.fp8_down = torch.empty(B.moe_fp8_packed_weight_bytes(s, 1), dtype=torch.uint8, device=self.device)
+        self.fp8_ws = torch.empty(max(1, B.moe_fp8_forward_workspace_bytes(s)), dtype=torch.uint8, device=self.device)
+        self.h_scale = to_device(np.ascontiguousarray(h_scale, dtype=np.float32), self.device)
+        g, u, d = (to_device(a, self.device) for a in (W_gate, W_up, W_down))
+        B.moe_fp8_pack_weights(s, g, u, d, self.fp8_gate_up, self.fp8_down)
+        torch.cuda.synchronize()
+        del g, u, d
+
+    def forward_fp8(self, x, events=None) -> None:
+        B.moe_fp8_fused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.fp8_gate_up,
+                                self.fp8_down, self.h_scale, self.y, self.fp8_ws, events)
+
     def route(self, logits) -> None:
         B.moe_route_topk(self.shape, logits, self.topk_idx, self.topk_w)
 

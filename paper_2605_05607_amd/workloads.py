@@ -174,3 +174,12 @@ def make_workload(cfg: MoEConfig, weights: bool = True, threads: int = 8) -> Wor
         Wu = _fill_normal((El, cfg.d, cfg.f), cfg.d ** -0.5, ss_u, cfg.dtype, threads)
         Wd = _fill_normal((El, cfg.f, cfg.d), cfg.f ** -0.5, ss_d, cfg.dtype, threads)
     return Workload(cfg, x, logits, Wg, Wu, Wd)
+
+
+def fp8_h_scale(cfg: MoEConfig) -> np.ndarray:
+    """Static scale of h for the FP8 form of the GEMMs, one per local expert: an input of the layer (a calibration
+    constant).  With x ~ N(0,1) and weights of standard deviation fan_in^-1/2, g and u are about N(0,1) and
+    |silu(g) u| stays below ~16 except for rare outliers (which saturate); the values differ between experts so that
+    a mix-up of experts shows."""
+    le = np.arange(cfg.E_loc)
+    return (16.0 / 448.0 * (1.0 + 0.25 * (le % 3))).astype(np.float32)

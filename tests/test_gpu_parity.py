@@ -446,3 +446,116 @@ def test_router_logits_deepseek_shape_sampled_tokens(oracle):
     n_safe, n = check_router(oracle, cfg.T, cfg.d, cfg.E, cfg.k, wl.BF16, seed=77, rows=rows)
     say(f"  {n_safe} of {n} sampled tokens compared index by index")
     assert n_safe > n // 2
+
+
+# ---------------------------------------------------------------- FP8 form of the expert GEMMs
+@pytest.mark.parametrize("rows,cols", [(1, 8), (37, 72), (300, 448), (64, 7168)])
+def test_fp8_quantize_rows_bit_exact(oracle, rows, cols):
+    import torch
+    say(f"fp8 quantize rows {rows} x {cols}")
+    rng = np.random.default_rng(rows + cols)
+    a = rng.standard_normal((rows, cols)) * 10.0 ** rng.uniform(-3, 2, size=(rows, 1))
+    a[:, ::5] *= 1e-3                               # small against the row maximum: subnormal codes and zeros
+    if rows > 2:
+        a[1] = 0.0                                  # a zero row: scale 1
+        a[2, :] = np.arange(cols) % 17 * 28.0       # multiples of amax / 16: exact ties between codes
+    bits = wl.f32_to_bf16_bits(a.astype(np.float32))
+    x = L.to_device(bits)
+    codes = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda")
+    scales = torch.full((rows,), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_fp8_quantize_rows(rows, cols, x, codes, scales)
+    torch.cuda.synchronize()
+    want_codes, want_scales = oracle.fp8_quantize(wl.bf16_bits_to_f32(bits), axis=-1)
+    assert np.array_equal(scales.cpu().numpy(), want_scales)
+    got = codes.cpu().numpy()
+    # -0 and +0 are the same value: compare codes up to the sign of zero
+    same = (got == want_codes) | (((got | want_codes) & 0x7F) == 0)
+    assert same.all(), f"{(~same).sum()} codes differ"
+
+
+FP8_SMALL = {
+    "deepseek_like": SMALL["deepseek_like"],
+    "qwen_like": SMALL["qwen_like"],
+    "mixtral_like": SMALL["mixtral_like"],
+    "table1_like_k16": SMALL["table1_like_k16"],
+    # reduction tails (368 = 2 x 128 + 112, 336 = 2 x 128 + 80), column tails, forced routing
+    "tails": cfg_of(T=1100, d=368, f=336, E=32, k=4, R=4, local_rank_begin=0, local_rank_end=1, router="forced",
+                    seed=31),
+    # more than one M tile of rows per expert on average: the GEMMs run as two launches
+    "two_launch": cfg_of(T=1200, d=256, f=256, E=16, k=4, R=4, local_rank_begin=1, local_rank_end=2, seed=32),
+}
+
+
+def run_forward_fp8(cfg, oracle, tokens=None):
+    import torch
+    w = wl.make_workload(cfg)
+    s_h = wl.fp8_h_scale(cfg)
+    lay = L.MoELayer(cfg)
+    lay.load_weights_fp8(w.W_gate, w.W_up, w.W_down, s_h)
+    x = L.to_device(w.x)
+    lg = L.to_device(w.logits)
+    lay.y.fill_(float("nan"))
+    lay.fp8_ws.fill_(0xFF)
+    lay.route(lg)
+    lay.build_dispatch()
+    lay.forward_fp8(x)
+    torch.cuda.synchronize()
+    got = G.tables_to_host(lay)
+    idx, tw = G.assert_tables_equal(got, oracle, w.logits, cfg)
+    y = lay.y_host()
+    ref = oracle.forward_fp8(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, s_h, cfg.E, cfg.R, cfg.local_rank_begin,
+                             cfg.local_rank_end, tokens=tokens)
+    return w, lay, x, idx, tw, y, ref
+
+
+@pytest.mark.parametrize("name", list(FP8_SMALL))
+def test_fp8_forward_matches_oracle_small(oracle, name):
+    import torch
+    cfg = FP8_SMALL[name]
+    say(f"fp8 forward small {name}: T={cfg.T} d={cfg.d} f={cfg.f} E={cfg.E} k={cfg.k} "
+        f"launches={B.moe_forward_gemm_launches(B.shape_of(cfg))}")
+    w, lay, x, idx, tw, y, ref = run_forward_fp8(cfg, oracle)
+    mx, mean = G.check_y(y, ref, cfg.dtype)
+    say(f"  max rel {mx:.2e} mean rel {mean:.2e}")
+    local = (idx // cfg.epr >= cfg.local_rank_begin) & (idx // cfg.epr < cfg.local_rank_end)
+    assert np.all(y[~local.any(axis=1)] == 0)
+    # the quantised layer is a different function from the bf16 one (the test would not notice a bf16 fallback
+    # otherwise) and still close to it
+    ref16 = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, cfg.local_rank_begin,
+                           cfg.local_rank_end)
+    rel = np.linalg.norm(y - ref16) / np.linalg.norm(ref16)
+    assert 5e-3 < rel < 0.1, rel
+    # rerun over a trashed workspace: bit-identical
+    y0 = lay.y.clone()
+    lay.fp8_ws.fill_(0x5A)
+    lay.y.fill_(7.0)
+    lay.forward_fp8(x)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.y, y0)
+
+
+def test_fp8_rejects_what_it_does_not_cover():
+    cfg = cfg_of(d=72, f=40)  # rows are not whole 16-code chunks
+    lay = L.MoELayer(cfg)
+    with pytest.raises(B.MoeError):
+        lay.load_weights_fp8(*(np.zeros(sh, np.uint16) for sh in ((cfg.E_loc, 72, 40),) * 2),
+                             np.zeros((cfg.E_loc, 40, 72), np.uint16), wl.fp8_h_scale(cfg))
+
+
+@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 64), ("qwen3", 48)])
+def test_fp8_forward_full_size_sampled_tokens(oracle, name, nsample):
+    cfg = wl.CONFIGS[name]
+    say(f"fp8 forward full size {name}")
+    rng = np.random.default_rng(6)
+    w0 = wl.make_workload(cfg, weights=False)
+    idx0, _ = oracle.route_topk(w0.logits, cfg.k)
+    slots = ((idx0 // cfg.epr >= cfg.local_rank_begin) & (idx0 // cfg.epr < cfg.local_rank_end)).sum(axis=1)
+    one, many = np.nonzero(slots == 1)[0], np.nonzero(slots > 1)[0]
+    n_one = min(one.size, nsample // 2 if many.size else nsample)
+    n_many = min(many.size, nsample - n_one)
+    tokens = np.sort(np.concatenate([rng.choice(one, size=n_one, replace=False),
+                                     rng.choice(many, size=n_many, replace=False)])).astype(np.int32)
+    w, lay, x, idx, tw, y, ref = run_forward_fp8(cfg, oracle, tokens=tokens)
+    mx, mean = G.check_y(y[tokens], ref, cfg.dtype)
+    say(f"  {name}: sampled {tokens.size} tokens, max rel {mx:.2e}, mean rel {mean:.2e}")
+    assert np.all(y[slots == 0] == 0) and np.isfinite(y).all()
