@@ -322,6 +322,35 @@ def main():
                             "hbm_gbs": gate_bytes / (t_gate * 1e-3) / 1e9,
                             "hbm_frac_of_peak": gate_bytes / (t_gate * 1e-3) / 1e9 / HBM_PEAK_GBS}
     del W_r, lg2, ws_r
+    # The same step with the FP8 (E4M3) form of the expert GEMMs (weights quantised once, untimed; x quantised inside
+    # the step): half the weight bytes, the same number of matrix-core instructions.  Not `value`: the metric is
+    # the bf16 layer.
+    if cfg.dtype == wl.BF16 and cfg.d % 16 == 0 and cfg.f % 16 == 0:
+        lay.load_weights_fp8(w.W_gate, w.W_up, w.W_down, wl.fp8_h_scale(cfg))
+
+        def step_fp8(events=None):
+            lay.route(lg)
+            lay.build_dispatch()
+            lay.forward_fp8(x, events)
+
+        t_fp8 = timed(step_fp8, 10)
+        ev8 = [torch.cuda.Event(enable_timing=True) for _ in range(5)]
+        for e in ev8:
+            e.record()
+        step_fp8([e.cuda_event for e in ev8])
+        torch.cuda.synchronize()
+        g8_ms = ev8[1].elapsed_time(ev8[3])
+        fp8_bytes = (g1["bytes"] + g2["bytes"]) - ne * 3 * cfg.d * cfg.f  # weights, x and h are one byte each ...
+        fp8_bytes -= U_tok * cfg.d + 2 * P * cfg.f                        # ... instead of two
+        out["fp8_gemms"] = {"entry": "moe_fp8_fused_forward", "ms_per_step": t_fp8,
+                            "tokens_per_s": cfg.T / (t_fp8 * 1e-3),
+                            "quantise_x_and_tile_table_ms": ev8[0].elapsed_time(ev8[1]), "gemms_ms": g8_ms,
+                            "combine_ms": ev8[3].elapsed_time(ev8[4]),
+                            "gemm_tflops": (g1["flops"] + g2["flops"]) / (g8_ms * 1e-3) / 1e12,
+                            "gemm_bytes": fp8_bytes, "hbm_gbs": fp8_bytes / (g8_ms * 1e-3) / 1e9,
+                            "hbm_frac_of_peak": fp8_bytes / (g8_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "speedup_vs_bf16_step": ms_per_step / t_fp8}
+        del lay.fp8_gate_up, lay.fp8_down, lay.fp8_ws
     # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

@@ -25,19 +25,18 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-// FP8 operands (E4M3): a 16-byte fragment holds 16 reduction indices per lane and feeds two instructions of 8
-// indices per lane half each; which indices share an instruction does not matter as long as A and B agree, and
-// both use "low 8 bytes, then high 8 bytes" of the same 16-byte chunk of the reduction range.
-typedef long i64x2 __attribute__((ext_vector_type(2)));
-template <bool FP8>
-__device__ __forceinline__ f32x16 mfma_frag(bf16x8 a, bf16x8 b, f32x16 c) {
-  if constexpr (FP8) {
-    const i64x2 a2 = __builtin_bit_cast(i64x2, a), b2 = __builtin_bit_cast(i64x2, b);
-    c = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[0], b2[0], c, 0, 0, 0);
-    return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a2[1], b2[1], c, 0, 0, 0);
-  } else {
-    return mfma_bf16(a, b, c);
-  }
+// FP8 operands (E4M3): a 16-byte fragment holds 16 reduction indices per lane; two fragments (32 bytes per lane)
+// feed one 32x32x64 instruction.  Which reduction indices share an instruction, and where in the operand they sit,
+// does not matter as long as A and B agree: both put the same two 16-byte chunks of the reduction range side by side.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ f32x16 mfma_fp8_pair(bf16x8 a_lo, bf16x8 a_hi, bf16x8 b_lo, bf16x8 b_hi, f32x16 c) {
+  const i32x8 a = __builtin_shufflevector(__builtin_bit_cast(i32x4, a_lo), __builtin_bit_cast(i32x4, a_hi), 0, 1, 2, 3,
+                                          4, 5, 6, 7);
+  const i32x8 b = __builtin_shufflevector(__builtin_bit_cast(i32x4, b_lo), __builtin_bit_cast(i32x4, b_hi), 0, 1, 2, 3,
+                                          4, 5, 6, 7);
+  // both operands E4M3 (format selectors 0), no block scales (all scale operands 0)
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
 }
 
 constexpr int kGemmThreads = 512;
@@ -156,8 +155,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 #define MOE355_MFMAS(FA, FB)                                                                           \
   do {                                                                                                 \
     _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) {                                                \
-      acc[mi][0] = mfma_frag<FP8>(FA[mi], FB[0], acc[mi][0]);                                          \
-      acc[mi][1] = mfma_frag<FP8>(FA[mi], FB[1], acc[mi][1]);                                          \
+      acc[mi][0] = mfma_bf16(FA[mi], FB[0], acc[mi][0]);                                               \
+      acc[mi][1] = mfma_bf16(FA[mi], FB[1], acc[mi][1]);                                               \
     }                                                                                                  \
   } while (0)
 
@@ -174,7 +173,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   do {                                                                                                 \
     if (NB > 0) {                                                                                      \
       __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);                                          \
-      __builtin_amdgcn_sched_group_barrier(0x008, (FP8 ? 4 : 2) * NB, 0);                              \
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                          \
     }                                                                                                  \
     if ((NW) > 0) {                                                                                    \
       __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                            \
@@ -207,6 +206,36 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     MOE355_ORDER(0);                                                                                   \
   } while (0)
 
+  // FP8 k-step: the operands of substeps 0 and 1 (then 2 and 3) sit in fa0 / fa1 and go into one instruction per
+  // accumulator; the fragments of the next pair are read once those instructions have been issued, the staging
+  // traffic is spread between the two groups as above, and the barrier again sits in front of the last group.
+#define MOE355_MFMAS8()                                                                                \
+  do {                                                                                                 \
+    _Pragma("unroll") for (int mi = 0; mi < NB; ++mi) {                                                \
+      acc[mi][0] = mfma_fp8_pair(fa0[mi], fa1[mi], fb0[0], fb1[0], acc[mi][0]);                        \
+      acc[mi][1] = mfma_fp8_pair(fa0[mi], fa1[mi], fb0[1], fb1[1], acc[mi][1]);                        \
+    }                                                                                                  \
+  } while (0)
+#define MOE355_KSTEP8(S, KT_, KPRE)                                                                     \
+  do {                                                                                                 \
+    const unsigned char *sCur = smem + ((KT_) & 1) * kStageBytes;                                      \
+    const int nxt = ((KT_) & 1) ^ 1;                                                                   \
+    const int kp_ = min((KPRE), kt_last);                                                              \
+    MOE355_MFMAS8();                                                                                   \
+    MOE355_STORE_P0(S, nxt);                                                                           \
+    MOE355_LOAD_P0(S, kp_);                                                                            \
+    MOE355_READ_FRAGS(fa0, fb0, sCur, 2);                                                              \
+    MOE355_READ_FRAGS(fa1, fb1, sCur, 3);                                                              \
+    MOE355_STORE_P1(S, nxt);                                                                           \
+    MOE355_LOAD_P1(S, kp_);                                                                            \
+    MOE355_STORE_P2(S, nxt);                                                                           \
+    MOE355_LOAD_P2(S, kp_);                                                                            \
+    __syncthreads();                                                                                   \
+    MOE355_MFMAS8();                                                                                   \
+    MOE355_READ_FRAGS(fa0, fb0, smem + nxt * kStageBytes, 0);                                          \
+    MOE355_READ_FRAGS(fa1, fb1, smem + nxt * kStageBytes, 1);                                          \
+  } while (0)
+
   const int KT = g.n_ktiles;
   const int kt_last = KT - 1;
   MOE355_LOAD_P0(x, 0); MOE355_LOAD_P1(x, 0); MOE355_LOAD_P2(x, 0);
@@ -221,8 +250,16 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   }
   __syncthreads();
   MOE355_READ_FRAGS(fa0, fb0, smem, 0);
+  if (FP8) MOE355_READ_FRAGS(fa1, fb1, smem, 1);
 
-  if (DEPTH == 1) {
+  if (FP8 && DEPTH == 1) {
+    for (int kt = 0; kt < KT; ++kt) MOE355_KSTEP8(x, kt, kt + 2);
+  } else if (FP8) {
+    for (int kt = 0; kt < KT; kt += 2) {
+      MOE355_KSTEP8(x, kt, kt + 3);
+      if (kt + 1 < KT) MOE355_KSTEP8(y, kt + 1, kt + 4);
+    }
+  } else if (DEPTH == 1) {
     for (int kt = 0; kt < KT; ++kt) MOE355_KSTEP(x, kt, kt + 2);
   } else {
     // set x carries the odd slabs, set y the even ones
@@ -232,6 +269,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     }
   }
 #undef MOE355_KSTEP
+#undef MOE355_KSTEP8
+#undef MOE355_MFMAS8
 #undef MOE355_ORDER
 #undef MOE355_READ_FRAGS
 #undef MOE355_MFMAS
