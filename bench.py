@@ -351,6 +351,19 @@ def main():
                             "hbm_frac_of_peak": fp8_bytes / (g8_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                             "speedup_vs_bf16_step": ms_per_step / t_fp8}
         del lay.fp8_gate_up, lay.fp8_down, lay.fp8_ws
+        # context: the vendor library's dense FP8 product of GEMM-1's size on this machine (not part of the path)
+        try:
+            Mref = max(256, -(-P // 256) * 256)
+            a8 = torch.randn((Mref, cfg.d), device="cuda").to(torch.float8_e4m3fn)
+            b8 = torch.randn((2 * cfg.f, cfg.d), device="cuda").to(torch.float8_e4m3fn).t()  # column-major operand
+            one = torch.ones((), dtype=torch.float32, device="cuda")
+            t_ref8 = timed(lambda: torch._scaled_mm(a8, b8, scale_a=one, scale_b=one, out_dtype=torch.bfloat16), 10)
+            out["fp8_gemms"]["dense_fp8_gemm_reference"] = {
+                "what": "torch._scaled_mm (hipBLASLt) e4m3, one dense product", "M": Mref, "N": 2 * cfg.f, "K": cfg.d,
+                "ms": t_ref8, "tflops": 2.0 * Mref * 2 * cfg.f * cfg.d / (t_ref8 * 1e-3) / 1e12}
+            del a8, b8
+        except Exception as exc:  # the reference figure is optional
+            out["fp8_gemms"]["dense_fp8_gemm_reference"] = {"error": str(exc)[:200]}
     # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
