@@ -148,3 +148,34 @@ def test_router_logits_arguments():
     for cfg in wl.CONFIGS.values():
         sh = B.shape_of(cfg)
         assert B.moe_router_workspace_bytes(sh) <= 8 * cfg.T * cfg.E * 4 + 512
+
+
+def test_fp8_entry_points_arguments():
+    lib = B.lib()
+    s = good_shape()
+    fake = 4096
+    tb = B.moe_dispatch(*([fake] * 9))
+    need = B.moe_fp8_forward_workspace_bytes(s)
+    assert need > B.moe_forward_workspace_bytes(s) + s.T * s.d  # room for x as codes and its scales
+    for which in (0, 1):
+        raw = (s.local_rank_end - s.local_rank_begin) * (s.E // s.R) * s.d * s.f * (2 if which == 0 else 1)
+        assert raw <= B.moe_fp8_packed_weight_bytes(s, which) < 2.2 * raw + (1 << 20)  # one byte per weight + padding
+    assert B.moe_fp8_packed_weight_bytes(s, 2) == 0
+    args = (C.byref(s), fake, fake, fake, C.byref(tb), fake, fake)
+    assert lib.moe_fp8_fused_forward(*args, None, fake, fake, need, None, None) == B.MOE_ERR_INVALID_ARG  # no h_scale
+    assert lib.moe_fp8_fused_forward(*args, fake, fake, fake, need - 1, None, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_fp8_fused_forward(*args, fake, None, fake, need, None, None) == B.MOE_ERR_INVALID_ARG
+    odd = good_shape(d=72)  # rows are not whole 16-code chunks
+    big = 1 << 30
+    assert lib.moe_fp8_fused_forward(C.byref(odd), fake, fake, fake, C.byref(tb), fake, fake, fake, fake, fake, big,
+                                     None, None) == B.MOE_ERR_UNSUPPORTED
+    assert lib.moe_fp8_pack_weights(C.byref(odd), fake, fake, fake, fake, fake, None) == B.MOE_ERR_UNSUPPORTED
+    f32 = good_shape(dtype=B.MOE_F32)
+    assert lib.moe_fp8_pack_weights(C.byref(f32), fake, fake, fake, fake, fake, None) == B.MOE_ERR_UNSUPPORTED
+    assert lib.moe_fp8_pack_weights(C.byref(s), fake, None, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_fp8_quantize_rows(4, 12, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG   # cols % 8
+    assert lib.moe_fp8_quantize_rows(4, 16, fake + 4, fake, fake, None) == B.MOE_ERR_INVALID_ARG  # misaligned
+    assert lib.moe_fp8_quantize_rows(-1, 16, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_fp8_quantize_rows(0, 16, fake, fake, fake, None) == B.MOE_OK
+    assert lib.moe_fp8_fused_forward(C.byref(good_shape(T=0)), fake, fake, fake, C.byref(tb), fake, fake, fake, fake,
+                                     fake, big, None, None) == B.MOE_OK
