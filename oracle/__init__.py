@@ -90,6 +90,26 @@ def route_topk(logits: np.ndarray, k: int):
     return idx, w
 
 
+GATE_SOFTMAX = 0
+GATE_SIGMOID = 1
+
+
+def route_topk_gate(logits: np.ndarray, k: int, gate: int, bias: Optional[np.ndarray] = None):
+    """Routing with a softmax or sigmoid gate and an optional selection-only bias.  Returns (idx, w, sel): sel is
+    the [T, E] float32 array of selection values."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    T, E = logits.shape
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        assert bias.shape == (E,)
+    idx = np.empty((T, k), dtype=np.int32)
+    w = np.empty((T, k), dtype=np.float32)
+    sel = np.empty((T, E), dtype=np.float32)
+    _check(_lib().moe_oracle_route_topk_gate(T, E, k, _p(logits), _p(bias), int(gate), _p(idx), _p(w), _p(sel)),
+           "route_topk_gate")
+    return idx, w, sel
+
+
 def build_tables(topk_idx: np.ndarray, E: int):
     topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
     T, k = topk_idx.shape

@@ -123,6 +123,63 @@ int moe_oracle_route_topk(int T, int E, int k, const float *logits, int32_t *top
 }
 
 /*
+ * Routing with the gate variants of recent MoE models (the paper evaluates DeepSeek-V3, whose gate is of this kind,
+ * and leaves the gate function open, Sec. II-A):
+ *   gate 0 (softmax): selection value v_e = l_e + b_e; weights as in moe_oracle_route_topk (softmax over the
+ *                     logits, renormalised over the picks);
+ *   gate 1 (sigmoid): s_e = 1 / (1 + exp(-l_e)); selection value v_e = s_e + b_e; weights w_j = s_j / sum of the
+ *                     picked s.
+ * b (may be NULL = 0) is a per-expert bias that steers the selection only and never enters the weights.
+ * Selection values are formed in fp32 (they decide an index, and fp32 is what the GPU kernel uses); the k largest
+ * are taken, lowest index on ties, slot order = pick order.  sel_out (may be NULL) receives the [T, E] selection
+ * values so that a caller can tell decisive picks from near-ties.
+ */
+int moe_oracle_route_topk_gate(int T, int E, int k, const float *logits, const float *bias, int gate,
+                               int32_t *topk_idx, float *topk_w, float *sel_out) {
+  if (T < 0 || E < 1 || k < 1 || k > E || !logits || !topk_idx || !topk_w || (gate != 0 && gate != 1))
+    return ORACLE_BAD_ARG;
+  unsigned char *taken = (unsigned char *)malloc((size_t)E);
+  float *sel = (float *)malloc(sizeof(float) * (size_t)E);
+  if (!taken || !sel) { free(taken); free(sel); return ORACLE_NOMEM; }
+  for (int t = 0; t < T; ++t) {
+    const float *row = logits + (size_t)t * E;
+    for (int e = 0; e < E; ++e) {
+      const float b = bias ? bias[e] : 0.0f;
+      if (!isfinite(row[e]) || !isfinite(b)) { free(taken); free(sel); return ORACLE_BAD_ARG; }
+      const float base = gate == 0 ? row[e] : 1.0f / (1.0f + expf(-row[e]));
+      sel[e] = base + b;
+      if (sel_out) sel_out[(size_t)t * E + e] = sel[e];
+      taken[e] = 0;
+    }
+    for (int j = 0; j < k; ++j) {
+      int best = -1;
+      for (int e = 0; e < E; ++e) {
+        if (taken[e]) continue;
+        if (best < 0 || sel[e] > sel[best]) best = e;
+      }
+      taken[best] = 1;
+      topk_idx[(size_t)t * k + j] = best;
+    }
+    double m = -INFINITY, sum = 0.0;
+    for (int j = 0; j < k; ++j) {
+      const double l = (double)row[topk_idx[(size_t)t * k + j]];
+      if (l > m) m = l;
+    }
+    for (int j = 0; j < k; ++j) {
+      const double l = (double)row[topk_idx[(size_t)t * k + j]];
+      sum += gate == 0 ? exp(l - m) : 1.0 / (1.0 + exp(-l));
+    }
+    for (int j = 0; j < k; ++j) {
+      const double l = (double)row[topk_idx[(size_t)t * k + j]];
+      topk_w[(size_t)t * k + j] = (float)((gate == 0 ? exp(l - m) : 1.0 / (1.0 + exp(-l))) / sum);
+    }
+  }
+  free(taken);
+  free(sel);
+  return ORACLE_OK;
+}
+
+/*
  * Dispatch tables (Sec. III-D AL Table; Sec. III-E nactive[expert]).
  * counts[e]  = number of (token, slot) pairs routed to e; offsets = exclusive prefix sum (E+1 entries).
  * Pairs are visited in ascending pair id p = t*k + j; the pair takes the next free row of its expert:

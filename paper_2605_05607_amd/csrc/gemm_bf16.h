@@ -1,4 +1,5 @@
-// Grouped bf16 GEMMs on the matrix cores: tile, work item, the per-item kernels and the resident kernel.
+// Grouped GEMMs on the matrix cores: tile, work item, the per-item kernels and the resident kernel, for bf16
+// operands and (template flag FP8) for E4M3 operands.
 #pragma once
 #include <type_traits>
 

@@ -434,3 +434,69 @@ def test_fp8_forward_vs_per_slot_bruteforce(oracle):
                 want[t] += float(tw[t, j]) * brute.ffn_dense_fp8(w.x[t:t + 1], w.W_gate[le], w.W_up[le], w.W_down[le],
                                                                  s_h[le])[0]
     np.testing.assert_allclose(y, want, rtol=1e-9, atol=1e-12)
+
+
+# ---------------------------------------------------------------- gate variants (sigmoid gate, selection-only bias)
+def _grid_logits(rng, T, E):
+    """Logits on a grid of 1/4 and biases on a grid of 1/64: selection values are either exactly equal or far
+    apart (no rounding can reorder them), so the picks have one right answer."""
+    return (rng.integers(-12, 13, size=(T, E)) / 4.0).astype(np.float32)
+
+
+@pytest.mark.parametrize("gate", [0, 1])
+def test_gate_variants_vs_full_sort(oracle, gate):
+    rng = np.random.default_rng(40 + gate)
+    T, E, k = 60, 24, 5
+    logits = _grid_logits(rng, T, E)
+    bias = (rng.integers(-8, 9, size=E) / 64.0).astype(np.float32)
+    idx, w, sel = oracle.route_topk_gate(logits, k, gate, bias)
+    l64 = logits.astype(np.float64)
+    s64 = 1.0 / (1.0 + np.exp(-l64))
+    base = l64 if gate == 0 else s64
+    want_sel = base + bias[None, :].astype(np.float64)
+    np.testing.assert_allclose(sel, want_sel, rtol=3e-7, atol=1e-7)
+    # stable sort of the fp32 selection values = pick order with ties to the lower index
+    order = np.argsort(-sel.astype(np.float64), axis=1, kind="stable")[:, :k]
+    np.testing.assert_array_equal(idx, order)
+    # on this grid, fp32 rounding cannot have reordered anything: same picks from the exact values
+    gaps = np.abs(want_sel[:, :, None] - want_sel[:, None, :])
+    assert np.all((gaps == 0) | (gaps > 1e-4))
+    np.testing.assert_array_equal(idx, np.argsort(-np.round(want_sel, 9), axis=1, kind="stable")[:, :k])
+    # weights: from the logits alone (the bias steers the selection only)
+    picked = np.take_along_axis(l64, idx.astype(np.int64), axis=1)
+    if gate == 0:
+        p = np.exp(picked - picked.max(axis=1, keepdims=True))
+    else:
+        p = 1.0 / (1.0 + np.exp(-picked))
+    np.testing.assert_allclose(w, p / p.sum(axis=1, keepdims=True), rtol=2e-7)
+    np.testing.assert_allclose(w.sum(axis=1), 1.0, atol=1e-6)
+
+
+def test_gate_variants_special_cases(oracle):
+    rng = np.random.default_rng(43)
+    logits = rng.standard_normal((50, 16)).astype(np.float32)
+    idx0, w0 = oracle.route_topk(logits, 4)
+    # softmax gate without a bias is the plain routing
+    idx, w, _ = oracle.route_topk_gate(logits, 4, 0, None)
+    np.testing.assert_array_equal(idx, idx0)
+    np.testing.assert_allclose(w, w0, rtol=1e-6)
+    # the sigmoid is monotone: same picks without a bias (these logits are far from its saturation), other weights
+    idx, w, _ = oracle.route_topk_gate(logits, 4, 1, None)
+    np.testing.assert_array_equal(idx, idx0)
+    assert np.abs(w - w0).max() > 1e-3
+    # a large bias forces an expert into the first slot and leaves its weight a function of its logit only
+    bias = np.zeros(16, dtype=np.float32)
+    bias[11] = 100.0
+    for gate in (0, 1):
+        idx, w, _ = oracle.route_topk_gate(logits, 4, gate, bias)
+        assert np.all(idx[:, 0] == 11)
+        l = np.take_along_axis(logits.astype(np.float64), idx.astype(np.int64), axis=1)
+        p = np.exp(l - l.max(axis=1, keepdims=True)) if gate == 0 else 1.0 / (1.0 + np.exp(-l))
+        np.testing.assert_allclose(w, p / p.sum(axis=1, keepdims=True), rtol=2e-7)
+    # k = E: every expert, in descending order of the selection value; sigmoid saturation makes exact ties
+    sat = np.array([[30.0, 40.0, -1.0, 35.0]], dtype=np.float32)
+    idx, w, sel = oracle.route_topk_gate(sat, 4, 1, None)
+    assert sel[0, 0] == sel[0, 1] == sel[0, 3] == 1.0
+    np.testing.assert_array_equal(idx[0], [0, 1, 3, 2])
+    with pytest.raises(ValueError):
+        oracle.route_topk_gate(np.array([[0.0, np.inf]], dtype=np.float32), 1, 1, None)
