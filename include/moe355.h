@@ -110,6 +110,19 @@ MOE355_API int moe_route_topk(const moe_shape *shape, const float *logits, int32
                               void *stream);
 
 /*
+ * Routing with the gate variants of DeepSeek-V3-style models (the paper evaluates that model and leaves the gate
+ * function open, Sec. II-A).  gate = MOE_GATE_SOFTMAX: selection value logit + bias, weights as moe_route_topk;
+ * gate = MOE_GATE_SIGMOID: s = 1 / (1 + exp(-logit)), selection value s + bias, weights = picked s divided by
+ * their sum.  bias [E] fp32 (device; NULL = none) steers the selection only and never enters the weights.
+ * Selection values are formed in fp32; k largest, lowest index on ties, slot order = pick order.  Other
+ * arguments, outputs and errors as moe_route_topk; an unknown gate gives MOE_ERR_INVALID_ARG.
+ */
+#define MOE_GATE_SOFTMAX 0
+#define MOE_GATE_SIGMOID 1
+MOE355_API int moe_route_topk_gate(const moe_shape *shape, const float *logits, const float *bias, int gate,
+                                   int32_t *topk_idx, float *topk_w, void *stream);
+
+/*
  * Dispatch tables from the routing (Sec. III-D AL Table / Sec. III-E nactive / Sec. II-B redundancy).
  * Fills every array of `out` for all E experts and all R ranks (local or not).  The result is unique:
  * integer-exact and independent of scheduling.  workspace >= moe_dispatch_workspace_bytes(shape).

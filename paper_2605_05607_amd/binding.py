@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
             fn = getattr(L, name)
             fn.restype = i32
             fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
+        L.moe_route_topk_gate.restype = i32
+        L.moe_route_topk_gate.argtypes = [sp, vp, vp, i32, vp, vp, vp]
         L.moe_fp8_packed_weight_bytes.restype = sz
         L.moe_fp8_packed_weight_bytes.argtypes = [sp, i32]
         L.moe_fp8_forward_workspace_bytes.restype = sz
@@ -249,6 +251,15 @@ def moe_unfused_forward(shape, x, topk_idx, topk_w, tables, packed_gate_up, pack
                         workspace_bytes=None, stream=None) -> None:
     _forward("moe_unfused_forward", shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
              workspace_bytes, stream)
+
+
+MOE_GATE_SOFTMAX = 0
+MOE_GATE_SIGMOID = 1
+
+
+def moe_route_topk_gate(shape, logits, bias, gate, topk_idx, topk_w, stream=None) -> None:
+    _check(lib().moe_route_topk_gate(C.byref(shape), _ptr(logits), _ptr(bias), int(gate), _ptr(topk_idx),
+                                     _ptr(topk_w), _stream(stream)), "moe_route_topk_gate")
 
 
 def moe_fp8_packed_weight_bytes(shape: moe_shape, which: int) -> int:

@@ -157,6 +157,68 @@ __global__ __launch_bounds__(kRouteWaves * kWave) void route_topk_kernel(const f
   }
 }
 
+// Routing with a softmax (gate 0) or sigmoid (gate 1) gate and an optional per-expert bias that steers the
+// selection only (the gate of DeepSeek-V3-style models; the paper leaves the gate open, Sec. II-A).  Selection
+// value: logit + bias, or 1 / (1 + exp(-logit)) + bias, in fp32; k largest, lowest index on ties; weights from the
+// logits alone: softmax over the picks, or the picked sigmoids divided by their sum.  Same structure as
+// route_topk_kernel: one wave per token, keys in the LDS.
+__global__ __launch_bounds__(kRouteWaves * kWave) void route_topk_gate_kernel(const float *__restrict__ logits,
+                                                                              const float *__restrict__ bias,
+                                                                              int gate,
+                                                                              int32_t *__restrict__ topk_idx,
+                                                                              float *__restrict__ topk_w, int T,
+                                                                              int E, int k) {
+  extern __shared__ uint32_t smem[];  // per wave: E keys, then 32 floats for the picked logits
+  const int wave = threadIdx.x >> 6;
+  const int lane = lane_id();
+  const int t = blockIdx.x * (blockDim.x >> 6) + wave;
+  if (t >= T) return;  // whole wave leaves together; no block-wide barrier is used below
+  uint32_t *keys = smem + (size_t)wave * (E + kMaxTopK);
+  float *picked = reinterpret_cast<float *>(keys + E);
+  const float *row = logits + (size_t)t * E;
+  for (int e = lane; e < E; e += kWave) {
+    const float l = row[e];
+    const float base = gate == 0 ? l : 1.0f / (1.0f + expf(-l));
+    keys[e] = ordered_key(base + (bias ? bias[e] : 0.0f));
+  }
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  for (int j = 0; j < k; ++j) {
+    uint32_t bk = 0;
+    uint32_t bi = 0xFFFFFFFFu;
+    for (int e = lane; e < E; e += kWave) {
+      const uint32_t key = keys[e];
+      if (key > bk) {
+        bk = key;
+        bi = (uint32_t)e;
+      }
+    }
+    unsigned long long best = ((unsigned long long)bk << 32) | (unsigned long long)(0xFFFFFFFFu - bi);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const unsigned long long other = __shfl_xor(best, off, 64);
+      best = other > best ? other : best;
+    }
+    const int e_best = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+    if (lane == 0) {
+      const int e_ok = e_best >= 0 && e_best < E ? e_best : 0;  // guards against non-finite input only
+      topk_idx[(size_t)t * k + j] = e_ok;
+      picked[j] = row[e_ok];
+      keys[e_ok] = 0u;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (lane < k) {
+    float m = picked[0];
+    for (int i = 1; i < k; ++i) m = fmaxf(m, picked[i]);
+    float sum = 0.f;
+    for (int i = 0; i < k; ++i) sum += gate == 0 ? expf(picked[i] - m) : 1.0f / (1.0f + expf(-picked[i]));
+    const float mine = gate == 0 ? expf(picked[lane] - m) : 1.0f / (1.0f + expf(-picked[lane]));
+    topk_w[(size_t)t * k + lane] = mine / sum;
+  }
+}
+
 }  // namespace moe355
 
 using namespace moe355;
@@ -188,5 +250,22 @@ extern "C" int moe_route_topk(const moe_shape *shape, const float *logits, int32
   const size_t smem = waves * per_wave;
   hipLaunchKernelGGL(route_topk_kernel, dim3(blocks), dim3(waves * kWave), smem, (hipStream_t)stream, logits,
                      topk_idx, topk_w, shape->T, shape->E, shape->k);
+  return launch_status();
+}
+
+extern "C" int moe_route_topk_gate(const moe_shape *shape, const float *logits, const float *bias, int gate,
+                                   int32_t *topk_idx, float *topk_w, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!logits || !topk_idx || !topk_w || (gate != MOE_GATE_SOFTMAX && gate != MOE_GATE_SIGMOID))
+    return MOE_ERR_INVALID_ARG;
+  if (shape->T == 0) return MOE_OK;
+  begin_launches();
+  const size_t per_wave = (size_t)(shape->E + kMaxTopK) * sizeof(uint32_t);
+  int waves = kRouteWaves;
+  while (waves > 1 && waves * per_wave > 48 * 1024) waves >>= 1;
+  hipLaunchKernelGGL(route_topk_gate_kernel, dim3(ceil_div(shape->T, waves)), dim3(waves * kWave), waves * per_wave,
+                     (hipStream_t)stream, logits, bias, gate, topk_idx, topk_w, shape->T, shape->E, shape->k);
   return launch_status();
 }

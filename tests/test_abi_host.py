@@ -179,3 +179,13 @@ def test_fp8_entry_points_arguments():
     assert lib.moe_fp8_quantize_rows(0, 16, fake, fake, fake, None) == B.MOE_OK
     assert lib.moe_fp8_fused_forward(C.byref(good_shape(T=0)), fake, fake, fake, C.byref(tb), fake, fake, fake, fake,
                                      fake, big, None, None) == B.MOE_OK
+
+
+def test_route_gate_arguments():
+    lib = B.lib()
+    s = good_shape()
+    fake = 4096
+    assert lib.moe_route_topk_gate(C.byref(s), fake, None, 2, fake, fake, None) == B.MOE_ERR_INVALID_ARG  # gate
+    assert lib.moe_route_topk_gate(C.byref(s), None, None, 1, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_topk_gate(C.byref(good_shape(k=9)), fake, None, 1, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_topk_gate(C.byref(good_shape(T=0)), fake, None, 1, fake, fake, None) == B.MOE_OK

@@ -559,3 +559,45 @@ def test_fp8_forward_full_size_sampled_tokens(oracle, name, nsample):
     mx, mean = G.check_y(y[tokens], ref, cfg.dtype)
     say(f"  {name}: sampled {tokens.size} tokens, max rel {mx:.2e}, mean rel {mean:.2e}")
     assert np.all(y[slots == 0] == 0) and np.isfinite(y).all()
+
+
+# ---------------------------------------------------------------- gate variants: sigmoid gate, selection-only bias
+@pytest.mark.parametrize("T,E,k,gate,with_bias", [(257, 256, 8, 1, True), (1000, 128, 4, 1, False), (300, 64, 6, 0, True),
+                                                  (90, 4096, 5, 1, True), (64, 8, 8, 1, True), (1, 4, 2, 0, True),
+                                                  (4096, 256, 8, 1, True)])
+def test_route_gate_variants(oracle, T, E, k, gate, with_bias):
+    import torch
+    say(f"route gate={gate} bias={with_bias} T={T} E={E} k={k}")
+    rng = np.random.default_rng(T + E + gate)
+    logits = rng.standard_normal((T, E)).astype(np.float32) * 2
+    logits[::5] = np.round(logits[::5] * 2) / 2       # exact ties
+    logits[3::11] += 30.0                             # the sigmoid saturates: many equal selection values
+    bias = (rng.standard_normal(E) * 0.1).astype(np.float32) if with_bias else None
+    if with_bias:
+        bias[::3] = 0.125                             # equal biases keep the exact ties
+    cfg = cfg_of(T=T, E=E, k=k, R=1, d=8, f=8, local_rank_begin=0, local_rank_end=1)
+    s = B.shape_of(cfg)
+    idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.full((T, k), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_route_topk_gate(s, L.to_device(logits), None if bias is None else L.to_device(bias), gate, idx, w)
+    torch.cuda.synchronize()
+    idx, w = idx.cpu().numpy(), w.cpu().numpy()
+    ridx, rw, sel = oracle.route_topk_gate(logits, k, gate, bias)
+    # Where the gap between the k-th and the (k+1)-th selection value and between consecutive picks exceeds what
+    # two exp implementations can differ by (a few ulp of a value <= 1 plus the bias), the picks are unique: exact
+    # comparison.  Elsewhere: the picks must be k distinct experts whose values are within that slack of the oracle's.
+    srt = -np.sort(-sel.astype(np.float64), axis=1)
+    slack = 4e-7 * (1.0 + np.abs(srt[:, :1]))
+    gaps = srt[:, :-1] - srt[:, 1:] if E > 1 else np.ones((T, 1))
+    lim = min(k, E - 1)
+    decisive = (gaps[:, :lim] > slack) | (gaps[:, :lim] == 0)
+    # an exact tie (gap 0) is only decisive if both implementations see it as one: true when gate == 0 (no exp)
+    safe = (gaps[:, :lim] > slack).all(axis=1) if gate == 1 else decisive.all(axis=1)
+    assert safe.sum() >= T // 4 or T < 8
+    assert np.array_equal(idx[safe], ridx[safe])
+    assert np.abs(w[safe] - rw[safe]).max() <= 1e-6 if safe.any() else True
+    picked = np.take_along_axis(sel.astype(np.float64), idx.astype(np.int64), axis=1)
+    assert np.all(picked >= srt[:, k - 1:k] - slack)
+    assert np.all(np.diff(picked, axis=1) <= slack)  # slot order = descending selection value
+    assert all(len(set(r)) == k for r in idx.tolist())
+    assert np.allclose(w.sum(axis=1), 1.0, atol=1e-5) and np.isfinite(w).all()
