@@ -90,22 +90,27 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // tile is zero there, so it contributes nothing and no select has to wait on the load
 #define MOE355_A_OFF(KT) ((KT) * KS + a_chunk * EPC < g.K ? (KT) * KS : -a_chunk * EPC)
   // NA = row loads per thread that reach valid rows (1: rows < 64, 2: rows < 128, 4: all); the others are skipped
+  // Weight tiles of a streaming item (at most 64 rows) are read once by one workgroup: loaded with the
+  // non-temporal hint so that they do not push the operands the full tiles share out of the L2.
+#define MOE355_B_LOAD(PTR)                                                                          \
+  (NA == 1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(PTR))                        \
+           : *reinterpret_cast<const u32x4 *>(PTR))
 #define MOE355_LOAD_P0(S, KT)                                                                       \
   do {                                                                                              \
     ra0##S = *reinterpret_cast<const u32x4 *>(a_base + a_off0 + MOE355_A_OFF(KT));                  \
     if (NA > 1) ra1##S = *reinterpret_cast<const u32x4 *>(a_base + a_off1 + MOE355_A_OFF(KT));      \
-    rb0##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes);                   \
+    rb0##S = MOE355_B_LOAD(b_src + (size_t)(KT) * kTileBytes);                                      \
   } while (0)
 #define MOE355_LOAD_P1(S, KT)                                                                       \
   do {                                                                                              \
     if (NA > 2) ra2##S = *reinterpret_cast<const u32x4 *>(a_base + a_off2 + MOE355_A_OFF(KT));      \
     if (NA > 2) ra3##S = *reinterpret_cast<const u32x4 *>(a_base + a_off3 + MOE355_A_OFF(KT));      \
-    rb1##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 8192);            \
+    rb1##S = MOE355_B_LOAD(b_src + (size_t)(KT) * kTileBytes + 8192);                               \
   } while (0)
 #define MOE355_LOAD_P2(S, KT)                                                                       \
   do {                                                                                              \
-    rb2##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 16384);           \
-    rb3##S = *reinterpret_cast<const u32x4 *>(b_src + (size_t)(KT) * kTileBytes + 24576);           \
+    rb2##S = MOE355_B_LOAD(b_src + (size_t)(KT) * kTileBytes + 16384);                              \
+    rb3##S = MOE355_B_LOAD(b_src + (size_t)(KT) * kTileBytes + 24576);                              \
   } while (0)
 #define MOE355_STORE_P0(S, BUF)                                                                     \
   do {                                                                                              \
@@ -276,6 +281,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 #undef MOE355_READ_FRAGS
 #undef MOE355_MFMAS
 #undef MOE355_LOAD_P0
+#undef MOE355_B_LOAD
 #undef MOE355_LOAD_P1
 #undef MOE355_LOAD_P2
 #undef MOE355_STORE_P0
