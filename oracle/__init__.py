@@ -268,3 +268,64 @@ def fp8_quantize_layer(x, W_gate, W_up, W_down):
     uq, su = fp8_quantize(_as_f32(np.ascontiguousarray(W_up)), axis=-2)
     dq, sd = fp8_quantize(_as_f32(np.ascontiguousarray(W_down)), axis=-2)
     return xq, sx, gq, sg, uq, su, dq, sd
+
+
+def _elt_of(a: np.ndarray) -> int:
+    if a.dtype == np.uint16:
+        return ELT_BF16
+    if a.dtype == np.float32:
+        return ELT_F32
+    raise TypeError("float32 or uint16 (bf16 bits)")
+
+
+def backward_tokens(x, dy, topk_idx, topk_w, W_gate, W_up, W_down, E: int, R: int, local_rank_begin: int,
+                    local_rank_end: int, tokens: Optional[np.ndarray] = None):
+    """Gradients with respect to x and to the gate weights for the listed tokens (all if None): (dx [n, d],
+    d_topk_w [n, k]) in float64, given dy [T, d] (element type of x)."""
+    elt = _elt_of(x)
+    for a in (dy, W_gate, W_up, W_down):
+        if a.dtype != x.dtype:
+            raise TypeError("dy and the weights must have the element type of x")
+    x, dy, W_gate, W_up, W_down = (np.ascontiguousarray(a) for a in (x, dy, W_gate, W_up, W_down))
+    topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    topk_w = np.ascontiguousarray(topk_w, dtype=np.float32)
+    T, d = x.shape
+    k = topk_idx.shape[1]
+    El, _, f = W_gate.shape
+    assert dy.shape == (T, d) and El == (local_rank_end - local_rank_begin) * (E // R)
+    if tokens is not None:
+        tokens = np.ascontiguousarray(tokens, dtype=np.int32)
+        n = int(tokens.shape[0])
+    else:
+        n = T
+    dx = np.empty((n, d), dtype=np.float64)
+    dw = np.empty((n, k), dtype=np.float64)
+    lib = _lib()
+    lib.moe_oracle_backward_tokens.argtypes = [C.c_int] * 9 + [C.c_void_p] * 8 + [C.c_int, C.c_void_p, C.c_void_p]
+    _check(lib.moe_oracle_backward_tokens(T, d, f, E, k, R, local_rank_begin, local_rank_end, elt, _p(x), _p(dy),
+                                          _p(topk_idx), _p(topk_w), _p(W_gate), _p(W_up), _p(W_down), _p(tokens), n,
+                                          _p(dx), _p(dw)), "backward_tokens")
+    return dx, dw
+
+
+def backward_weights(x, dy, topk_idx, topk_w, W_gate, W_up, W_down, E: int, R: int, local_rank_begin: int,
+                     local_rank_end: int, le: int, n0: int = 0, n1: Optional[int] = None):
+    """Weight gradients of local expert ``le`` for the hidden indices [n0, n1): (dW_gate[:, n0:n1],
+    dW_up[:, n0:n1], dW_down[n0:n1, :]) in float64."""
+    elt = _elt_of(x)
+    x, dy, W_gate, W_up, W_down = (np.ascontiguousarray(a) for a in (x, dy, W_gate, W_up, W_down))
+    topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    topk_w = np.ascontiguousarray(topk_w, dtype=np.float32)
+    T, d = x.shape
+    k = topk_idx.shape[1]
+    El, _, f = W_gate.shape
+    n1 = f if n1 is None else n1
+    dWg = np.empty((d, n1 - n0), dtype=np.float64)
+    dWu = np.empty((d, n1 - n0), dtype=np.float64)
+    dWd = np.empty((n1 - n0, d), dtype=np.float64)
+    lib = _lib()
+    lib.moe_oracle_backward_weights.argtypes = [C.c_int] * 9 + [C.c_void_p] * 7 + [C.c_int] * 3 + [C.c_void_p] * 3
+    _check(lib.moe_oracle_backward_weights(T, d, f, E, k, R, local_rank_begin, local_rank_end, elt, _p(x), _p(dy),
+                                           _p(topk_idx), _p(topk_w), _p(W_gate), _p(W_up), _p(W_down), le, n0, n1,
+                                           _p(dWg), _p(dWu), _p(dWd)), "backward_weights")
+    return dWg, dWu, dWd

@@ -448,3 +448,141 @@ int moe_oracle_forward_fp8(int T, int d, int f, int E, int k, int R, int lrb, in
   }
   return status;
 }
+
+/* ------------------------------------------------------------------------------------------------------------
+ * Backward pass of the layer (the paper's end-to-end results cover forward and backward, Sec. V; it gives no
+ * formulas, these are the derivatives of the forward above).  For a local row (token t, slot j, local expert le,
+ * gate weight w) and the incoming gradient dy_t of y_t:
+ *   dh_raw = dy_t Wd^T,  dw = <h, dh_raw>  (= <o, dy_t>),  dh = w * dh_raw,
+ *   dg = dh * u * silu'(g),  du = dh * silu(g),   silu'(g) = s (1 + g (1 - s)),  s = 1 / (1 + exp(-g)),
+ *   dx_t += dg Wg^T + du Wu^T,
+ *   dWg += x_t^T dg,  dWu += x_t^T du,  dWd += h^T (w dy_t).
+ * Only the local slots contribute (one GPU's share, like the forward).  Everything in double, sums in ascending
+ * index order, rows of an expert in ascending token order.
+ * ------------------------------------------------------------------------------------------------------------ */
+
+/* g, u (full length f) of token t under local expert le */
+static void oracle_gate_up(const void *x, int elt, int t, int d, int f, const void *W_gate, const void *W_up, size_t le,
+                           int n0, int n1, double *g, double *u) {
+  for (int n = n0; n < n1; ++n) { g[n] = 0; u[n] = 0; }
+  for (int c = 0; c < d; ++c) {
+    const double xc = (double)load_elt(x, (size_t)t * d + c, elt);
+    const size_t rowb = le * (size_t)d * f + (size_t)c * f;
+    for (int n = n0; n < n1; ++n) {
+      g[n] += xc * (double)load_elt(W_gate, rowb + n, elt);
+      u[n] += xc * (double)load_elt(W_up, rowb + n, elt);
+    }
+  }
+}
+
+/*
+ * Gradients that belong to tokens: dx rows [n_tok, d] and d_topk_w rows [n_tok, k] (0 for slots whose expert is
+ * not local) for the listed tokens (tokens == NULL: 0..n_tok-1).
+ */
+int moe_oracle_backward_tokens(int T, int d, int f, int E, int k, int R, int lrb, int lre, int elt, const void *x,
+                               const void *dy, const int32_t *topk_idx, const float *topk_w, const void *W_gate,
+                               const void *W_up, const void *W_down, const int32_t *tokens, int n_tok,
+                               double *dx_out, double *dw_out) {
+  if (T < 0 || d < 1 || f < 1 || E < 1 || k < 1 || R < 1 || E % R != 0) return ORACLE_BAD_ARG;
+  if (lrb < 0 || lre <= lrb || lre > R || (elt != ELT_F32 && elt != ELT_BF16) || n_tok < 0) return ORACLE_BAD_ARG;
+  if (!x || !dy || !topk_idx || !topk_w || !W_gate || !W_up || !W_down || !dx_out || !dw_out) return ORACLE_BAD_ARG;
+  const int epr = E / R;
+  const int e_lo = lrb * epr, e_hi = lre * epr;
+  int status = ORACLE_OK;
+#pragma omp parallel
+  {
+    double *g = (double *)malloc(sizeof(double) * (size_t)f);
+    double *u = (double *)malloc(sizeof(double) * (size_t)f);
+    double *dg = (double *)malloc(sizeof(double) * (size_t)f);
+    double *du = (double *)malloc(sizeof(double) * (size_t)f);
+    if (!g || !u || !dg || !du) {
+#pragma omp critical
+      status = ORACLE_NOMEM;
+    } else {
+#pragma omp for schedule(dynamic, 1)
+      for (int i = 0; i < n_tok; ++i) {
+        const int t = tokens ? tokens[i] : i;
+        double *dx = dx_out + (size_t)i * d;
+        for (int c = 0; c < d; ++c) dx[c] = 0;
+        for (int j = 0; j < k; ++j) dw_out[(size_t)i * k + j] = 0;
+        if (t < 0 || t >= T) continue;
+        for (int j = 0; j < k; ++j) {
+          const int e = topk_idx[(size_t)t * k + j];
+          if (e < e_lo || e >= e_hi) continue;
+          const size_t le = (size_t)(e - e_lo);
+          const double w = (double)topk_w[(size_t)t * k + j];
+          oracle_gate_up(x, elt, t, d, f, W_gate, W_up, le, 0, f, g, u);
+          double dwsum = 0;
+          for (int n = 0; n < f; ++n) {
+            double dh_raw = 0;
+            const size_t rowb = le * (size_t)f * d + (size_t)n * d;
+            for (int m = 0; m < d; ++m)
+              dh_raw += (double)load_elt(dy, (size_t)t * d + m, elt) * (double)load_elt(W_down, rowb + m, elt);
+            const double s = 1.0 / (1.0 + exp(-g[n]));
+            dwsum += (g[n] * s * u[n]) * dh_raw;
+            const double dh = w * dh_raw;
+            dg[n] = dh * u[n] * (s * (1.0 + g[n] * (1.0 - s)));
+            du[n] = dh * (g[n] * s);
+          }
+          dw_out[(size_t)i * k + j] = dwsum;
+          for (int c = 0; c < d; ++c) {
+            const size_t rowb = le * (size_t)d * f + (size_t)c * f;
+            double acc = 0;
+            for (int n = 0; n < f; ++n)
+              acc += dg[n] * (double)load_elt(W_gate, rowb + n, elt) + du[n] * (double)load_elt(W_up, rowb + n, elt);
+            dx[c] += acc;
+          }
+        }
+      }
+    }
+    free(g); free(u); free(dg); free(du);
+  }
+  return status;
+}
+
+/*
+ * Weight gradients of local expert le for the hidden indices n in [n0, n1):  dWg[:, n0:n1] and dWu[:, n0:n1]
+ * ([d, n1-n0] each, row-major) and dWd[n0:n1, :] ([n1-n0, d]).  All tokens, ascending.
+ */
+int moe_oracle_backward_weights(int T, int d, int f, int E, int k, int R, int lrb, int lre, int elt, const void *x,
+                                const void *dy, const int32_t *topk_idx, const float *topk_w, const void *W_gate,
+                                const void *W_up, const void *W_down, int le, int n0, int n1, double *dWg,
+                                double *dWu, double *dWd) {
+  if (T < 0 || d < 1 || f < 1 || E < 1 || k < 1 || R < 1 || E % R != 0) return ORACLE_BAD_ARG;
+  if (lrb < 0 || lre <= lrb || lre > R || (elt != ELT_F32 && elt != ELT_BF16)) return ORACLE_BAD_ARG;
+  if (!x || !dy || !topk_idx || !topk_w || !W_gate || !W_up || !W_down || !dWg || !dWu || !dWd) return ORACLE_BAD_ARG;
+  const int epr = E / R;
+  if (le < 0 || le >= (lre - lrb) * epr || n0 < 0 || n1 > f || n0 >= n1) return ORACLE_BAD_ARG;
+  const int e = lrb * epr + le, nn = n1 - n0;
+  double *g = (double *)malloc(sizeof(double) * (size_t)f);
+  double *u = (double *)malloc(sizeof(double) * (size_t)f);
+  if (!g || !u) { free(g); free(u); return ORACLE_NOMEM; }
+  for (size_t i = 0; i < (size_t)d * nn; ++i) { dWg[i] = 0; dWu[i] = 0; dWd[i] = 0; }
+  for (int t = 0; t < T; ++t) {
+    for (int j = 0; j < k; ++j) {
+      if (topk_idx[(size_t)t * k + j] != e) continue;
+      const double w = (double)topk_w[(size_t)t * k + j];
+      oracle_gate_up(x, elt, t, d, f, W_gate, W_up, (size_t)le, n0, n1, g, u);
+      for (int n = n0; n < n1; ++n) {
+        double dh_raw = 0;
+        const size_t rowb = (size_t)le * f * d + (size_t)n * d;
+        for (int m = 0; m < d; ++m)
+          dh_raw += (double)load_elt(dy, (size_t)t * d + m, elt) * (double)load_elt(W_down, rowb + m, elt);
+        const double s = 1.0 / (1.0 + exp(-g[n]));
+        const double h = g[n] * s * u[n];
+        const double dh = w * dh_raw;
+        const double dgn = dh * u[n] * (s * (1.0 + g[n] * (1.0 - s)));
+        const double dun = dh * (g[n] * s);
+        for (int c = 0; c < d; ++c) {
+          const double xc = (double)load_elt(x, (size_t)t * d + c, elt);
+          dWg[(size_t)c * nn + (n - n0)] += xc * dgn;
+          dWu[(size_t)c * nn + (n - n0)] += xc * dun;
+        }
+        for (int m = 0; m < d; ++m)
+          dWd[(size_t)(n - n0) * d + m] += h * (w * (double)load_elt(dy, (size_t)t * d + m, elt));
+      }
+    }
+  }
+  free(g); free(u);
+  return ORACLE_OK;
+}

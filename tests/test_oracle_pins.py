@@ -500,3 +500,85 @@ def test_gate_variants_special_cases(oracle):
     np.testing.assert_array_equal(idx[0], [0, 1, 3, 2])
     with pytest.raises(ValueError):
         oracle.route_topk_gate(np.array([[0.0, np.inf]], dtype=np.float32), 1, 1, None)
+
+
+# ---------------------------------------------------------------- backward pass
+def _loss(oracle, w, idx, tw, x, Wg, Wu, Wd, dy, cfg, lr):
+    """L = sum(y * dy): its gradients are what the backward pass returns for the incoming gradient dy."""
+    y = oracle.forward(x, idx, tw, Wg, Wu, Wd, cfg.E, cfg.R, *lr)
+    return float((y * dy.astype(np.float64)).sum())
+
+
+def test_backward_matches_finite_differences_of_the_forward(oracle):
+    """Central differences of the (pinned) forward in float32-representable steps: every output of the backward."""
+    cfg = small_cfg(T=7, d=6, f=5, E=4, k=2, R=2, local_rank_begin=0, local_rank_end=2, dtype=wl.F32)
+    w = _draw(cfg)
+    lr = (0, 2)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    rng = np.random.default_rng(3)
+    dy = rng.standard_normal((cfg.T, cfg.d)).astype(np.float32)
+    dx, dw = oracle.backward_tokens(w.x, dy, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr)
+    eps = np.float32(2.0 ** -7)
+
+    def fd(arr, pos):
+        a, b = arr.copy(), arr.copy()
+        a[pos] += eps
+        b[pos] -= eps
+        return a, b, float(a[pos] - b[pos])
+
+    def check(got, arr, make_args, n_probe=12, tol=2e-3):
+        for _ in range(n_probe):
+            pos = tuple(int(rng.integers(0, s)) for s in arr.shape)
+            a, b, step = fd(arr, pos)
+            want = (_loss(oracle, w, idx, tw, *make_args(a), dy, cfg, lr)
+                    - _loss(oracle, w, idx, tw, *make_args(b), dy, cfg, lr)) / step
+            assert abs(got(pos) - want) <= tol * (1 + abs(want)), (pos, got(pos), want)
+
+    check(lambda p: dx[p], w.x, lambda a: (a, w.W_gate, w.W_up, w.W_down))
+    grads = [oracle.backward_weights(w.x, dy, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr, le)
+             for le in range(cfg.E)]
+    check(lambda p: grads[p[0]][0][p[1], p[2]], w.W_gate, lambda a: (w.x, a, w.W_up, w.W_down))
+    check(lambda p: grads[p[0]][1][p[1], p[2]], w.W_up, lambda a: (w.x, w.W_gate, a, w.W_down))
+    check(lambda p: grads[p[0]][2][p[1], p[2]], w.W_down, lambda a: (w.x, w.W_gate, w.W_up, a))
+    # gate weights: the forward is linear in them, so a difference of any size is exact
+    for _ in range(8):
+        t, j = int(rng.integers(0, cfg.T)), int(rng.integers(0, cfg.k))
+        a, b = tw.copy(), tw.copy()
+        a[t, j] += 0.25
+        b[t, j] -= 0.25
+        want = (_loss(oracle, w, idx, a, w.x, w.W_gate, w.W_up, w.W_down, dy, cfg, lr)
+                - _loss(oracle, w, idx, b, w.x, w.W_gate, w.W_up, w.W_down, dy, cfg, lr)) / 0.5
+        assert abs(dw[t, j] - want) <= 1e-9 * (1 + abs(want))
+
+
+def test_backward_local_slots_only_and_ranges(oracle):
+    cfg = small_cfg(T=30, local_rank_begin=1, local_rank_end=3)
+    w = _draw(cfg)
+    lr = (1, 3)
+    idx, tw = oracle.route_topk(w.logits, cfg.k)
+    rng = np.random.default_rng(4)
+    dy = wl.f32_to_bf16_bits(rng.standard_normal((cfg.T, cfg.d)).astype(np.float32)) if w.x.dtype == np.uint16 \
+        else rng.standard_normal((cfg.T, cfg.d)).astype(np.float32)
+    dx, dw = oracle.backward_tokens(w.x, dy, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr)
+    epr = cfg.E // cfg.R
+    local = (idx >= epr) & (idx < 3 * epr)
+    assert np.all(dw[~local] == 0) and np.all(dw[local] != 0)
+    assert np.all(dx[~local.any(axis=1)] == 0)
+    sub = np.array([9, 2, 21], dtype=np.int32)
+    dxs, dws = oracle.backward_tokens(w.x, dy, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr, tokens=sub)
+    np.testing.assert_array_equal(dxs, dx[sub])
+    np.testing.assert_array_equal(dws, dw[sub])
+    # a hidden-index range of the weight gradients is the slice of the whole
+    full = oracle.backward_weights(w.x, dy, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr, 1)
+    part = oracle.backward_weights(w.x, dy, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr, 1, 3, 9)
+    np.testing.assert_array_equal(part[0], full[0][:, 3:9])
+    np.testing.assert_array_equal(part[1], full[1][:, 3:9])
+    np.testing.assert_array_equal(part[2], full[2][3:9, :])
+    # dw = <o, dy>: the unweighted expert output against the incoming gradient (forward with weight 1 on one slot)
+    t = int(np.nonzero(local.any(axis=1))[0][0])
+    j = int(np.nonzero(local[t])[0][0])
+    one = np.zeros_like(tw)
+    one[t, j] = 1.0
+    o = oracle.forward(w.x, idx, one, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr, tokens=np.array([t], np.int32))[0]
+    dyf = wl.bf16_bits_to_f32(dy) if dy.dtype == np.uint16 else dy
+    np.testing.assert_allclose(dw[t, j], float((o * dyf[t].astype(np.float64)).sum()), rtol=1e-10)
