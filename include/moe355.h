@@ -250,6 +250,43 @@ MOE355_API int moe_fp8_fused_forward(const moe_shape *shape, const void *x, cons
                                      const void *packed_down, const float *h_scale, void *y, void *workspace,
                                      size_t workspace_bytes, void *stream, void *const *events);
 
+/*
+ * Training path (the paper's end-to-end results cover forward and backward, Sec. V; it gives no formulas: these are
+ * the derivatives of the layer as moe_fused_forward computes it).  bf16 layers with f % 64 == 0, MOE_ERR_UNSUPPORTED
+ * otherwise.  For a local row (token t, slot j, local expert le, gate weight w) and the incoming gradient dy_t:
+ *   dh_raw = dy_t Wd^T, d_topk_w[t,j] = <o, dy_t>, dh = w dh_raw, dg = dh u silu'(g), du = dh silu(g),
+ *   dx_t = sum over the local slots of dg Wg^T + du Wu^T,
+ *   dW_gate[le] = sum over the expert's rows of x_t^T dg, dW_up likewise with du, dW_down[le] = sum of h^T (w dy_t).
+ * Only local slots contribute (one GPU's share): dx rows of tokens without a local slot are zero, d_topk_w is zero
+ * for slots whose expert is not local.
+ *
+ * moe_fused_forward_train: moe_fused_forward that also keeps g, u (bf16) and every weighted expert output row (fp32)
+ *   in `kept` (caller-owned, >= moe_train_kept_bytes(shape), 256-byte aligned), which the backward call reads.
+ * moe_pack_weights_backward: one-off; the transposed uses of the weights in the layout the GEMM kernels stream:
+ *   packed_down_t (W_down^T) and packed_gate_up_t ([W_gate^T ; W_up^T]), moe_backward_packed_weight_bytes(shape, 0 / 1)
+ *   bytes, 16-byte aligned.  Inputs as for moe_pack_weights.
+ * moe_fused_backward: x, dy [T,d] bf16; the routing and tables of the forward; dx [T,d] bf16 and d_topk_w [T,k] fp32
+ *   are written in full.  dW_gate, dW_up [E_loc,d,f] and dW_down [E_loc,f,d] (bf16, written in full, zero for an
+ *   expert without rows) are computed when all three pointers are non-NULL and skipped when all three are NULL.
+ *   workspace >= moe_backward_workspace_bytes(shape), 256-byte aligned.  Sums run in a fixed order: same inputs,
+ *   same bits.
+ */
+MOE355_API size_t moe_train_kept_bytes(const moe_shape *shape);
+MOE355_API size_t moe_backward_workspace_bytes(const moe_shape *shape);
+MOE355_API size_t moe_backward_packed_weight_bytes(const moe_shape *shape, int which);
+MOE355_API int moe_pack_weights_backward(const moe_shape *shape, const void *W_gate, const void *W_up,
+                                         const void *W_down, void *packed_down_t, void *packed_gate_up_t,
+                                         void *stream);
+MOE355_API int moe_fused_forward_train(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                       const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                       const void *packed_down, void *y, void *kept, size_t kept_bytes,
+                                       void *workspace, size_t workspace_bytes, void *stream);
+MOE355_API int moe_fused_backward(const moe_shape *shape, const void *x, const void *dy, const int32_t *topk_idx,
+                                  const float *topk_w, const moe_dispatch *tables, const void *packed_down_t,
+                                  const void *packed_gate_up_t, const void *kept, size_t kept_bytes, void *dx,
+                                  float *d_topk_w, void *dW_gate, void *dW_up, void *dW_down, void *workspace,
+                                  size_t workspace_bytes, void *stream);
+
 /* Static string for a status code. */
 MOE355_API const char *moe_status_string(int status);
 

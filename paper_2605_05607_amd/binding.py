@@ -90,6 +90,17 @@ def lib() -> C.CDLL:
         L.moe_fp8_quantize_rows.argtypes = [C.c_int64, i32, vp, vp, vp, vp]
         L.moe_fp8_fused_forward.restype = i32
         L.moe_fp8_fused_forward.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
+        for name in ("moe_train_kept_bytes", "moe_backward_workspace_bytes"):
+            getattr(L, name).restype = sz
+            getattr(L, name).argtypes = [sp]
+        L.moe_backward_packed_weight_bytes.restype = sz
+        L.moe_backward_packed_weight_bytes.argtypes = [sp, i32]
+        L.moe_pack_weights_backward.restype = i32
+        L.moe_pack_weights_backward.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        L.moe_fused_forward_train.restype = i32
+        L.moe_fused_forward_train.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, sz, vp]
+        L.moe_fused_backward.restype = i32
+        L.moe_fused_backward.argtypes = [sp, vp, vp, vp, vp, dp, vp, vp, vp, sz, vp, vp, vp, vp, vp, vp, sz, vp]
         L.moe_dispatch_gather.restype = i32
         L.moe_dispatch_gather.argtypes = [sp, vp, dp, vp, vp]
         L.moe_combine_reduce.restype = i32
@@ -288,6 +299,45 @@ def moe_fp8_fused_forward(shape, x, topk_idx, topk_w, tables, packed_gate_up, pa
     _check(lib().moe_fp8_fused_forward(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w), C.byref(tables.struct),
                                        _ptr(packed_gate_up), _ptr(packed_down), _ptr(h_scale), _ptr(y),
                                        _ptr(workspace), nbytes, _stream(stream), arr), "moe_fp8_fused_forward")
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def moe_train_kept_bytes(shape: moe_shape) -> int:
+    return int(lib().moe_train_kept_bytes(C.byref(shape)))
+
+
+def moe_backward_workspace_bytes(shape: moe_shape) -> int:
+    return int(lib().moe_backward_workspace_bytes(C.byref(shape)))
+
+
+def moe_backward_packed_weight_bytes(shape: moe_shape, which: int) -> int:
+    return int(lib().moe_backward_packed_weight_bytes(C.byref(shape), which))
+
+
+def moe_pack_weights_backward(shape, W_gate, W_up, W_down, packed_down_t, packed_gate_up_t, stream=None) -> None:
+    _check(lib().moe_pack_weights_backward(C.byref(shape), _ptr(W_gate), _ptr(W_up), _ptr(W_down),
+                                           _ptr(packed_down_t), _ptr(packed_gate_up_t), _stream(stream)),
+           "moe_pack_weights_backward")
+
+
+def moe_fused_forward_train(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, kept, workspace,
+                            stream=None) -> None:
+    _check(lib().moe_fused_forward_train(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
+                                         C.byref(tables.struct), _ptr(packed_gate_up), _ptr(packed_down), _ptr(y),
+                                         _ptr(kept), _nbytes(kept), _ptr(workspace), _nbytes(workspace),
+                                         _stream(stream)), "moe_fused_forward_train")
+
+
+def moe_fused_backward(shape, x, dy, topk_idx, topk_w, tables, packed_down_t, packed_gate_up_t, kept, dx, d_topk_w,
+                       dW_gate, dW_up, dW_down, workspace, stream=None) -> None:
+    _check(lib().moe_fused_backward(C.byref(shape), _ptr(x), _ptr(dy), _ptr(topk_idx), _ptr(topk_w),
+                                    C.byref(tables.struct), _ptr(packed_down_t), _ptr(packed_gate_up_t), _ptr(kept),
+                                    _nbytes(kept), _ptr(dx), _ptr(d_topk_w), _ptr(dW_gate), _ptr(dW_up),
+                                    _ptr(dW_down), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "moe_fused_backward")
 
 
 def moe_dispatch_gather(shape, x, tables, xs, stream=None) -> None:

@@ -4,6 +4,7 @@
 // with a single write-back (Combine; the one-GPU form of the in-switch reduction of Sec. II-C).
 #include <algorithm>
 
+#include "backward_kernels.h"
 #include "combine_kernels.h"
 #include "fp8_kernels.h"
 #include "gemm_bf16.h"
@@ -66,7 +67,7 @@ static size_t fp8_tile_bytes(const moe_shape *s, const Derived &dv, int which) {
 static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, const int32_t *a1_map, int a1_ld,
                         const void *packed_gu, const void *packed_down, const Ws &w, const int32_t *sole, void *y,
                         hipStream_t st, void *const *events = nullptr, bool pipelined = false,
-                        const Fp8Operands *q = nullptr) {
+                        const Fp8Operands *q = nullptr, void *keep_gu = nullptr, float *keep_o = nullptr) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
@@ -80,6 +81,10 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
   g2.row_sole = sole; g2.y = y;
   g2.K = s->f; g2.N = s->d; g2.lda = s->f; g2.ldo = s->d;
   g2.n_items = w.header + 3; g2.work = w.work2;
+  if (keep_gu) {  // training forward: g and u are kept, and every weighted row goes to the kept o
+    g1.aux = keep_gu;
+    g2.out = keep_o;
+  }
   const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dv.max_mtiles * nt + 255) / 256 * 256)); };
   if (q) {
     static std::atomic<uint64_t> done1{0}, done2{0}, done_pipe{0};
@@ -136,8 +141,16 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
       mark(3);
       return launch_status();
     }
-    hipLaunchKernelGGL(gemm_bf16_kernel<true>, grid_of(dv.nt1), dim3(kGemmThreads), 2 * kStageBytes, st,
-                       g1);
+    if (keep_gu) {
+      static std::atomic<uint64_t> done_t{0};
+      if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<true, false, true>), 2 * kStageBytes,
+                             done_t))
+        return MOE_ERR_HIP;
+      hipLaunchKernelGGL((gemm_bf16_kernel<true, false, true>), grid_of(dv.nt1), dim3(kGemmThreads), 2 * kStageBytes,
+                         st, g1);
+    } else {
+      hipLaunchKernelGGL(gemm_bf16_kernel<true>, grid_of(dv.nt1), dim3(kGemmThreads), 2 * kStageBytes, st, g1);
+    }
     int rc = launch_status();
     mark(2);
     if (rc != MOE_OK) return rc;
@@ -211,7 +224,8 @@ extern "C" int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
 static int forward_common(const moe_shape *shape, const void *x, const int32_t *topk_idx, const float *topk_w,
                           const moe_dispatch *tables, const void *packed_gate_up, const void *packed_down, void *y,
                           void *workspace, size_t workspace_bytes, void *stream, bool fused,
-                          void *const *events = nullptr, int gemm_launches = 0, const float *h_scale = nullptr) {
+                          void *const *events = nullptr, int gemm_launches = 0, const float *h_scale = nullptr,
+                          void *keep = nullptr) {
   Derived dv;
   int rc = check_shape(shape, &dv);
   if (rc != MOE_OK) return rc;
@@ -245,7 +259,15 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
   // fused bf16 layers: GEMM-2 writes the rows that need no reduction straight to y and Combine skips them
-  int32_t *sole = fused && shape->dtype == MOE_BF16 ? w.row_sole : nullptr;
+  // (not in the training forward, which keeps every weighted row for the backward pass)
+  int32_t *sole = fused && shape->dtype == MOE_BF16 && !keep ? w.row_sole : nullptr;
+  void *keep_gu = nullptr;
+  float *keep_o = nullptr;
+  if (keep) {
+    const size_t rows = (size_t)(dv.P_cap > 0 ? dv.P_cap : 1);
+    keep_gu = keep;
+    keep_o = reinterpret_cast<float *>(static_cast<unsigned char *>(keep) + align_up(rows * 2 * shape->f * 2, 256));
+  }
   mark(0);
   Fp8Operands q{};
   if (fp8) {
@@ -268,9 +290,9 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   mark(1);
   if (fused) {
     if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, sole, y, st,
-                           events, pipelined, fp8 ? &q : nullptr)) != MOE_OK)
+                           events, pipelined, fp8 ? &q : nullptr, keep_gu, keep_o)) != MOE_OK)
       return rc;
-    rc = launch_combine(shape, dv, w.o, topk_idx, tables, y, sole != nullptr, st);
+    rc = launch_combine(shape, dv, keep ? keep_o : w.o, topk_idx, tables, y, sole != nullptr, st);
     mark(4);
     return rc;
   }
@@ -407,6 +429,188 @@ extern "C" int moe_unfused_forward(const moe_shape *shape, const void *x, const 
                                    void *stream) {
   return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
                         workspace_bytes, stream, false);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Training path: forward that keeps what the backward pass needs, and the backward pass.
+// ------------------------------------------------------------------------------------------------
+namespace moe355 {
+
+// Backward workspace: the tile table (lists for the two backward GEMMs), the per-row metadata and the intermediates.
+struct BwdLayout {
+  FwdLayout t;   // header .. tile_ready as in the forward layout (h and o unused)
+  size_t dgu;    // bf16 [P_cap, 2 f]  dg, then du
+  size_t hw;     // bf16 [P_cap, f]    w silu(g) u
+  size_t dxr;    // float[P_cap, d]    rows of dx before the per-token sum
+  size_t total;
+};
+
+static Derived backward_derived(const moe_shape *s, const Derived &dv) {
+  Derived b = dv;
+  b.nt1 = ceil_div(s->f, kBN);  // first backward GEMM: dh over f in plain 256-column tiles
+  return b;
+}
+
+static BwdLayout backward_layout(const moe_shape *s, const Derived &dvb) {
+  BwdLayout L;
+  size_t off = 0;
+  auto take = [&off](size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  };
+  const size_t rows = (size_t)(dvb.P_cap > 0 ? dvb.P_cap : 1);
+  L.t.header = take(32 * sizeof(int32_t));
+  L.t.work1 = take((size_t)dvb.max_mtiles * dvb.nt1 * 4 * sizeof(int32_t));
+  L.t.work2 = take((size_t)dvb.max_mtiles * dvb.nt2 * 4 * sizeof(int32_t));
+  L.t.row_tok = take(rows * sizeof(int32_t));
+  L.t.row_w = take(rows * sizeof(float));
+  L.t.row_sole = take(rows * sizeof(int32_t));
+  L.t.tile_ready = take((size_t)dvb.max_mtiles * sizeof(int32_t));
+  L.t.h = L.t.o = 0;
+  L.dgu = take(rows * 2 * (size_t)s->f * 2);
+  L.hw = take(rows * (size_t)s->f * 2);
+  L.dxr = take(rows * (size_t)s->d * sizeof(float));
+  L.t.total = L.total = off;
+  return L;
+}
+
+static bool backward_supported(const moe_shape *s) { return s->dtype == MOE_BF16 && s->f % kBK == 0; }
+
+}  // namespace moe355
+
+extern "C" size_t moe_train_kept_bytes(const moe_shape *shape) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK) return 0;
+  const size_t rows = (size_t)(dv.P_cap > 0 ? dv.P_cap : 1);
+  return align_up(rows * 2 * shape->f * 2, 256) + align_up(rows * (size_t)shape->d * sizeof(float), 256);
+}
+
+extern "C" size_t moe_backward_workspace_bytes(const moe_shape *shape) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK) return 0;
+  return backward_layout(shape, backward_derived(shape, dv)).total;
+}
+
+extern "C" size_t moe_backward_packed_weight_bytes(const moe_shape *shape, int which) {
+  Derived dv;
+  if (check_shape(shape, &dv) != MOE_OK || (which != 0 && which != 1)) return 0;
+  if (which == 0) return (size_t)dv.E_loc * ceil_div(shape->f, kBN) * ceil_div(shape->d, kBK) * kTileBytes;  // Wd^T
+  return (size_t)dv.E_loc * ceil_div(shape->d, kBN) * (2 * ceil_div(shape->f, kBK)) * kTileBytes;  // [Wg^T; Wu^T]
+}
+
+extern "C" int moe_pack_weights_backward(const moe_shape *shape, const void *W_gate, const void *W_up,
+                                         const void *W_down, void *packed_down_t, void *packed_gate_up_t,
+                                         void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!W_gate || !W_up || !W_down || !packed_down_t || !packed_gate_up_t) return MOE_ERR_INVALID_ARG;
+  if (!backward_supported(shape)) return MOE_ERR_UNSUPPORTED;
+  if ((reinterpret_cast<uintptr_t>(W_gate) | reinterpret_cast<uintptr_t>(W_up) | reinterpret_cast<uintptr_t>(W_down) |
+       reinterpret_cast<uintptr_t>(packed_down_t) | reinterpret_cast<uintptr_t>(packed_gate_up_t)) % 16 != 0)
+    return MOE_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  begin_launches();
+  const int d = shape->d, f = shape->f;
+  const int ntf = ceil_div(f, kBN), ktd = ceil_div(d, kBK), ntd = ceil_div(d, kBN), ktf = f / kBK;
+  if (ntf > 65535 || ntd > 65535 || dv.E_loc > 65535) return MOE_ERR_UNSUPPORTED;
+  // B[k = model index][n = hidden index] = W_down[n][k]
+  hipLaunchKernelGGL(pack_bf16_transposed_kernel, dim3(ktd, ntf, dv.E_loc), dim3(256), 0, st,
+                     static_cast<const bf16_t *>(W_down), static_cast<bf16_t *>(packed_down_t), d, f, ntf, ktd, 0);
+  // B[k = hidden index, gate then up][n = model index] = W_gate[n][k], W_up[n][k]
+  hipLaunchKernelGGL(pack_bf16_transposed_kernel, dim3(ktf, ntd, dv.E_loc), dim3(256), 0, st,
+                     static_cast<const bf16_t *>(W_gate), static_cast<bf16_t *>(packed_gate_up_t), f, d, ntd, 2 * ktf, 0);
+  hipLaunchKernelGGL(pack_bf16_transposed_kernel, dim3(ktf, ntd, dv.E_loc), dim3(256), 0, st,
+                     static_cast<const bf16_t *>(W_up), static_cast<bf16_t *>(packed_gate_up_t), f, d, ntd, 2 * ktf, ktf);
+  return launch_status();
+}
+
+extern "C" int moe_fused_forward_train(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                       const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                       const void *packed_down, void *y, void *kept, size_t kept_bytes,
+                                       void *workspace, size_t workspace_bytes, void *stream) {
+  if (!shape) return MOE_ERR_INVALID_ARG;
+  if (shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  if (!kept || kept_bytes < moe_train_kept_bytes(shape)) return MOE_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(kept) % 256 != 0) return MOE_ERR_INVALID_ARG;
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, nullptr, 2, nullptr, kept);
+}
+
+extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const void *dy, const int32_t *topk_idx,
+                                  const float *topk_w, const moe_dispatch *tables, const void *packed_down_t,
+                                  const void *packed_gate_up_t, const void *kept, size_t kept_bytes, void *dx,
+                                  float *d_topk_w, void *dW_gate, void *dW_up, void *dW_down, void *workspace,
+                                  size_t workspace_bytes, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!x || !dy || !topk_idx || !topk_w || !packed_down_t || !packed_gate_up_t || !dx || !d_topk_w ||
+      !tables_ok(tables))
+    return MOE_ERR_INVALID_ARG;
+  const bool wgrad = dW_gate || dW_up || dW_down;
+  if (wgrad && !(dW_gate && dW_up && dW_down)) return MOE_ERR_INVALID_ARG;  // all three or none
+  if (!backward_supported(shape)) return MOE_ERR_UNSUPPORTED;
+  if (!kept || kept_bytes < moe_train_kept_bytes(shape)) return MOE_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < moe_backward_workspace_bytes(shape)) return MOE_ERR_WORKSPACE;
+  if ((reinterpret_cast<uintptr_t>(workspace) | reinterpret_cast<uintptr_t>(kept)) % 256 != 0)
+    return MOE_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(dy) | reinterpret_cast<uintptr_t>(dx) |
+       reinterpret_cast<uintptr_t>(packed_down_t) | reinterpret_cast<uintptr_t>(packed_gate_up_t)) % 16 != 0)
+    return MOE_ERR_INVALID_ARG;
+  const Derived dvb = backward_derived(shape, dv);
+  if ((int64_t)dvb.max_mtiles * std::max(dvb.nt1, dvb.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
+  if (std::max(dvb.nt1, dvb.nt2) >= 1 << kTileShift || dvb.max_mtiles >= 1 << (31 - kTileShift)) return MOE_ERR_UNSUPPORTED;
+  if (std::max<int64_t>(shape->T, dv.P_cap) * std::max(shape->d, 2 * shape->f) >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
+  if (wgrad) return MOE_ERR_UNSUPPORTED;  // the weight gradients are not built yet
+  hipStream_t st = (hipStream_t)stream;
+  begin_launches();
+  const size_t n_pairs = (size_t)shape->T * shape->k;
+  if (shape->T == 0) return MOE_OK;
+  const BwdLayout L = backward_layout(shape, dvb);
+  const Ws w = carve(workspace, L.t);
+  unsigned char *b = static_cast<unsigned char *>(workspace);
+  bf16_t *dgu = reinterpret_cast<bf16_t *>(b + L.dgu), *hw = reinterpret_cast<bf16_t *>(b + L.hw);
+  float *dxr = reinterpret_cast<float *>(b + L.dxr);
+  const size_t rows = (size_t)(dv.P_cap > 0 ? dv.P_cap : 1);
+  const bf16_t *kept_gu = static_cast<const bf16_t *>(kept);
+  const float *kept_o = reinterpret_cast<const float *>(static_cast<const unsigned char *>(kept) +
+                                                        align_up(rows * 2 * shape->f * 2, 256));
+  if ((rc = launch_prep(shape, dvb, tables, topk_idx, topk_w, w, w.row_sole, st)) != MOE_OK) return rc;
+  // gradient of the gate weights (zero for the slots whose expert is not local)
+  hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)std::min<size_t>(1024, (n_pairs + 255) / 256)), dim3(256), 0, st,
+                     d_topk_w, n_pairs, 0.0f);
+  hipLaunchKernelGGL(gate_weight_grad_kernel, dim3((unsigned)std::min<size_t>(4096, (rows + 3) / 4)), dim3(256), 0, st,
+                     kept_o, static_cast<const bf16_t *>(dy), w.header, w.row_tok, w.row_w, tables->perm, shape->d,
+                     d_topk_w);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  static std::atomic<uint64_t> done_b1{0}, done_b2{0};
+  if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<false, false, true>), 2 * kStageBytes,
+                         done_b1) ||
+      !allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<false>), 2 * kStageBytes, done_b2))
+    return MOE_ERR_HIP;
+  const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dvb.max_mtiles * nt + 255) / 256 * 256)); };
+  // dh_raw = dy[token of the row] Wd^T, then the SwiGLU derivative with the kept g and u
+  GemmArgs g1{};
+  g1.A = dy; g1.row_map = w.row_tok; g1.Bp = packed_down_t; g1.out = dgu; g1.row_w = w.row_w;
+  g1.aux = const_cast<bf16_t *>(kept_gu); g1.aux2 = hw;
+  g1.n_items = w.header + 0; g1.work = w.work1;
+  g1.K = shape->d; g1.N = shape->f; g1.lda = shape->d; g1.ldo = 2 * shape->f;
+  g1.n_ntiles = dvb.nt1; g1.n_ktiles = ceil_div(shape->d, kBK);
+  hipLaunchKernelGGL((gemm_bf16_kernel<false, false, true>), grid_of(dvb.nt1), dim3(kGemmThreads), 2 * kStageBytes, st,
+                     g1);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  // rows of dx = [dg | du] [Wg^T ; Wu^T]; a row that is its token's only local slot goes straight to dx
+  GemmArgs g2{};
+  g2.A = dgu; g2.row_map = nullptr; g2.Bp = packed_gate_up_t; g2.out = dxr; g2.row_w = nullptr;
+  g2.row_sole = w.row_sole; g2.y = dx;
+  g2.n_items = w.header + 3; g2.work = w.work2;
+  g2.K = 2 * shape->f; g2.N = shape->d; g2.lda = 2 * shape->f; g2.ldo = shape->d;
+  g2.n_ntiles = dvb.nt2; g2.n_ktiles = 2 * (shape->f / kBK);
+  hipLaunchKernelGGL(gemm_bf16_kernel<false>, grid_of(dvb.nt2), dim3(kGemmThreads), 2 * kStageBytes, st, g2);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  return launch_combine(shape, dv, dxr, topk_idx, tables, dx, true, st);
 }
 
 extern "C" int moe_dispatch_gather(const moe_shape *shape, const void *x, const moe_dispatch *tables, void *xs,

@@ -51,6 +51,10 @@ struct GemmArgs {
   const int32_t *n_items;  // device: number of work items of this GEMM
   const int4 *work;        // device: work list
   int K, N, lda, ldo, n_ntiles, n_ktiles;
+  // training path only (null otherwise): kept g and u (written by GEMM-1, read by the first backward GEMM) and the
+  // weighted h the first backward GEMM writes
+  void *aux;
+  void *aux2;
   // FP8 operands only (null otherwise)
   const float *a_scale;  // GEMM-1: scale of every token's row of x (indexed like A's rows)
   const float *b_scale;  // scales of the output columns: GEMM-1 [E_loc][2][N] (gate, up), GEMM-2 [E_loc][N]

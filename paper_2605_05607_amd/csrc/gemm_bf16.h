@@ -49,7 +49,12 @@ constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue p
 // so the staging, the LDS image and the fragment reads are byte for byte those of the bf16 tile.  The scales
 // (g.a_scale per token, g.b_scale per expert and output column, g.h_scale per expert) are applied in the epilogues
 // and GEMM-1 writes h as codes.
-template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false>
+// TRAIN selects the epilogues of the training path (bf16 only):
+//   GATED  : as GEMM-1, and g and u are kept as well (g.aux = gu [rows, 2 N] bf16: g, then u) for the backward pass;
+//   !GATED : the first GEMM of the backward pass, dh_raw = dy Wd^T (N = f).  With the kept g, u and the gate weight w:
+//            dh = w dh_raw, dg = dh u silu'(g), du = dh silu(g)  ->  g.out = dgu [rows, 2 N] bf16 (dg, then du), and
+//            g.aux2 = w silu(g) u [rows, N] bf16 (the h operand of the down-projection weight gradient, weight folded in).
+template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
                                                int rows, int nblk_total) {
   // RESIDENT (the kernel that loops over items): the thread index goes through an empty asm so that nothing
@@ -298,7 +303,28 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 #pragma unroll
   for (int mi = 0; mi < NB; ++mi) {
     const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
-    if (GATED && FP8) {
+    if (!GATED && TRAIN) {
+      const bf16_t *gu = static_cast<const bf16_t *>(g.aux);
+      bf16_t *dgu = static_cast<bf16_t *>(g.out), *hw = static_cast<bf16_t *>(g.aux2);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int col = nt * kBN + wn * 64 + j * 32 + l31;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row_l = blk_row0 + (r >> 2) * 8 + khalf * 4 + (r & 3);
+          if (row_l < rows && col < g.N) {
+            const size_t row = (size_t)(m0 + row_l);
+            const float wv = g.row_w[row];
+            const float gv = (float)gu[row * 2 * g.N + col], uv = (float)gu[row * 2 * g.N + g.N + col];
+            const float sg = 1.0f / (1.0f + __expf(-gv)), silu = gv * sg;
+            const float dh = wv * acc[mi][j][r];
+            dgu[row * 2 * g.N + col] = (bf16_t)(dh * uv * (sg * (1.0f + gv * (1.0f - sg))));
+            dgu[row * 2 * g.N + g.N + col] = (bf16_t)(dh * silu);
+            hw[row * g.N + col] = (bf16_t)(wv * silu * uv);
+          }
+        }
+      }
+    } else if (GATED && FP8) {
       // h block: 32 rows x 32 columns of E4M3 codes, row pitch 48 bytes.  g and u get the scales of their token
       // and of their columns; h = silu(g) * u is divided by the expert's scale for h and converted.
       const int col_h = nt * (kBN / 2) + wn * 32 + l31;
@@ -331,6 +357,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const float gv = acc[mi][0][r], uv = acc[mi][1][r];
         *reinterpret_cast<bf16_t *>(patch + rl * 80 + l31 * 2) = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
+        if (TRAIN) {
+          const int row_l = blk_row0 + rl, col_h = nt * (kBN / 2) + wn * 32 + l31;
+          if (row_l < rows && col_h < g.N) {
+            bf16_t *gu = static_cast<bf16_t *>(g.aux) + (size_t)(m0 + row_l) * 2 * g.N;
+            gu[col_h] = (bf16_t)gv;
+            gu[g.N + col_h] = (bf16_t)uv;
+          }
+        }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -366,7 +400,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const int row_l = blk_row0 + rl;
-        const float wgt = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
+        const float wgt = row_l < rows ? (g.row_w ? g.row_w[m0 + row_l] : 1.f) : 0.f;
         *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = FP8 ? acc[mi][0][r] * cs0 * wgt : acc[mi][0][r] * wgt;
         *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) =
             FP8 ? acc[mi][1][r] * cs1 * wgt : acc[mi][1][r] * wgt;
@@ -399,14 +433,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 
 // One work item on the matrix cores.  Wave-uniform dispatch on the number of valid 32-row blocks: every variant
 // executes the same sequence of barriers.
-template <bool GATED, bool RESIDENT, bool FP8 = false>
+template <bool GATED, bool RESIDENT, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item) {
   const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
 #define MOE355_TILE(NB_, NA_) \
-  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8>(g, smem, nt, le, m0, rows, nblk_total)
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN>(g, smem, nt, le, m0, rows, nblk_total)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -419,12 +453,12 @@ __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char 
 }
 
 // One workgroup per work item; workgroup -> item by chunked_item.
-template <bool GATED, bool FP8 = false>
+template <bool GATED, bool FP8 = false, bool TRAIN = false>
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_kernel(const GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
   const int q = chunked_item(blockIdx.x, *g.n_items);
   if (q < 0) return;
-  gemm_bf16_item<GATED, false, FP8>(g, smem, g.work[q]);
+  gemm_bf16_item<GATED, false, FP8, TRAIN>(g, smem, g.work[q]);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -38,6 +38,26 @@ __global__ __launch_bounds__(256) void pack_bf16_kernel(const bf16_t *__restrict
   }
 }
 
+// The same tile image from a source whose rows are the OUTPUT columns (the transposed use of a weight matrix in the
+// backward pass): B[k][n] = W[n][k], W = [E_loc][N][K] with K contiguous, so a thread's 8 values are one 16-byte
+// load.  The tiles go to reduction tiles kt_offset + kt of n_ktiles_total (two sources can share one reduction
+// range: the gate weights, then the up weights).
+__global__ __launch_bounds__(256) void pack_bf16_transposed_kernel(const bf16_t *__restrict__ W,
+                                                                   bf16_t *__restrict__ out, int K, int N,
+                                                                   int n_ntiles, int n_ktiles_total, int kt_offset) {
+  const int kt = blockIdx.x, nt = blockIdx.y, le = blockIdx.z;
+  const int n_l = threadIdx.x;
+  const int col = nt * kBN + n_l;
+  const bf16_t *src = W + ((size_t)le * N + (col < N ? col : 0)) * K;
+  bf16_t *tile = out + ((size_t)(le * n_ntiles + nt) * n_ktiles_total + kt_offset + kt) * (kBN * kBK);
+  for (int c = 0; c < 8; ++c) {
+    const int kk = kt * kBK + c * 8;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (col < N && kk < K) v = *reinterpret_cast<const u32x4 *>(src + kk);  // K % 8 == 0: the chunk is inside the row
+    *reinterpret_cast<u32x4 *>(tile + ((((n_l >> 5) * 4 + (c >> 1)) * 64 + (c & 1) * 32 + (n_l & 31)) << 3)) = v;
+  }
+}
+
 __global__ void copy_f32_kernel(const float *__restrict__ src, float *__restrict__ dst, size_t n) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
     dst[i] = src[i];

@@ -69,6 +69,38 @@ class MoELayer:
         B.moe_fp8_fused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.fp8_gate_up,
                                 self.fp8_down, self.h_scale, self.y, self.fp8_ws, events)
 
+    def enable_training(self, W_gate: np.ndarray, W_up: np.ndarray, W_down: np.ndarray, wgrad: bool = True) -> None:
+        """Buffers of the training path: transposed weight packs, the kept activations, gradients, workspace."""
+        import torch
+        s = self.shape
+        dev = self.device
+        self.packed_down_t = torch.empty(B.moe_backward_packed_weight_bytes(s, 0), dtype=torch.uint8, device=dev)
+        self.packed_gate_up_t = torch.empty(B.moe_backward_packed_weight_bytes(s, 1), dtype=torch.uint8, device=dev)
+        g, u, d = (to_device(a, dev) for a in (W_gate, W_up, W_down))
+        B.moe_pack_weights_backward(s, g, u, d, self.packed_down_t, self.packed_gate_up_t)
+        torch.cuda.synchronize()
+        del g, u, d
+        self.kept = torch.empty(max(1, B.moe_train_kept_bytes(s)), dtype=torch.uint8, device=dev)
+        self.backward_ws = torch.empty(max(1, B.moe_backward_workspace_bytes(s)), dtype=torch.uint8, device=dev)
+        self.dx = torch.empty((max(1, s.T), s.d), dtype=torch.bfloat16, device=dev)
+        self.d_topk_w = torch.empty(max(1, s.T * s.k), dtype=torch.float32, device=dev)
+        El = self.cfg.E_loc
+        if wgrad:
+            self.dW_gate = torch.empty((El, s.d, s.f), dtype=torch.bfloat16, device=dev)
+            self.dW_up = torch.empty((El, s.d, s.f), dtype=torch.bfloat16, device=dev)
+            self.dW_down = torch.empty((El, s.f, s.d), dtype=torch.bfloat16, device=dev)
+        else:
+            self.dW_gate = self.dW_up = self.dW_down = None
+
+    def forward_train(self, x) -> None:
+        B.moe_fused_forward_train(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
+                                  self.packed_down, self.y, self.kept, self.forward_ws)
+
+    def backward(self, x, dy) -> None:
+        B.moe_fused_backward(self.shape, x, dy, self.topk_idx, self.topk_w, self.tables, self.packed_down_t,
+                             self.packed_gate_up_t, self.kept, self.dx, self.d_topk_w, self.dW_gate, self.dW_up,
+                             self.dW_down, self.backward_ws)
+
     def route(self, logits) -> None:
         B.moe_route_topk(self.shape, logits, self.topk_idx, self.topk_w)
 

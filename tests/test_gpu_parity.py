@@ -601,3 +601,73 @@ def test_route_gate_variants(oracle, T, E, k, gate, with_bias):
     assert np.all(np.diff(picked, axis=1) <= slack)  # slot order = descending selection value
     assert all(len(set(r)) == k for r in idx.tolist())
     assert np.allclose(w.sum(axis=1), 1.0, atol=1e-5) and np.isfinite(w).all()
+
+
+# ---------------------------------------------------------------- training path: forward that keeps g, u, o; backward
+BWD_SMALL = {
+    "deepseek_like": cfg_of(T=700, d=448, f=320, E=64, k=8, R=8, local_rank_begin=0, local_rank_end=1, router="zipf",
+                            seed=21),
+    "qwen_like": SMALL["qwen_like"],
+    "mixtral_like": SMALL["mixtral_like"],
+    "ragged": cfg_of(T=333, d=200, f=128, E=12, k=3, R=3, local_rank_begin=1, local_rank_end=3, seed=41),
+    "table1_like_k16": SMALL["table1_like_k16"],
+}
+
+
+def dy_for(cfg, seed=9):
+    rng = np.random.default_rng(seed + cfg.seed)
+    return wl.f32_to_bf16_bits(rng.standard_normal((cfg.T, cfg.d)).astype(np.float32))
+
+
+def run_backward(cfg, oracle, wgrad):
+    import torch
+    w = wl.make_workload(cfg)
+    lay = L.MoELayer(cfg)
+    lay.load_weights(w.W_gate, w.W_up, w.W_down)
+    lay.enable_training(w.W_gate, w.W_up, w.W_down, wgrad=wgrad)
+    x, lg = L.to_device(w.x), L.to_device(w.logits)
+    dy_bits = dy_for(cfg)
+    dy = L.to_device(dy_bits)
+    lay.route(lg)
+    lay.build_dispatch()
+    lay.y.fill_(float("nan"))
+    lay.forward_train(x)
+    lay.dx.fill_(float("nan"))
+    lay.d_topk_w.fill_(float("nan"))
+    lay.backward_ws.fill_(0xFF)
+    if wgrad:
+        for t in (lay.dW_gate, lay.dW_up, lay.dW_down):
+            t.fill_(float("nan"))
+    lay.backward(x, dy)
+    torch.cuda.synchronize()
+    got = G.tables_to_host(lay)
+    idx, tw = G.assert_tables_equal(got, oracle, w.logits, cfg)
+    return w, lay, x, dy, dy_bits, idx, tw
+
+
+@pytest.mark.parametrize("name", list(BWD_SMALL))
+def test_backward_tokens_matches_oracle_small(oracle, name):
+    import torch
+    cfg = BWD_SMALL[name]
+    say(f"backward (dx, d_topk_w) small {name}: T={cfg.T} d={cfg.d} f={cfg.f} E={cfg.E} k={cfg.k}")
+    w, lay, x, dy, dy_bits, idx, tw = run_backward(cfg, oracle, wgrad=False)
+    lr = (cfg.local_rank_begin, cfg.local_rank_end)
+    # the training forward gives the same y as the plain forward's oracle
+    ref_y = oracle.forward(w.x, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr)
+    G.check_y(lay.y_host(), ref_y, cfg.dtype)
+    ref_dx, ref_dw = oracle.backward_tokens(w.x, dy_bits, idx, tw, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr)
+    dx = lay.dx[: cfg.T].to(torch.float64).cpu().numpy()
+    mx, mean = G.check_y(dx, ref_dx, cfg.dtype)
+    dw = lay.d_topk_w[: cfg.T * cfg.k].cpu().numpy().astype(np.float64).reshape(cfg.T, cfg.k)
+    local = (idx // cfg.epr >= lr[0]) & (idx // cfg.epr < lr[1])
+    assert np.all(dw[~local] == 0) and np.all(dx[~local.any(axis=1)] == 0)
+    err = np.abs(dw - ref_dw).max() / np.abs(ref_dw).max()
+    say(f"  dx max rel {mx:.2e} mean rel {mean:.2e}; d_topk_w max err / max {err:.2e}")
+    assert err <= 2e-2
+    # rerun over a trashed workspace: bit-identical
+    dx0, dw0 = lay.dx.clone(), lay.d_topk_w.clone()
+    lay.backward_ws.fill_(0x5A)
+    lay.dx.fill_(3.0)
+    lay.backward(x, dy)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.dx, dx0) and torch.equal(lay.d_topk_w, dw0)
