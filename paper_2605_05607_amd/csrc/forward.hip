@@ -11,6 +11,7 @@
 #include "gemm_f32.h"
 #include "pack_kernels.h"
 #include "prep_kernel.h"
+#include "wgrad_bf16.h"
 
 namespace moe355 {
 
@@ -442,6 +443,12 @@ struct BwdLayout {
   size_t dgu;    // bf16 [P_cap, 2 f]  dg, then du
   size_t hw;     // bf16 [P_cap, f]    w silu(g) u
   size_t dxr;    // float[P_cap, d]    rows of dx before the per-token sum
+  // weight gradients: operands transposed to [column][row] with every expert's rows padded to a multiple of 64
+  size_t kb;     // int32[E_loc + 1]   first 64-row block of every local expert in the padded row order
+  size_t xT, dyT;  // bf16 [d][kpad]   gathered x rows, gathered dy rows
+  size_t hwT;    // bf16 [f][kpad]
+  size_t dguT;   // bf16 [2 f][kpad]
+  size_t kpad;   // padded row capacity (elements): 64 (ceil(P_cap / 64) + E_loc)
   size_t total;
 };
 
@@ -471,6 +478,12 @@ static BwdLayout backward_layout(const moe_shape *s, const Derived &dvb) {
   L.dgu = take(rows * 2 * (size_t)s->f * 2);
   L.hw = take(rows * (size_t)s->f * 2);
   L.dxr = take(rows * (size_t)s->d * sizeof(float));
+  L.kpad = 64 * ((rows + 63) / 64 + (size_t)dvb.E_loc);
+  L.kb = take((size_t)(dvb.E_loc + 1) * sizeof(int32_t));
+  L.xT = take((size_t)s->d * L.kpad * 2);
+  L.dyT = take((size_t)s->d * L.kpad * 2);
+  L.hwT = take((size_t)s->f * L.kpad * 2);
+  L.dguT = take(2 * (size_t)s->f * L.kpad * 2);
   L.t.total = L.total = off;
   return L;
 }
@@ -563,7 +576,9 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   if ((int64_t)dvb.max_mtiles * std::max(dvb.nt1, dvb.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
   if (std::max(dvb.nt1, dvb.nt2) >= 1 << kTileShift || dvb.max_mtiles >= 1 << (31 - kTileShift)) return MOE_ERR_UNSUPPORTED;
   if (std::max<int64_t>(shape->T, dv.P_cap) * std::max(shape->d, 2 * shape->f) >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
-  if (wgrad) return MOE_ERR_UNSUPPORTED;  // the weight gradients are not built yet
+  if (wgrad && (reinterpret_cast<uintptr_t>(dW_gate) | reinterpret_cast<uintptr_t>(dW_up) |
+                reinterpret_cast<uintptr_t>(dW_down)) % 8 != 0)
+    return MOE_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   begin_launches();
   const size_t n_pairs = (size_t)shape->T * shape->k;
@@ -610,7 +625,36 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   g2.n_ntiles = dvb.nt2; g2.n_ktiles = 2 * (shape->f / kBK);
   hipLaunchKernelGGL(gemm_bf16_kernel<false>, grid_of(dvb.nt2), dim3(kGemmThreads), 2 * kStageBytes, st, g2);
   if ((rc = launch_status()) != MOE_OK) return rc;
-  return launch_combine(shape, dv, dxr, topk_idx, tables, dx, true, st);
+  if ((rc = launch_combine(shape, dv, dxr, topk_idx, tables, dx, true, st)) != MOE_OK || !wgrad) return rc;
+  // weight gradients: transpose (and gather) the four operands, then one grouped product per weight matrix
+  static std::atomic<uint64_t> done_w{0};
+  if (!allow_dynamic_lds(reinterpret_cast<const void *>(&wgrad_bf16_kernel), 2 * kStageBytes, done_w))
+    return MOE_ERR_HIP;
+  int32_t *kb = reinterpret_cast<int32_t *>(b + L.kb);
+  bf16_t *xT = reinterpret_cast<bf16_t *>(b + L.xT), *dyT = reinterpret_cast<bf16_t *>(b + L.dyT);
+  bf16_t *hwT = reinterpret_cast<bf16_t *>(b + L.hwT), *dguT = reinterpret_cast<bf16_t *>(b + L.dguT);
+  const int kblocks = (int)(L.kpad / 64);
+  if (kblocks > 65535) return MOE_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(wgrad_blocks_kernel, dim3(1), dim3(256), 0, st, tables->offsets, w.header, dv.e_lo, dv.E_loc, kb);
+  const auto transpose = [&](const bf16_t *src, const int32_t *map, int ld, int C, bf16_t *dst) {
+    hipLaunchKernelGGL(gather_transpose_kernel, dim3(ceil_div(C, 64), kblocks), dim3(256), 0, st, src, map, ld, 0, C,
+                       tables->offsets, w.header, kb, dv.e_lo, dv.E_loc, dst, L.kpad);
+  };
+  transpose(static_cast<const bf16_t *>(x), w.row_tok, shape->d, shape->d, xT);
+  transpose(static_cast<const bf16_t *>(dy), w.row_tok, shape->d, shape->d, dyT);
+  transpose(hw, nullptr, shape->f, shape->f, hwT);
+  transpose(dgu, nullptr, 2 * shape->f, 2 * shape->f, dguT);
+  if ((rc = launch_status()) != MOE_OK) return rc;
+  const auto product = [&](const bf16_t *AT, const bf16_t *BT, int M, int N, void *C) {
+    WgradArgs a;
+    a.AT = AT; a.BT = BT; a.C = static_cast<bf16_t *>(C); a.kb = kb; a.kpad = L.kpad;
+    a.M = M; a.N = N; a.n_mt = ceil_div(M, kBM); a.n_nt = ceil_div(N, kBN);
+    hipLaunchKernelGGL(wgrad_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(kGemmThreads), 2 * kStageBytes, st, a);
+  };
+  product(xT, dguT, shape->d, shape->f, dW_gate);                                  // x^T dg
+  product(xT, dguT + (size_t)shape->f * L.kpad, shape->d, shape->f, dW_up);       // x^T du
+  product(hwT, dyT, shape->f, shape->d, dW_down);                                  // (w h)^T dy
+  return launch_status();
 }
 
 extern "C" int moe_dispatch_gather(const moe_shape *shape, const void *x, const moe_dispatch *tables, void *xs,
