@@ -401,6 +401,32 @@ def main():
             del a8, b8
         except Exception as exc:  # the reference figure is optional
             out["fp8_gemms"]["dense_fp8_gemm_reference"] = {"error": str(exc)[:200]}
+    # Training path (not `value`): the forward that keeps g, u and the weighted rows, then the backward pass (dx, gate-
+    # weight gradients and the three weight gradients).  Flops: forward 6 P d f, backward 12 P d f.
+    if cfg.dtype == wl.BF16 and cfg.f % 64 == 0:
+        lay.enable_training(w.W_gate, w.W_up, w.W_down, wgrad=True)
+        dy = torch.randn((cfg.T, cfg.d), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+        t_ft = timed(lambda: lay.forward_train(x), 5)
+        t_bw = timed(lambda: lay.backward(x, dy), 5)
+        dWg, dWu, dWd = lay.dW_gate, lay.dW_up, lay.dW_down
+        lay.dW_gate = lay.dW_up = lay.dW_down = None
+        t_bw_tok = timed(lambda: lay.backward(x, dy), 5)
+        lay.dW_gate, lay.dW_up, lay.dW_down = dWg, dWu, dWd
+        fl = 2.0 * P * cfg.d * cfg.f
+        wg_bytes = 3.0 * cfg.E_loc * cfg.d * cfg.f * 2  # every weight gradient is written in full
+        out["training"] = {"entries": "moe_fused_forward_train, moe_fused_backward", "forward_train_ms": t_ft,
+                           "backward_ms": t_bw, "backward_without_weight_gradients_ms": t_bw_tok,
+                           "weight_gradients_ms": t_bw - t_bw_tok,
+                           "forward_plus_backward_ms": t_ft + t_bw,
+                           "backward_tflops": 6 * fl / (t_bw * 1e-3) / 1e12,
+                           "dgrad_tflops": 3 * fl / (t_bw_tok * 1e-3) / 1e12,
+                           "wgrad_tflops": 3 * fl / ((t_bw - t_bw_tok) * 1e-3) / 1e12,
+                           "wgrad_bytes_written": wg_bytes,
+                           "wgrad_write_gbs": wg_bytes / ((t_bw - t_bw_tok) * 1e-3) / 1e9}
+        for name in ("packed_down_t", "packed_gate_up_t", "kept", "backward_ws", "dx", "d_topk_w", "dW_gate", "dW_up",
+                     "dW_down"):
+            delattr(lay, name)
+        del dy, dWg, dWu, dWd
     # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

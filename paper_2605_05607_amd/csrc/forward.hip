@@ -582,7 +582,14 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   hipStream_t st = (hipStream_t)stream;
   begin_launches();
   const size_t n_pairs = (size_t)shape->T * shape->k;
-  if (shape->T == 0) return MOE_OK;
+  if (shape->T == 0) {
+    if (wgrad) {  // no rows: every weight gradient is zero (bf16 zeros are zero words)
+      const size_t words = (size_t)dv.E_loc * shape->d * shape->f / 2;
+      for (void *p : {dW_gate, dW_up, dW_down})
+        hipLaunchKernelGGL(fill_f32_kernel, dim3(1024), dim3(256), 0, st, static_cast<float *>(p), words, 0.0f);
+    }
+    return launch_status();
+  }
   const BwdLayout L = backward_layout(shape, dvb);
   const Ws w = carve(workspace, L.t);
   unsigned char *b = static_cast<unsigned char *>(workspace);
@@ -650,6 +657,8 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
     a.AT = AT; a.BT = BT; a.C = static_cast<bf16_t *>(C); a.kb = kb; a.kpad = L.kpad;
     a.M = M; a.N = N; a.n_mt = ceil_div(M, kBM); a.n_nt = ceil_div(N, kBN);
     hipLaunchKernelGGL(wgrad_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(kGemmThreads), 2 * kStageBytes, st, a);
+    a.n_mt = ceil_div(M, 128); a.n_nt = ceil_div(N, 128);  // experts with few or no rows: small tiles
+    hipLaunchKernelGGL(wgrad_thin_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(256), 0, st, a);
   };
   product(xT, dguT, shape->d, shape->f, dW_gate);                                  // x^T dg
   product(xT, dguT + (size_t)shape->f * L.kpad, shape->d, shape->f, dW_up);       // x^T du

@@ -92,6 +92,11 @@ struct WgradArgs {
   int M, N, n_mt, n_nt;
 };
 
+// Experts with at most kThinSteps blocks of 64 rows (and experts without rows, whose gradients are zero) are left to
+// wgrad_thin_bf16_kernel: their cost is writing the output, and that kernel's small workgroups overlap the stores of
+// one tile with the loads of the next on the same CU.
+constexpr int kThinSteps = 2;
+
 // One workgroup per (local expert, 256 x 256 output tile); 8 waves = 2 x 4, each 128 x 64 as 4 x 2 accumulators.
 // LDS: two stages of (A 256 x 64, B 256 x 64), rows of 128 bytes with the forward tile's chunk swizzle.
 __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const WgradArgs a) {
@@ -102,6 +107,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
   const int mt = blockIdx.x / a.n_nt, nt = blockIdx.x % a.n_nt;
   const int m0 = mt * kBM, n0 = nt * kBN;
   const int kb0 = a.kb[le], KT = a.kb[le + 1] - kb0;
+  if (KT <= kThinSteps) return;  // whole workgroup: the thin kernel owns this expert
 
   const int chunk = tid & 7, row0 = tid >> 3;  // rows row0 + 64 i
   const bf16_t *ap[4], *bp[4];
@@ -122,54 +128,89 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
       for (int r = 0; r < 16; ++r) acc[mi][j][r] = 0.f;
 
   const int l31 = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
-  if (KT > 0) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra[i] = *reinterpret_cast<const u32x4 *>(ap[i]);
-      rb[i] = *reinterpret_cast<const u32x4 *>(bp[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<u32x4 *>(smem + dst + 8192 * i) = ra[i];
-      *reinterpret_cast<u32x4 *>(smem + 32768 + dst + 8192 * i) = rb[i];
+  const int a_rd = (wm * 128 + l31) * 128;            // + mi * 4096
+  const int b_rd = 32768 + (wn * 64 + l31) * 128;     // + j * 4096
+  bf16x8 fa0[4], fb0[2], fa1[4], fb1[2];  // operand fragments of two consecutive substeps
+#define MOE355_W_READ(FA, FB, STAGE, KK)                                                           \
+  do {                                                                                             \
+    const int slot_ = (((KK) * 2 + khalf) ^ sw) * 16;                                              \
+    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) FA[mi] =                                      \
+        *reinterpret_cast<const bf16x8 *>((STAGE) + a_rd + mi * 4096 + slot_);                     \
+    FB[0] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + slot_);                             \
+    FB[1] = *reinterpret_cast<const bf16x8 *>((STAGE) + b_rd + 4096 + slot_);                      \
+  } while (0)
+#define MOE355_W_MFMAS(FA, FB)                                                                     \
+  do {                                                                                             \
+    _Pragma("unroll") for (int mi = 0; mi < 4; ++mi) {                                             \
+      acc[mi][0] = mfma_bf16(FA[mi], FB[0], acc[mi][0]);                                           \
+      acc[mi][1] = mfma_bf16(FA[mi], FB[1], acc[mi][1]);                                           \
+    }                                                                                              \
+  } while (0)
+  // the slab in flight moves in three portions {a0, a1, b0}, {a2, a3, b1}, {b2, b3}: stored into the other stage and
+  // reloaded for the slab after it, spread under the matrix instructions as in the forward tile
+#define MOE355_W_STORE(NX, I0, I1, J0, J1)                                                         \
+  do {                                                                                             \
+    if ((I0) >= 0) *reinterpret_cast<u32x4 *>((NX) + dst + 8192 * (I0)) = ra[(I0) < 0 ? 0 : (I0)]; \
+    if ((I1) >= 0) *reinterpret_cast<u32x4 *>((NX) + dst + 8192 * (I1)) = ra[(I1) < 0 ? 0 : (I1)]; \
+    *reinterpret_cast<u32x4 *>((NX) + 32768 + dst + 8192 * (J0)) = rb[(J0)];                       \
+    if ((J1) >= 0) *reinterpret_cast<u32x4 *>((NX) + 32768 + dst + 8192 * (J1)) = rb[(J1) < 0 ? 0 : (J1)]; \
+  } while (0)
+#define MOE355_W_LOAD(KP, I0, I1, J0, J1)                                                          \
+  do {                                                                                             \
+    if ((I0) >= 0) ra[(I0) < 0 ? 0 : (I0)] = *reinterpret_cast<const u32x4 *>(ap[(I0) < 0 ? 0 : (I0)] + (size_t)(KP) * 64); \
+    if ((I1) >= 0) ra[(I1) < 0 ? 0 : (I1)] = *reinterpret_cast<const u32x4 *>(ap[(I1) < 0 ? 0 : (I1)] + (size_t)(KP) * 64); \
+    rb[(J0)] = *reinterpret_cast<const u32x4 *>(bp[(J0)] + (size_t)(KP) * 64);                     \
+    if ((J1) >= 0) rb[(J1) < 0 ? 0 : (J1)] = *reinterpret_cast<const u32x4 *>(bp[(J1) < 0 ? 0 : (J1)] + (size_t)(KP) * 64); \
+  } while (0)
+#define MOE355_W_ORDER(NW)                                                                         \
+  do {                                                                                             \
+    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);                                             \
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                             \
+    if ((NW) > 0) {                                                                                \
+      __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                        \
+      __builtin_amdgcn_sched_group_barrier(0x020, (NW), 0);                                        \
+    }                                                                                              \
+  } while (0)
+  {
+    const int kt_last = KT - 1;  // KT > kThinSteps >= 1
+    MOE355_W_LOAD(0, 0, 1, 0, -1); MOE355_W_LOAD(0, 2, 3, 1, -1); MOE355_W_LOAD(0, -1, -1, 2, 3);
+    MOE355_W_STORE(smem, 0, 1, 0, -1); MOE355_W_STORE(smem, 2, 3, 1, -1); MOE355_W_STORE(smem, -1, -1, 2, 3);
+    {
+      const int k1 = min(1, kt_last);
+      MOE355_W_LOAD(k1, 0, 1, 0, -1); MOE355_W_LOAD(k1, 2, 3, 1, -1); MOE355_W_LOAD(k1, -1, -1, 2, 3);
     }
     __syncthreads();
+    MOE355_W_READ(fa0, fb0, smem, 0);
     for (int kt = 0; kt < KT; ++kt) {
-      const unsigned char *st = smem + (kt & 1) * kStageBytes;
-      if (kt + 1 < KT) {  // uniform
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          ra[i] = *reinterpret_cast<const u32x4 *>(ap[i] + (size_t)(kt + 1) * 64);
-          rb[i] = *reinterpret_cast<const u32x4 *>(bp[i] + (size_t)(kt + 1) * 64);
-        }
-      }
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int slot = ((kk * 2 + khalf) ^ sw) * 16;
-        bf16x8 fa[4], fb[2];
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-          fa[mi] = *reinterpret_cast<const bf16x8 *>(st + (wm * 128 + mi * 32 + l31) * 128 + slot);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          fb[j] = *reinterpret_cast<const bf16x8 *>(st + 32768 + (wn * 64 + j * 32 + l31) * 128 + slot);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) {
-          acc[mi][0] = mfma_bf16(fa[mi], fb[0], acc[mi][0]);
-          acc[mi][1] = mfma_bf16(fa[mi], fb[1], acc[mi][1]);
-        }
-      }
-      if (kt + 1 < KT) {
-        unsigned char *nx = smem + ((kt + 1) & 1) * kStageBytes;  // last read before the previous barrier
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          *reinterpret_cast<u32x4 *>(nx + dst + 8192 * i) = ra[i];
-          *reinterpret_cast<u32x4 *>(nx + 32768 + dst + 8192 * i) = rb[i];
-        }
-      }
+      const unsigned char *cur = smem + (kt & 1) * kStageBytes;
+      unsigned char *nx = smem + ((kt & 1) ^ 1) * kStageBytes;
+      const int kp = min(kt + 2, kt_last);  // past the end: the last slab again (in bounds, never used)
+      MOE355_W_READ(fa1, fb1, cur, 1);
+      MOE355_W_MFMAS(fa0, fb0);
+      MOE355_W_STORE(nx, 0, 1, 0, -1);
+      MOE355_W_LOAD(kp, 0, 1, 0, -1);
+      MOE355_W_READ(fa0, fb0, cur, 2);
+      MOE355_W_MFMAS(fa1, fb1);
+      MOE355_W_STORE(nx, 2, 3, 1, -1);
+      MOE355_W_LOAD(kp, 2, 3, 1, -1);
+      MOE355_W_READ(fa1, fb1, cur, 3);
+      MOE355_W_MFMAS(fa0, fb0);
+      MOE355_W_STORE(nx, -1, -1, 2, 3);
+      MOE355_W_LOAD(kp, -1, -1, 2, 3);
+      MOE355_W_ORDER(3);
+      MOE355_W_ORDER(3);
+      MOE355_W_ORDER(2);
       __syncthreads();
+      MOE355_W_READ(fa0, fb0, nx, 0);
+      MOE355_W_MFMAS(fa1, fb1);
+      MOE355_W_ORDER(0);
     }
   }
+#undef MOE355_W_READ
+#undef MOE355_W_MFMAS
+#undef MOE355_W_STORE
+#undef MOE355_W_LOAD
+#undef MOE355_W_ORDER
   // epilogue: each wave turns its 32 x 64 blocks around through a private LDS patch (fp32, row pitch 288 bytes) so
   // that a row leaves as contiguous bf16
   __syncthreads();
@@ -196,6 +237,95 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
 #pragma unroll
         for (int q = 0; q < 4; ++q) o[q] = (bf16_t)v[q];
         *reinterpret_cast<bf16x4 *>(C + (size_t)m * a.N + n) = o;
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// Experts with 0 .. kThinSteps blocks of rows: 128 x 128 output tiles, 4 waves = 2 x 2, each 64 x 64; one LDS stage of
+// (A 128 x 64, B 128 x 64) = 32 KiB (the epilogue patches reuse it), so that several workgroups share a CU.
+// grid (n_mt * n_nt of 128-tiles, E_loc); a.n_mt / a.n_nt count 128-tiles here.
+__global__ __launch_bounds__(256) void wgrad_thin_bf16_kernel(const WgradArgs a) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * kPatchBytes];  // 36 KiB >= one 32 KiB stage
+  const int tid = threadIdx.x, lane = tid & 63, w4 = tid >> 6;
+  const int wm = w4 >> 1, wn = w4 & 1;
+  const int le = blockIdx.y;
+  const int mt = blockIdx.x / a.n_nt, nt = blockIdx.x % a.n_nt;
+  const int m0 = mt * 128, n0 = nt * 128;
+  const int kb0 = a.kb[le], KT = a.kb[le + 1] - kb0;
+  if (KT > kThinSteps) return;  // whole workgroup: wgrad_bf16_kernel owns this expert
+  const int chunk = tid & 7, row0 = tid >> 3;  // rows row0 + 32 i
+  const int l31 = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][j][r] = 0.f;
+  for (int kt = 0; kt < KT; ++kt) {
+    u32x4 ra[4], rb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const size_t koff = (size_t)(kb0 + kt) * 64 + chunk * 8;
+      ra[i] = *reinterpret_cast<const u32x4 *>(a.AT + (size_t)min(m0 + row0 + 32 * i, a.M - 1) * a.kpad + koff);
+      rb[i] = *reinterpret_cast<const u32x4 *>(a.BT + (size_t)min(n0 + row0 + 32 * i, a.N - 1) * a.kpad + koff);
+    }
+    if (kt > 0) __syncthreads();  // the previous step's fragment reads are done
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = row0 + 32 * i;
+      const int dst = (row * 8 + (chunk ^ ((row >> 1) & 7))) * 16;
+      *reinterpret_cast<u32x4 *>(smem + dst) = ra[i];
+      *reinterpret_cast<u32x4 *>(smem + 16384 + dst) = rb[i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const int slot = ((kk * 2 + khalf) ^ sw) * 16;
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        fa[q] = *reinterpret_cast<const bf16x8 *>(smem + (wm * 64 + q * 32 + l31) * 128 + slot);
+        fb[q] = *reinterpret_cast<const bf16x8 *>(smem + 16384 + (wn * 64 + q * 32 + l31) * 128 + slot);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) {
+        acc[mi][0] = mfma_bf16(fa[mi], fb[0], acc[mi][0]);
+        acc[mi][1] = mfma_bf16(fa[mi], fb[1], acc[mi][1]);
+      }
+    }
+  }
+  __syncthreads();  // the stage is dead: every wave takes a private patch
+  unsigned char *patch = smem + w4 * kPatchBytes;
+  bf16_t *C = a.C + (size_t)le * a.M * a.N;
+#pragma unroll
+  for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+      *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = acc[mi][0][r];
+      *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) = acc[mi][1][r];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int rl = it * 8 + (lane >> 3), cc = lane & 7;  // 8 groups of 8 columns per row: 16-byte stores
+      const int m = m0 + wm * 64 + mi * 32 + rl, n = n0 + wn * 64 + cc * 8;
+      const f32x4 v0 = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 32);
+      const f32x4 v1 = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 32 + 16);
+      if (m < a.M && n < a.N) {  // N % 8 == 0: the eight columns are inside together
+        bf16x8 o;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          o[q] = (bf16_t)v0[q];
+          o[4 + q] = (bf16_t)v1[q];
+        }
+        *reinterpret_cast<bf16x8 *>(C + (size_t)m * a.N + n) = o;
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");

@@ -189,3 +189,37 @@ def test_route_gate_arguments():
     assert lib.moe_route_topk_gate(C.byref(s), None, None, 1, fake, fake, None) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_route_topk_gate(C.byref(good_shape(k=9)), fake, None, 1, fake, fake, None) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_route_topk_gate(C.byref(good_shape(T=0)), fake, None, 1, fake, fake, None) == B.MOE_OK
+
+
+def test_training_entry_points_arguments():
+    lib = B.lib()
+    s = good_shape()
+    fake = 4096
+    tb = B.moe_dispatch(*([fake] * 9))
+    kept = B.moe_train_kept_bytes(s)
+    ws = B.moe_backward_workspace_bytes(s)
+    El = (s.local_rank_end - s.local_rank_begin) * (s.E // s.R)
+    rows = s.T * min(s.k, El)
+    assert kept >= rows * (2 * s.f * 2 + s.d * 4)           # g, u in bf16 and the weighted rows in fp32
+    assert ws >= rows * (3 * s.f * 2 + s.d * 4) + (2 * s.d + 3 * s.f) * rows * 2  # intermediates + transposed operands
+    assert B.moe_backward_packed_weight_bytes(s, 0) >= El * s.d * s.f * 2
+    assert B.moe_backward_packed_weight_bytes(s, 1) >= 2 * El * s.d * s.f * 2
+    assert B.moe_backward_packed_weight_bytes(s, 2) == 0
+    fwd_ws = B.moe_forward_workspace_bytes(s)
+    f_args = (C.byref(s), fake, fake, fake, C.byref(tb), fake, fake, fake)
+    assert lib.moe_fused_forward_train(*f_args, fake, kept - 1, fake, fwd_ws, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_fused_forward_train(*f_args, None, kept, fake, fwd_ws, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_fused_forward_train(*f_args, fake, kept, fake, fwd_ws - 1, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_fused_forward_train(C.byref(good_shape(dtype=B.MOE_F32)), fake, fake, fake, C.byref(tb), fake, fake,
+                                       fake, fake, 1 << 30, fake, 1 << 30, None) == B.MOE_ERR_UNSUPPORTED
+    b_args = (C.byref(s), fake, fake, fake, fake, C.byref(tb), fake, fake, fake, kept, fake, fake)
+    assert lib.moe_fused_backward(*b_args, None, None, None, fake, ws - 1, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_fused_backward(*b_args, fake, None, None, fake, ws, None) == B.MOE_ERR_INVALID_ARG  # all three or none
+    assert lib.moe_fused_backward(C.byref(s), fake, None, fake, fake, C.byref(tb), fake, fake, fake, kept, fake, fake,
+                                  None, None, None, fake, ws, None) == B.MOE_ERR_INVALID_ARG           # no dy
+    odd = good_shape(f=72)  # the backward needs whole 64-index reduction tiles over f
+    assert lib.moe_fused_backward(C.byref(odd), fake, fake, fake, fake, C.byref(tb), fake, fake, fake, 1 << 30, fake,
+                                  fake, None, None, None, fake, 1 << 30, None) == B.MOE_ERR_UNSUPPORTED
+    assert lib.moe_pack_weights_backward(C.byref(odd), fake, fake, fake, fake, fake, None) == B.MOE_ERR_UNSUPPORTED
+    assert lib.moe_pack_weights_backward(C.byref(s), fake, fake, None, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    # (T = 0 launches a fill for the weight gradients, or nothing without them: exercised on the GPU)

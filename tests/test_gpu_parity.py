@@ -753,3 +753,18 @@ def test_backward_full_size_sampled(oracle, name, nsample):
         assert lay.dW_gate[le].abs().max().item() == 0 and lay.dW_down[le].abs().max().item() == 0
     for t in (lay.dW_gate, lay.dW_up, lay.dW_down):
         assert torch.isfinite(t.float()).all()
+
+
+def test_backward_empty_layer_zeroes_the_weight_gradients():
+    import torch
+    cfg = cfg_of(T=0, d=64, f=64)
+    lay = L.MoELayer(cfg)
+    z = np.zeros((cfg.E_loc, 64, 64), np.uint16)
+    lay.load_weights(z, z, z)
+    lay.enable_training(z, z, z, wgrad=True)
+    for t in (lay.dW_gate, lay.dW_up, lay.dW_down):
+        t.fill_(float("nan"))
+    lay.forward_train(lay.y)   # any non-null pointers; T = 0 touches nothing
+    lay.backward(lay.y, lay.y)
+    torch.cuda.synchronize()
+    assert all(t.abs().max().item() == 0 for t in (lay.dW_gate, lay.dW_up, lay.dW_down))
