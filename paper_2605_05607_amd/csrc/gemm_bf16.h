@@ -304,24 +304,61 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   for (int mi = 0; mi < NB; ++mi) {
     const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
     if (!GATED && TRAIN) {
+      // This wave's 32 x 64 block of g and of u comes in through the LDS in 16-byte pieces (row pitch 144 bytes, g
+      // at 0, u at 4608 of a private 16 KiB region: the stages are dead), every lane replaces the elements it holds
+      // accumulators for by dg and du in place and puts w silu(g) u into a third block at 9216, and the three
+      // blocks leave in 16-byte pieces.
+      unsigned char *blk = smem + w8 * 16384;
       const bf16_t *gu = static_cast<const bf16_t *>(g.aux);
       bf16_t *dgu = static_cast<bf16_t *>(g.out), *hw = static_cast<bf16_t *>(g.aux2);
+      const int col0 = nt * kBN + wn * 64;
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int c = it * 64 + lane;  // 16-byte chunk: 8 chunks per row
+        const int rl = c >> 3, cc = c & 7;
+        const int row_l = blk_row0 + rl, col = col0 + cc * 8;
+        if (row_l < rows && col < g.N) {
+          const bf16_t *src = gu + (size_t)(m0 + row_l) * 2 * g.N + col;
+          *reinterpret_cast<u32x4 *>(blk + rl * 144 + cc * 16) = *reinterpret_cast<const u32x4 *>(src);
+          *reinterpret_cast<u32x4 *>(blk + 4608 + rl * 144 + cc * 16) = *reinterpret_cast<const u32x4 *>(src + g.N);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int col = nt * kBN + wn * 64 + j * 32 + l31;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row_l = blk_row0 + (r >> 2) * 8 + khalf * 4 + (r & 3);
-          if (row_l < rows && col < g.N) {
-            const size_t row = (size_t)(m0 + row_l);
-            const float wv = g.row_w[row];
-            const float gv = (float)gu[row * 2 * g.N + col], uv = (float)gu[row * 2 * g.N + g.N + col];
-            const float sg = 1.0f / (1.0f + __expf(-gv)), silu = gv * sg;
-            const float dh = wv * acc[mi][j][r];
-            dgu[row * 2 * g.N + col] = (bf16_t)(dh * uv * (sg * (1.0f + gv * (1.0f - sg))));
-            dgu[row * 2 * g.N + g.N + col] = (bf16_t)(dh * silu);
-            hw[row * g.N + col] = (bf16_t)(wv * silu * uv);
-          }
+          const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+          const int row_l = blk_row0 + rl;
+          bf16_t *pg = reinterpret_cast<bf16_t *>(blk + rl * 144 + (j * 32 + l31) * 2);
+          bf16_t *pu = reinterpret_cast<bf16_t *>(blk + 4608 + rl * 144 + (j * 32 + l31) * 2);
+          bf16_t *ph = reinterpret_cast<bf16_t *>(blk + 9216 + rl * 144 + (j * 32 + l31) * 2);
+          const bool in = row_l < rows && col0 + j * 32 + l31 < g.N;  // outside: never stored, keep the math finite
+          const float wv = in ? g.row_w[m0 + row_l] : 0.f;
+          const float gv = in ? (float)*pg : 0.f, uv = in ? (float)*pu : 0.f;
+          const float sg = 1.0f / (1.0f + __expf(-gv)), silu = gv * sg;
+          const float dh = wv * acc[mi][j][r];
+          *pg = (bf16_t)(dh * uv * (sg * (1.0f + gv * (1.0f - sg))));
+          *pu = (bf16_t)(dh * silu);
+          *ph = (bf16_t)(wv * silu * uv);
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int it = 0; it < 4; ++it) {
+        const int c = it * 64 + lane;
+        const int rl = c >> 3, cc = c & 7;
+        const int row_l = blk_row0 + rl, col = col0 + cc * 8;
+        if (row_l < rows && col < g.N) {
+          bf16_t *dst = dgu + (size_t)(m0 + row_l) * 2 * g.N + col;
+          *reinterpret_cast<u32x4 *>(dst) = *reinterpret_cast<const u32x4 *>(blk + rl * 144 + cc * 16);
+          *reinterpret_cast<u32x4 *>(dst + g.N) = *reinterpret_cast<const u32x4 *>(blk + 4608 + rl * 144 + cc * 16);
+          *reinterpret_cast<u32x4 *>(hw + (size_t)(m0 + row_l) * g.N + col) =
+              *reinterpret_cast<const u32x4 *>(blk + 9216 + rl * 144 + cc * 16);
         }
       }
     } else if (GATED && FP8) {
@@ -351,19 +388,16 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
           *reinterpret_cast<u32x4 *>(static_cast<uint8_t *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
       }
     } else if (GATED) {
-      // h block: 32 rows x 32 columns bf16, row pitch 80 bytes (keeps the two half-waves on different banks)
+      // h block: 32 rows x 32 columns bf16, row pitch 80 bytes (keeps the two half-waves on different banks);
+      // TRAIN: two more such blocks for g and u, 2560 bytes apart
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const float gv = acc[mi][0][r], uv = acc[mi][1][r];
         *reinterpret_cast<bf16_t *>(patch + rl * 80 + l31 * 2) = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
         if (TRAIN) {
-          const int row_l = blk_row0 + rl, col_h = nt * (kBN / 2) + wn * 32 + l31;
-          if (row_l < rows && col_h < g.N) {
-            bf16_t *gu = static_cast<bf16_t *>(g.aux) + (size_t)(m0 + row_l) * 2 * g.N;
-            gu[col_h] = (bf16_t)gv;
-            gu[g.N + col_h] = (bf16_t)uv;
-          }
+          *reinterpret_cast<bf16_t *>(patch + 2560 + rl * 80 + l31 * 2) = (bf16_t)gv;
+          *reinterpret_cast<bf16_t *>(patch + 5120 + rl * 80 + l31 * 2) = (bf16_t)uv;
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -376,8 +410,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         const int row_l = blk_row0 + rl;
         const int col = nt * (kBN / 2) + wn * 32 + cc * 8;
         const u32x4 v = *reinterpret_cast<const u32x4 *>(patch + rl * 80 + cc * 16);
-        if (row_l < rows && col < g.N)
+        if (row_l < rows && col < g.N) {
           *reinterpret_cast<u32x4 *>(static_cast<bf16_t *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
+          if (TRAIN) {
+            bf16_t *gu = static_cast<bf16_t *>(g.aux) + (size_t)(m0 + row_l) * 2 * g.N + col;
+            *reinterpret_cast<u32x4 *>(gu) = *reinterpret_cast<const u32x4 *>(patch + 2560 + rl * 80 + cc * 16);
+            *reinterpret_cast<u32x4 *>(gu + g.N) = *reinterpret_cast<const u32x4 *>(patch + 5120 + rl * 80 + cc * 16);
+          }
+        }
       }
     } else {
       // o block: 32 rows x 64 columns fp32, row pitch 288 bytes.  A row whose token has no other local slot
