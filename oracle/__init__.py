@@ -329,3 +329,16 @@ def backward_weights(x, dy, topk_idx, topk_w, W_gate, W_up, W_down, E: int, R: i
                                            _p(topk_idx), _p(topk_w), _p(W_gate), _p(W_up), _p(W_down), le, n0, n1,
                                            _p(dWg), _p(dWu), _p(dWd)), "backward_weights")
     return dWg, dWu, dWd
+
+
+def route_backward(logits: np.ndarray, topk_idx: np.ndarray, d_topk_w: np.ndarray) -> np.ndarray:
+    """Gradient of the logits [T, E] (float64) from the gradient of the routing weights [T, k] of route_topk."""
+    logits = np.ascontiguousarray(logits, dtype=np.float32)
+    topk_idx = np.ascontiguousarray(topk_idx, dtype=np.int32)
+    dw = np.ascontiguousarray(d_topk_w, dtype=np.float64)
+    T, E = logits.shape
+    k = topk_idx.shape[1]
+    assert dw.shape == (T, k)
+    out = np.empty((T, E), dtype=np.float64)
+    _check(_lib().moe_oracle_route_backward(T, E, k, _p(logits), _p(topk_idx), _p(dw), _p(out)), "route_backward")
+    return out

@@ -586,3 +586,34 @@ int moe_oracle_backward_weights(int T, int d, int f, int E, int k, int R, int lr
   free(g); free(u);
   return ORACLE_OK;
 }
+
+/*
+ * Backward of the routing weights of moe_oracle_route_topk (softmax over the logits, renormalised over the picks,
+ * i.e. a softmax over the k picked logits): with w_j the weights and dw_j the incoming gradients of token t,
+ *   dlogit[e_j] = w_j * (dw_j - sum_i w_i dw_i),   0 for the experts that were not picked
+ * (the selection itself is piecewise constant).  dlogits is [T, E] in double; the weights are recomputed from the
+ * logits in double.
+ */
+int moe_oracle_route_backward(int T, int E, int k, const float *logits, const int32_t *topk_idx, const double *dw,
+                              double *dlogits) {
+  if (T < 0 || E < 1 || k < 1 || k > E || !logits || !topk_idx || !dw || !dlogits) return ORACLE_BAD_ARG;
+  for (int t = 0; t < T; ++t) {
+    const float *row = logits + (size_t)t * E;
+    for (int e = 0; e < E; ++e) dlogits[(size_t)t * E + e] = 0.0;
+    double m = -INFINITY, sum = 0.0, dot = 0.0;
+    for (int j = 0; j < k; ++j) {
+      const int e = topk_idx[(size_t)t * k + j];
+      if (e < 0 || e >= E) return ORACLE_BAD_ARG;
+      if ((double)row[e] > m) m = (double)row[e];
+    }
+    for (int j = 0; j < k; ++j) sum += exp((double)row[topk_idx[(size_t)t * k + j]] - m);
+    for (int j = 0; j < k; ++j)
+      dot += exp((double)row[topk_idx[(size_t)t * k + j]] - m) / sum * dw[(size_t)t * k + j];
+    for (int j = 0; j < k; ++j) {
+      const int e = topk_idx[(size_t)t * k + j];
+      const double w = exp((double)row[e] - m) / sum;
+      dlogits[(size_t)t * E + e] = w * (dw[(size_t)t * k + j] - dot);
+    }
+  }
+  return ORACLE_OK;
+}

@@ -582,3 +582,39 @@ def test_backward_local_slots_only_and_ranges(oracle):
     o = oracle.forward(w.x, idx, one, w.W_gate, w.W_up, w.W_down, cfg.E, cfg.R, *lr, tokens=np.array([t], np.int32))[0]
     dyf = wl.bf16_bits_to_f32(dy) if dy.dtype == np.uint16 else dy
     np.testing.assert_allclose(dw[t, j], float((o * dyf[t].astype(np.float64)).sum()), rtol=1e-10)
+
+
+def test_route_backward_vs_finite_differences_and_closed_form(oracle):
+    rng = np.random.default_rng(50)
+    T, E, k = 9, 12, 4
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    idx, w = oracle.route_topk(logits, k)
+    dw = rng.standard_normal((T, k))
+    dl = oracle.route_backward(logits, idx, dw)
+    # closed form through the full Jacobian of a softmax over the picked logits (NumPy, float64)
+    for t in range(T):
+        l = logits[t, idx[t]].astype(np.float64)
+        p = np.exp(l - l.max())
+        p /= p.sum()
+        J = np.diag(p) - np.outer(p, p)
+        want = np.zeros(E)
+        want[idx[t]] = J @ dw[t]
+        np.testing.assert_allclose(dl[t], want, rtol=1e-12, atol=1e-15)
+    # central differences of the routing weights themselves (picks unchanged for a small step)
+    eps = np.float32(2.0 ** -9)
+    for _ in range(10):
+        t, e = int(rng.integers(0, T)), int(rng.integers(0, E))
+        a, b = logits.copy(), logits.copy()
+        a[t, e] += eps
+        b[t, e] -= eps
+        ia, wa = oracle.route_topk(a, k)
+        ib, wb = oracle.route_topk(b, k)
+        if not (np.array_equal(ia[t], idx[t]) and np.array_equal(ib[t], idx[t])):
+            continue
+        want = float(((wa[t].astype(np.float64) - wb[t].astype(np.float64)) * dw[t]).sum()) / float(a[t, e] - b[t, e])
+        assert abs(dl[t, e] - want) <= 2e-4 * (1 + abs(want))  # the weights are stored in fp32
+    # the gradients of a row sum to zero (the weights sum to one) and vanish off the picks
+    np.testing.assert_allclose(dl.sum(axis=1), 0.0, atol=1e-14)
+    mask = np.zeros((T, E), bool)
+    np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
+    assert np.all(dl[~mask] == 0)
