@@ -287,6 +287,14 @@ MOE355_API int moe_fused_backward(const moe_shape *shape, const void *x, const v
                                   float *d_topk_w, void *dW_gate, void *dW_up, void *dW_down, void *workspace,
                                   size_t workspace_bytes, void *stream);
 
+/*
+ * Backward of moe_route_topk's weights (a softmax over the k picked logits; the selection is piecewise constant):
+ * dlogits [T,E] fp32 (written in full) = w_j (d_topk_w_j - sum_i w_i d_topk_w_i) at the picked experts, 0 elsewhere.
+ * topk_idx, topk_w as written by moe_route_topk; d_topk_w [T,k] fp32, e.g. from moe_fused_backward.
+ */
+MOE355_API int moe_route_backward(const moe_shape *shape, const int32_t *topk_idx, const float *topk_w,
+                                  const float *d_topk_w, float *dlogits, void *stream);
+
 /* Static string for a status code. */
 MOE355_API const char *moe_status_string(int status);
 

@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
             fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
         L.moe_route_topk_gate.restype = i32
         L.moe_route_topk_gate.argtypes = [sp, vp, vp, i32, vp, vp, vp]
+        L.moe_route_backward.restype = i32
+        L.moe_route_backward.argtypes = [sp, vp, vp, vp, vp, vp]
         L.moe_fp8_packed_weight_bytes.restype = sz
         L.moe_fp8_packed_weight_bytes.argtypes = [sp, i32]
         L.moe_fp8_forward_workspace_bytes.restype = sz
@@ -271,6 +273,11 @@ MOE_GATE_SIGMOID = 1
 def moe_route_topk_gate(shape, logits, bias, gate, topk_idx, topk_w, stream=None) -> None:
     _check(lib().moe_route_topk_gate(C.byref(shape), _ptr(logits), _ptr(bias), int(gate), _ptr(topk_idx),
                                      _ptr(topk_w), _stream(stream)), "moe_route_topk_gate")
+
+
+def moe_route_backward(shape, topk_idx, topk_w, d_topk_w, dlogits, stream=None) -> None:
+    _check(lib().moe_route_backward(C.byref(shape), _ptr(topk_idx), _ptr(topk_w), _ptr(d_topk_w), _ptr(dlogits),
+                                    _stream(stream)), "moe_route_backward")
 
 
 def moe_fp8_packed_weight_bytes(shape: moe_shape, which: int) -> int:

@@ -219,6 +219,34 @@ __global__ __launch_bounds__(kRouteWaves * kWave) void route_topk_gate_kernel(co
   }
 }
 
+// Backward of moe_route_topk's weights: they are a softmax over the k picked logits, so for token t
+//   dlogits[t][e_j] = w_j (dw_j - sum_i w_i dw_i),  0 for the experts that were not picked.
+// One wave per token; the row of dlogits is zeroed by the wave, then the k lanes that hold a pick write theirs.
+__global__ __launch_bounds__(256) void route_backward_kernel(const int32_t *__restrict__ topk_idx,
+                                                             const float *__restrict__ topk_w,
+                                                             const float *__restrict__ d_topk_w,
+                                                             float *__restrict__ dlogits, int T, int E, int k) {
+  const int lane = lane_id();
+  const int t = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (t >= T) return;  // whole wave
+  float *row = dlogits + (size_t)t * E;
+  for (int e = lane; e < E; e += kWave) row[e] = 0.f;
+  const float w = lane < k ? topk_w[(size_t)t * k + lane] : 0.f;
+  const float dw = lane < k ? d_topk_w[(size_t)t * k + lane] : 0.f;
+  float dot = 0.f;
+  for (int j = 0; j < k; ++j)  // slot order, the same sum in every lane
+    dot = fmaf(__shfl(w, j), __shfl(dw, j), dot);
+  // the zeros above and the values below come from different lanes of this wave: order them
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // the zero stores have been acknowledged (vmcnt(0))
+  if (lane < k) {
+    const int e = topk_idx[(size_t)t * k + lane];
+    if (e >= 0 && e < E) row[e] = w * (dw - dot);
+  }
+}
+
 }  // namespace moe355
 
 using namespace moe355;
@@ -267,5 +295,18 @@ extern "C" int moe_route_topk_gate(const moe_shape *shape, const float *logits, 
   while (waves > 1 && waves * per_wave > 48 * 1024) waves >>= 1;
   hipLaunchKernelGGL(route_topk_gate_kernel, dim3(ceil_div(shape->T, waves)), dim3(waves * kWave), waves * per_wave,
                      (hipStream_t)stream, logits, bias, gate, topk_idx, topk_w, shape->T, shape->E, shape->k);
+  return launch_status();
+}
+
+extern "C" int moe_route_backward(const moe_shape *shape, const int32_t *topk_idx, const float *topk_w,
+                                  const float *d_topk_w, float *dlogits, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!topk_idx || !topk_w || !d_topk_w || !dlogits) return MOE_ERR_INVALID_ARG;
+  if (shape->T == 0) return MOE_OK;
+  begin_launches();
+  hipLaunchKernelGGL(route_backward_kernel, dim3(ceil_div(shape->T, 4)), dim3(256), 0, (hipStream_t)stream, topk_idx,
+                     topk_w, d_topk_w, dlogits, shape->T, shape->E, shape->k);
   return launch_status();
 }

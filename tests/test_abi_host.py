@@ -223,3 +223,13 @@ def test_training_entry_points_arguments():
     assert lib.moe_pack_weights_backward(C.byref(odd), fake, fake, fake, fake, fake, None) == B.MOE_ERR_UNSUPPORTED
     assert lib.moe_pack_weights_backward(C.byref(s), fake, fake, None, fake, fake, None) == B.MOE_ERR_INVALID_ARG
     # (T = 0 launches a fill for the weight gradients, or nothing without them: exercised on the GPU)
+
+
+def test_route_backward_arguments():
+    lib = B.lib()
+    s = good_shape()
+    fake = 4096
+    assert lib.moe_route_backward(C.byref(s), fake, fake, None, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_backward(C.byref(s), fake, fake, fake, None, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_backward(None, fake, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_backward(C.byref(good_shape(T=0)), fake, fake, fake, fake, None) == B.MOE_OK

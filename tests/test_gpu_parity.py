@@ -768,3 +768,25 @@ def test_backward_empty_layer_zeroes_the_weight_gradients():
     lay.backward(lay.y, lay.y)
     torch.cuda.synchronize()
     assert all(t.abs().max().item() == 0 for t in (lay.dW_gate, lay.dW_up, lay.dW_down))
+
+
+@pytest.mark.parametrize("T,E,k", [(1, 4, 2), (257, 256, 8), (300, 64, 1), (129, 640, 32), (4096, 256, 8)])
+def test_route_backward(oracle, T, E, k):
+    import torch
+    say(f"route backward T={T} E={E} k={k}")
+    rng = np.random.default_rng(T + E + k)
+    logits = rng.standard_normal((T, E)).astype(np.float32) * 2
+    dw = rng.standard_normal((T, k)).astype(np.float32)
+    cfg = cfg_of(T=T, E=E, k=k, R=1, d=8, f=8, local_rank_begin=0, local_rank_end=1)
+    lay, got = G.run_tables(cfg, logits)
+    idx, w = oracle.route_topk(logits, k)
+    assert np.array_equal(got["topk_idx"].reshape(T, k), idx)
+    dl = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda")
+    B.moe_route_backward(lay.shape, lay.topk_idx, lay.topk_w, L.to_device(dw), dl)
+    torch.cuda.synchronize()
+    ref = oracle.route_backward(logits, idx, dw.astype(np.float64))
+    out = dl.cpu().numpy().astype(np.float64)
+    mask = np.zeros((T, E), bool)
+    np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
+    assert np.all(out[~mask] == 0)
+    assert np.abs(out - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())  # fp32 weights and sums of k <= 32 terms
