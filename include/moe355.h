@@ -262,6 +262,7 @@ MOE355_API int moe_fp8_fused_forward(const moe_shape *shape, const void *x, cons
  *
  * moe_fused_forward_train: moe_fused_forward that also keeps g, u (bf16) and every weighted expert output row (fp32)
  *   in `kept` (caller-owned, >= moe_train_kept_bytes(shape), 256-byte aligned), which the backward call reads.
+ *   The two GEMMs run as one or two launches by the rule of moe_forward_gemm_launches.
  * moe_pack_weights_backward: one-off; the transposed uses of the weights in the layout the GEMM kernels stream:
  *   packed_down_t (W_down^T) and packed_gate_up_t ([W_gate^T ; W_up^T]), moe_backward_packed_weight_bytes(shape, 0 / 1)
  *   bytes, 16-byte aligned.  Inputs as for moe_pack_weights.

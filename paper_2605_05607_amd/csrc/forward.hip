@@ -136,8 +136,16 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
       PipelineArgs pa;
       pa.g1 = g1; pa.g2 = g2;
       pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1;
-      hipLaunchKernelGGL(gemm_bf16_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
-                         pa);
+      if (keep_gu) {
+        static std::atomic<uint64_t> done_tp{0};
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_train_pipeline_kernel), 2 * kStageBytes, done_tp))
+          return MOE_ERR_HIP;
+        hipLaunchKernelGGL(gemm_train_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
+                           pa);
+      } else {
+        hipLaunchKernelGGL(gemm_bf16_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
+                           pa);
+      }
       mark(2);
       mark(3);
       return launch_status();
@@ -548,7 +556,7 @@ extern "C" int moe_fused_forward_train(const moe_shape *shape, const void *x, co
   if (!kept || kept_bytes < moe_train_kept_bytes(shape)) return MOE_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(kept) % 256 != 0) return MOE_ERR_INVALID_ARG;
   return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
-                        workspace_bytes, stream, true, nullptr, 2, nullptr, kept);
+                        workspace_bytes, stream, true, nullptr, 0, nullptr, kept);
 }
 
 extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const void *dy, const int32_t *topk_idx,

@@ -533,7 +533,7 @@ struct PipelineArgs {
 constexpr int kMaxPolls = 1 << 22;  // x ~1 us: a bound so that no wave can wait forever
 
 // All items of one GEMM that this workgroup can get hold of: home queue first, then the other queues.
-template <bool GATED, bool FP8 = false>
+template <bool GATED, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char *smem, int *s_item,
                                                 int32_t *__restrict__ tickets, int32_t *__restrict__ tile_ready,
                                                 int32_t *__restrict__ error, int nt1) {
@@ -580,7 +580,7 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
     const int4 item = g.work[q];
     const int tile = item.w >> kTileShift;
     if (GATED) {
-      gemm_bf16_item<true, true, FP8>(g, smem, item);
+      gemm_bf16_item<true, true, FP8, TRAIN>(g, smem, item);
       // every wave first waits until its own h stores have been acknowledged (vmcnt(0); gfx9 encoding with the
       // other counters left at their maxima), so that the one write-back below cannot overtake any of them
       __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -616,6 +616,14 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(con
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
   __shared__ int s_item;
   gemm_bf16_drain<true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
+  gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
+}
+
+// The same resident kernel for the training forward: GEMM-1 also keeps g and u.
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_train_pipeline_kernel(const PipelineArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  __shared__ int s_item;
+  gemm_bf16_drain<true, false, true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
   gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
 }
 
