@@ -451,12 +451,12 @@ struct BwdLayout {
   size_t dgu;    // bf16 [P_cap, 2 f]  dg, then du
   size_t hw;     // bf16 [P_cap, f]    w silu(g) u
   size_t dxr;    // float[P_cap, d]    rows of dx before the per-token sum
-  // weight gradients: operands transposed to [column][row] with every expert's rows padded to a multiple of 64
-  size_t kb;     // int32[E_loc + 1]   first 64-row block of every local expert in the padded row order
-  size_t xT, dyT;  // bf16 [d][kpad]   gathered x rows, gathered dy rows
-  size_t hwT;    // bf16 [f][kpad]
-  size_t dguT;   // bf16 [2 f][kpad]
-  size_t kpad;   // padded row capacity (elements): 64 (ceil(P_cap / 64) + E_loc)
+  // weight gradients: operands transposed to [64-row block][column][64 rows], every expert's rows padded to blocks
+  size_t kb;     // int32[E_loc + 1]   first block of every local expert in the padded row order
+  size_t xT, dyT;  // bf16 [blocks][d][64]   gathered x rows, gathered dy rows
+  size_t hwT;    // bf16 [blocks][f][64]
+  size_t dguT;   // bf16 [blocks][2 f][64]
+  size_t kpad;   // padded row capacity: 64 (ceil(P_cap / 64) + E_loc)
   size_t total;
 };
 
@@ -653,24 +653,25 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   hipLaunchKernelGGL(wgrad_blocks_kernel, dim3(1), dim3(256), 0, st, tables->offsets, w.header, dv.e_lo, dv.E_loc, kb);
   const auto transpose = [&](const bf16_t *src, const int32_t *map, int ld, int C, bf16_t *dst) {
     hipLaunchKernelGGL(gather_transpose_kernel, dim3(ceil_div(C, 64), kblocks), dim3(256), 0, st, src, map, ld, 0, C,
-                       tables->offsets, w.header, kb, dv.e_lo, dv.E_loc, dst, L.kpad);
+                       tables->offsets, w.header, kb, dv.e_lo, dv.E_loc, dst);
   };
   transpose(static_cast<const bf16_t *>(x), w.row_tok, shape->d, shape->d, xT);
   transpose(static_cast<const bf16_t *>(dy), w.row_tok, shape->d, shape->d, dyT);
   transpose(hw, nullptr, shape->f, shape->f, hwT);
   transpose(dgu, nullptr, 2 * shape->f, 2 * shape->f, dguT);
   if ((rc = launch_status()) != MOE_OK) return rc;
-  const auto product = [&](const bf16_t *AT, const bf16_t *BT, int M, int N, void *C) {
+  const auto product = [&](const bf16_t *AT, int lda, const bf16_t *BT, int ldb, int b0, int M, int N, void *C) {
     WgradArgs a;
-    a.AT = AT; a.BT = BT; a.C = static_cast<bf16_t *>(C); a.kb = kb; a.kpad = L.kpad;
+    a.AT = AT; a.BT = BT; a.C = static_cast<bf16_t *>(C); a.kb = kb;
+    a.lda = lda; a.ldb = ldb; a.a0 = 0; a.b0 = b0;
     a.M = M; a.N = N; a.n_mt = ceil_div(M, kBM); a.n_nt = ceil_div(N, kBN);
     hipLaunchKernelGGL(wgrad_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(kGemmThreads), 2 * kStageBytes, st, a);
     a.n_mt = ceil_div(M, 128); a.n_nt = ceil_div(N, 128);  // experts with few or no rows: small tiles
     hipLaunchKernelGGL(wgrad_thin_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(256), 0, st, a);
   };
-  product(xT, dguT, shape->d, shape->f, dW_gate);                                  // x^T dg
-  product(xT, dguT + (size_t)shape->f * L.kpad, shape->d, shape->f, dW_up);       // x^T du
-  product(hwT, dyT, shape->f, shape->d, dW_down);                                  // (w h)^T dy
+  product(xT, shape->d, dguT, 2 * shape->f, 0, shape->d, shape->f, dW_gate);         // x^T dg
+  product(xT, shape->d, dguT, 2 * shape->f, shape->f, shape->d, shape->f, dW_up);    // x^T du
+  product(hwT, shape->f, dyT, shape->d, 0, shape->f, shape->d, dW_down);             // (w h)^T dy
   return launch_status();
 }
 

@@ -1,9 +1,10 @@
 // Weight gradients of the expert FFN on the matrix cores: for every local expert, C = A^T B summed over the expert's
 // rows (dW_gate = x^T dg, dW_up = x^T du, dW_down = (w h)^T dy).  The reduction index is the row, which is the slow
 // index of both operands in memory, while a matrix-core operand wants 8 consecutive reduction indices per lane; so
-// the operands are first transposed (and gathered: x and dy rows are fetched by token) into [column][row] buffers
-// in which every expert's rows start at a multiple of 64 and are zero-padded to a multiple of 64.  The GEMM then is
-// the forward tile's main loop with both operands staged like its A operand.
+// the operands are first transposed (and gathered: x and dy rows are fetched by token) into buffers of 64-row blocks,
+// [block][column][64 rows], in which every expert's rows start at a block boundary and are zero-padded to one: what
+// a workgroup stages per k-step is then one contiguous piece of memory per operand.  The GEMM is the forward tile's
+// main loop with both operands staged like its A operand.
 #pragma once
 #include "gemm_bf16.h"
 
@@ -32,14 +33,14 @@ __global__ __launch_bounds__(256) void wgrad_blocks_kernel(const int32_t *__rest
   if (threadIdx.x == 0) kb[E_loc] = total;
 }
 
-// dst[c][64 b + i] = src[row(r)][c0 + c] for the i-th row r of padded block b (zero where the block is padded),
-// c < C.  src rows have pitch ld; row(r) = row_map[r] or r.  dst has pitch kpad.  grid (ceil(C / 64), block cap).
+// dst[b][c][i] = src[row(r)][c0 + c] for the i-th row r of padded block b (zero where the block is padded), c < C,
+// i < 64.  src rows have pitch ld; row(r) = row_map[r] or r.  grid (ceil(C / 64), block cap).
 __global__ __launch_bounds__(256) void gather_transpose_kernel(const bf16_t *__restrict__ src,
                                                                const int32_t *__restrict__ row_map, int ld, int c0,
                                                                int C, const int32_t *__restrict__ offsets,
                                                                const int32_t *__restrict__ header,
                                                                const int32_t *__restrict__ kb, int e_lo, int E_loc,
-                                                               bf16_t *__restrict__ dst, size_t kpad) {
+                                                               bf16_t *__restrict__ dst) {
   __shared__ uint16_t tile[64][66];  // [row][column], 33 words per row: column reads hit distinct banks
   const int b = blockIdx.y;
   if (b >= kb[E_loc]) return;
@@ -79,16 +80,16 @@ __global__ __launch_bounds__(256) void gather_transpose_kernel(const bf16_t *__r
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       v[q] = (uint32_t)tile[ch * 8 + 2 * q][cl] | ((uint32_t)tile[ch * 8 + 2 * q + 1][cl] << 16);
-    *reinterpret_cast<u32x4 *>(dst + (size_t)(cblk + cl) * kpad + (size_t)b * 64 + ch * 8) = v;
+    *reinterpret_cast<u32x4 *>(dst + ((size_t)b * C + cblk + cl) * 64 + ch * 8) = v;
   }
 }
 
 struct WgradArgs {
-  const bf16_t *AT;   // [M][kpad]  transposed left operand (rows = columns of the original row-major operand)
-  const bf16_t *BT;   // [N][kpad]
+  const bf16_t *AT;   // [block][lda][64]: rows a0 .. a0 + M of every block are the left operand's columns
+  const bf16_t *BT;   // [block][ldb][64]: rows b0 .. b0 + N
   bf16_t *C;          // [E_loc][M][N]
   const int32_t *kb;  // [E_loc + 1]
-  size_t kpad;
+  int lda, ldb, a0, b0;
   int M, N, n_mt, n_nt;
 };
 
@@ -113,10 +114,11 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
   const bf16_t *ap[4], *bp[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    ap[i] = a.AT + (size_t)min(m0 + row0 + 64 * i, a.M - 1) * a.kpad + (size_t)kb0 * 64 + chunk * 8;
-    bp[i] = a.BT + (size_t)min(n0 + row0 + 64 * i, a.N - 1) * a.kpad + (size_t)kb0 * 64 + chunk * 8;
+    ap[i] = a.AT + ((size_t)kb0 * a.lda + a.a0 + min(m0 + row0 + 64 * i, a.M - 1)) * 64 + chunk * 8;
+    bp[i] = a.BT + ((size_t)kb0 * a.ldb + a.b0 + min(n0 + row0 + 64 * i, a.N - 1)) * 64 + chunk * 8;
   }
   const int dst = (row0 * 8 + (chunk ^ ((row0 >> 1) & 7))) * 16;  // + 8192 per 64 rows; B stage 32768 further
+  const size_t a_step = (size_t)a.lda * 64, b_step = (size_t)a.ldb * 64;  // elements from one block to the next
   u32x4 ra[4], rb[4];
 
   f32x16 acc[4][2];
@@ -157,10 +159,10 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
   } while (0)
 #define MOE355_W_LOAD(KP, I0, I1, J0, J1)                                                          \
   do {                                                                                             \
-    if ((I0) >= 0) ra[(I0) < 0 ? 0 : (I0)] = *reinterpret_cast<const u32x4 *>(ap[(I0) < 0 ? 0 : (I0)] + (size_t)(KP) * 64); \
-    if ((I1) >= 0) ra[(I1) < 0 ? 0 : (I1)] = *reinterpret_cast<const u32x4 *>(ap[(I1) < 0 ? 0 : (I1)] + (size_t)(KP) * 64); \
-    rb[(J0)] = *reinterpret_cast<const u32x4 *>(bp[(J0)] + (size_t)(KP) * 64);                     \
-    if ((J1) >= 0) rb[(J1) < 0 ? 0 : (J1)] = *reinterpret_cast<const u32x4 *>(bp[(J1) < 0 ? 0 : (J1)] + (size_t)(KP) * 64); \
+    if ((I0) >= 0) ra[(I0) < 0 ? 0 : (I0)] = *reinterpret_cast<const u32x4 *>(ap[(I0) < 0 ? 0 : (I0)] + (size_t)(KP) * a_step); \
+    if ((I1) >= 0) ra[(I1) < 0 ? 0 : (I1)] = *reinterpret_cast<const u32x4 *>(ap[(I1) < 0 ? 0 : (I1)] + (size_t)(KP) * a_step); \
+    rb[(J0)] = *reinterpret_cast<const u32x4 *>(bp[(J0)] + (size_t)(KP) * b_step);                 \
+    if ((J1) >= 0) rb[(J1) < 0 ? 0 : (J1)] = *reinterpret_cast<const u32x4 *>(bp[(J1) < 0 ? 0 : (J1)] + (size_t)(KP) * b_step); \
   } while (0)
 #define MOE355_W_ORDER(NW)                                                                         \
   do {                                                                                             \
@@ -269,9 +271,11 @@ __global__ __launch_bounds__(256) void wgrad_thin_bf16_kernel(const WgradArgs a)
     u32x4 ra[4], rb[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const size_t koff = (size_t)(kb0 + kt) * 64 + chunk * 8;
-      ra[i] = *reinterpret_cast<const u32x4 *>(a.AT + (size_t)min(m0 + row0 + 32 * i, a.M - 1) * a.kpad + koff);
-      rb[i] = *reinterpret_cast<const u32x4 *>(a.BT + (size_t)min(n0 + row0 + 32 * i, a.N - 1) * a.kpad + koff);
+      const size_t blk = (size_t)(kb0 + kt);
+      ra[i] = *reinterpret_cast<const u32x4 *>(
+          a.AT + (blk * a.lda + a.a0 + min(m0 + row0 + 32 * i, a.M - 1)) * 64 + chunk * 8);
+      rb[i] = *reinterpret_cast<const u32x4 *>(
+          a.BT + (blk * a.ldb + a.b0 + min(n0 + row0 + 32 * i, a.N - 1)) * 64 + chunk * 8);
     }
     if (kt > 0) __syncthreads();  // the previous step's fragment reads are done
 #pragma unroll
