@@ -122,7 +122,14 @@ def test_forward_matches_oracle_small(oracle, name):
                                 dict(R=1, local_rank_begin=0, local_rank_end=1),
                                 dict(R=16, local_rank_begin=3, local_rank_end=4),
                                 dict(T=129, E=2, k=1, R=2, local_rank_begin=1, local_rank_end=2),
-                                dict(T=257, E=1, k=1, R=1, local_rank_begin=0, local_rank_end=1, d=64, f=64)])
+                                dict(T=257, E=1, k=1, R=1, local_rank_begin=0, local_rank_end=1, d=64, f=64),
+                                # many local experts: the tile table's per-expert scans, its rank sort (up to 1024
+                                # experts) and the expert-order fallback beyond
+                                dict(T=600, E=512, k=4, R=1, local_rank_begin=0, local_rank_end=1, d=64, f=64),
+                                dict(T=900, E=2048, k=3, R=2, local_rank_begin=0, local_rank_end=2, d=64, f=64,
+                                     router="zipf"),
+                                dict(T=3000, E=4096, k=2, R=4096, local_rank_begin=100, local_rank_end=1400, d=32,
+                                     f=32)])
 def test_forward_edge_shapes(oracle, kw):
     cfg = cfg_of(**kw)
     say(f"forward edge {kw}")
@@ -613,6 +620,8 @@ BWD_SMALL = {
     "table1_like_k16": SMALL["table1_like_k16"],
     # 80 pairs over 64 experts: many local experts without a row (their gradients are zero), others with one or two
     "empty_experts": cfg_of(T=40, d=64, f=64, E=64, k=2, R=2, local_rank_begin=0, local_rank_end=1, seed=42),
+    # several hundred local experts: the block scan and the block -> expert search of the weight-gradient path
+    "many_experts": cfg_of(T=500, d=64, f=64, E=512, k=4, R=1, local_rank_begin=0, local_rank_end=1, seed=43),
 }
 
 
