@@ -248,7 +248,7 @@ def main():
     roof["algorithmic"] = gk["bytes"] if roof["bound"] == "hbm" else gk["flops"]
     roof["kernel"] = ("gemm_bf16_pipeline_kernel (gathered gate/up GEMM + SwiGLU, then down GEMM x gate weight, one "
                       "launch)" if one_launch else
-                      ("gemm_bf16_kernel<true, false>" if cfg.dtype == wl.BF16 else "gemm_f32_kernel<true>")
+                      ("gemm_bf16_kernel<true, false, false>" if cfg.dtype == wl.BF16 else "gemm_f32_kernel<true>")
                       + " (GEMM-1: gathered gate/up GEMM + SwiGLU)")
     roof["avg_launch_ms"] = gk_ms
     roof["launches_sampled"] = n_sampled
