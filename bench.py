@@ -153,7 +153,8 @@ def timed_value(lay, lg, x, K, ev_first, ev_last, every):
             lay.forward(x)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    return wall * 1e3 / K, float(np.mean([a.elapsed_time(b) for a, b in ev.values()])), len(sampled)
+    durs = np.array([a.elapsed_time(b) for a, b in ev.values()])
+    return wall * 1e3 / K, float(durs.mean()), (len(sampled), float(np.median(durs)), float(durs.min()))
 
 
 def main():
@@ -251,7 +252,7 @@ def main():
                       ("gemm_bf16_kernel<true, false, false>" if cfg.dtype == wl.BF16 else "gemm_f32_kernel<true>")
                       + " (GEMM-1: gathered gate/up GEMM + SwiGLU)")
     roof["avg_launch_ms"] = gk_ms
-    roof["launches_sampled"] = n_sampled
+    roof["launches_sampled"], roof["median_launch_ms"], roof["min_launch_ms"] = n_sampled
 
     out = {
         "metric": "fused MoE layer tokens/s on 1 MI355X", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
@@ -464,6 +465,20 @@ def main():
     out["copy_reference"] = {"what": "torch 1 GiB device-to-device copy", "ms": t_copy,
                              "hbm_gbs": 2.0 * src.numel() * 4 / (t_copy * 1e-3) / 1e9}
     del src, dst
+    # Context for the matrix-core fractions: what this box's matrix cores sustain on register operands (no loads at
+    # all; pseudo-random values), one workgroup of 8 waves per CU as the GEMM kernels run.
+    sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    B.moe_probe_mfma_rate(256, 2000, sink)  # warm-up
+    probe_flops = [0.0]
+
+    def probe():
+        probe_flops[0] = B.moe_probe_mfma_rate(256, 20000, sink)
+
+    t_probe = timed(probe, 3)
+    out["mfma_rate_probe"] = {"what": "8 waves per CU, 8 independent bf16 32x32x16 instructions per round, register "
+                                      "operands", "ms": t_probe, "tflops": probe_flops[0] / (t_probe * 1e-3) / 1e12}
+    roof["frac_of_probed_mfma_rate"] = (gk["flops"] / (gk_ms * 1e-3) / 1e12) / out["mfma_rate_probe"]["tflops"]
+    del sink
     # Context for the matrix-core fractions: what the vendor library's dense bf16 GEMM reaches on this very box
     # with the same kind of data (random normal), on a problem as large as this layer's GEMM-1 would be if it were
     # one dense product.  Not part of the path, not timed into `value`.

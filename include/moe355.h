@@ -296,6 +296,15 @@ MOE355_API int moe_fused_backward(const moe_shape *shape, const void *x, const v
 MOE355_API int moe_route_backward(const moe_shape *shape, const int32_t *topk_idx, const float *topk_w,
                                   const float *d_topk_w, float *dlogits, void *stream);
 
+/*
+ * For the measurement harness (no part of the layer calls it): one launch of `workgroups` x 512 threads in which every
+ * wave issues `iters` rounds of eight independent bf16 32x32x16 matrix-core instructions on pseudo-random register
+ * operands, the rate this device's matrix cores sustain when nothing has to be loaded.  *flops (host) receives the
+ * floating point operations of the launch; the caller times it.  sink: device scratch of >= workgroups * 512 floats.
+ */
+MOE355_API int moe_probe_mfma_rate(int workgroups, int iters, float *sink, size_t sink_floats, double *flops,
+                                   void *stream);
+
 /* Static string for a status code. */
 MOE355_API const char *moe_status_string(int status);
 

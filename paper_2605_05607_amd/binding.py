@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
             fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
         L.moe_route_topk_gate.restype = i32
         L.moe_route_topk_gate.argtypes = [sp, vp, vp, i32, vp, vp, vp]
+        L.moe_probe_mfma_rate.restype = i32
+        L.moe_probe_mfma_rate.argtypes = [i32, i32, vp, sz, C.POINTER(C.c_double), vp]
         L.moe_route_backward.restype = i32
         L.moe_route_backward.argtypes = [sp, vp, vp, vp, vp, vp]
         L.moe_fp8_packed_weight_bytes.restype = sz
@@ -273,6 +275,14 @@ MOE_GATE_SIGMOID = 1
 def moe_route_topk_gate(shape, logits, bias, gate, topk_idx, topk_w, stream=None) -> None:
     _check(lib().moe_route_topk_gate(C.byref(shape), _ptr(logits), _ptr(bias), int(gate), _ptr(topk_idx),
                                      _ptr(topk_w), _stream(stream)), "moe_route_topk_gate")
+
+
+def moe_probe_mfma_rate(workgroups: int, iters: int, sink, stream=None) -> float:
+    """Launches the matrix-core rate probe; returns the floating point operations of the launch."""
+    flops = C.c_double(0.0)
+    _check(lib().moe_probe_mfma_rate(workgroups, iters, _ptr(sink), sink.numel(), C.byref(flops), _stream(stream)),
+           "moe_probe_mfma_rate")
+    return float(flops.value)
 
 
 def moe_route_backward(shape, topk_idx, topk_w, d_topk_w, dlogits, stream=None) -> None:

@@ -233,3 +233,12 @@ def test_route_backward_arguments():
     assert lib.moe_route_backward(C.byref(s), fake, fake, fake, None, None) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_route_backward(None, fake, fake, fake, fake, None) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_route_backward(C.byref(good_shape(T=0)), fake, fake, fake, fake, None) == B.MOE_OK
+
+
+def test_mfma_rate_probe_arguments():
+    lib = B.lib()
+    fl = C.c_double(0.0)
+    assert lib.moe_probe_mfma_rate(0, 10, 4096, 1 << 20, C.byref(fl), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_mfma_rate(4, 0, 4096, 1 << 20, C.byref(fl), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_mfma_rate(4, 10, None, 1 << 20, C.byref(fl), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_mfma_rate(4, 10, 4096, 4 * 512 - 1, C.byref(fl), None) == B.MOE_ERR_WORKSPACE
