@@ -799,3 +799,25 @@ def test_route_backward(oracle, T, E, k):
     np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
     assert np.all(out[~mask] == 0)
     assert np.abs(out - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())  # fp32 weights and sums of k <= 32 terms
+
+
+def test_training_path_without_any_local_row():
+    """Routing that sends nothing to this GPU's experts: y, dx, d_topk_w and every weight gradient are zero."""
+    import torch
+    cfg = cfg_of(T=200, d=64, f=64, E=16, k=2, R=4, local_rank_begin=1, local_rank_end=2)
+    w = wl.make_workload(cfg)
+    logits = w.logits.copy()
+    logits[:, cfg.first_local_expert:cfg.first_local_expert + cfg.E_loc] = -50.0
+    lay = L.MoELayer(cfg)
+    lay.load_weights(w.W_gate, w.W_up, w.W_down)
+    lay.enable_training(w.W_gate, w.W_up, w.W_down, wgrad=True)
+    x, dy = L.to_device(w.x), L.to_device(dy_for(cfg))
+    lay.route(L.to_device(logits))
+    lay.build_dispatch()
+    for t in (lay.y, lay.dx, lay.d_topk_w, lay.dW_gate, lay.dW_up, lay.dW_down):
+        t.fill_(float("nan"))
+    lay.forward_train(x)
+    lay.backward(x, dy)
+    torch.cuda.synchronize()
+    for t in (lay.y, lay.dx, lay.d_topk_w, lay.dW_gate, lay.dW_up, lay.dW_down):
+        assert t.float().abs().max().item() == 0
