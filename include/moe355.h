@@ -226,7 +226,8 @@ MOE355_API int moe_unfused_forward(const moe_shape *shape, const void *x, const 
  * at +-448), products are accumulated in fp32:
  *   x       one scale per token   = largest magnitude of the row / 448 (1 for a zero row), code = cvt(x / scale);
  *   weights one scale per expert and output column, same rule over the reduction index;
- *   h       code = cvt(silu(g) * u / h_scale[le]) with a given (calibrated, static) scale per local expert;
+ *   h       code = cvt(silu(g) * u / h_scale[le]) with a given (calibrated, static) scale per local expert
+ *           (finite and > 0; values beyond 448 * h_scale[le] saturate);
  *   g, u = (sum of code products) * scale(token) * scale(column);  o = (sum) * h_scale[le] * scale(column) * w.
  * y, the tables, the gate weights and the reduction are those of moe_fused_forward (y in bf16).
  *
@@ -254,7 +255,8 @@ MOE355_API int moe_fp8_fused_forward(const moe_shape *shape, const void *x, cons
  * Training path (the paper's end-to-end results cover forward and backward, Sec. V; it gives no formulas: these are
  * the derivatives of the layer as moe_fused_forward computes it).  bf16 layers with f % 64 == 0, MOE_ERR_UNSUPPORTED
  * otherwise.  For a local row (token t, slot j, local expert le, gate weight w) and the incoming gradient dy_t:
- *   dh_raw = dy_t Wd^T, d_topk_w[t,j] = <o, dy_t>, dh = w dh_raw, dg = dh u silu'(g), du = dh silu(g),
+ *   dh_raw = dy_t Wd^T, d_topk_w[t,j] = <o, dy_t> (formed as <w o, dy_t> / w from the kept rows; reported as 0 where
+ *   w underflowed to exactly 0), dh = w dh_raw, dg = dh u silu'(g), du = dh silu(g),
  *   dx_t = sum over the local slots of dg Wg^T + du Wu^T,
  *   dW_gate[le] = sum over the expert's rows of x_t^T dg, dW_up likewise with du, dW_down[le] = sum of h^T (w dy_t).
  * Only local slots contribute (one GPU's share): dx rows of tokens without a local slot are zero, d_topk_w is zero

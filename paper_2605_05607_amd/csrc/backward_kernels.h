@@ -32,7 +32,8 @@ __global__ __launch_bounds__(256) void gate_weight_grad_kernel(const float *__re
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-    if (lane == 0) d_topk_w[perm[base + r]] = acc / row_w[r];
+    // (a weight that underflowed to zero leaves nothing of o in o_w: its gradient is reported as zero)
+    if (lane == 0) d_topk_w[perm[base + r]] = row_w[r] != 0.f ? acc / row_w[r] : 0.f;
   }
 }
 
