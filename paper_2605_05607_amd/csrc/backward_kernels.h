@@ -24,6 +24,7 @@ __global__ __launch_bounds__(256) void gate_weight_grad_kernel(const float *__re
     const float *orow = o_w + (size_t)r * d;
     const bf16_t *grow = dy + (size_t)row_tok[r] * d;
     float acc = 0.f;
+#pragma unroll 4
     for (int c = lane * 4; c < d; c += 256) {  // d % 8 == 0: groups of 4 stay inside the row
       const f32x4 ov = *reinterpret_cast<const f32x4 *>(orow + c);
       const bf16x4 gv = *reinterpret_cast<const bf16x4 *>(grow + c);

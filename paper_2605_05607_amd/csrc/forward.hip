@@ -361,11 +361,19 @@ extern "C" int moe_fp8_pack_weights(const moe_shape *shape, const void *W_gate, 
   float *s_dn = reinterpret_cast<float *>(dn + align_up(fp8_tile_bytes(shape, dv, 1), 256));  // [E_loc][d]
   const bf16_t *Wg = static_cast<const bf16_t *>(W_gate), *Wu = static_cast<const bf16_t *>(W_up);
   const bf16_t *Wd = static_cast<const bf16_t *>(W_down);
-  hipLaunchKernelGGL(fp8_column_scales_kernel, dim3(ceil_div(f, 256), dv.E_loc), dim3(256), 0, st, Wg, d, f, s_gu,
-                     2 * f);
-  hipLaunchKernelGGL(fp8_column_scales_kernel, dim3(ceil_div(f, 256), dv.E_loc), dim3(256), 0, st, Wu, d, f, s_gu + f,
-                     2 * f);
-  hipLaunchKernelGGL(fp8_column_scales_kernel, dim3(ceil_div(d, 256), dv.E_loc), dim3(256), 0, st, Wd, f, d, s_dn, d);
+  // column maxima (the reduction range cut into slices for enough workgroups), then scales in place
+  const size_t n_gu = (size_t)dv.E_loc * 2 * f, n_dn = (size_t)dv.E_loc * d;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(256), dim3(256), 0, st, s_gu, n_gu, 0.0f);
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(256), dim3(256), 0, st, s_dn, n_dn, 0.0f);
+  const int slices_d = std::max(1, std::min(32, d / 64)), slices_f = std::max(1, std::min(32, f / 64));
+  hipLaunchKernelGGL(fp8_column_amax_kernel, dim3(ceil_div(f, 256), dv.E_loc, slices_d), dim3(256), 0, st, Wg, d, f,
+                     reinterpret_cast<uint32_t *>(s_gu), 2 * f);
+  hipLaunchKernelGGL(fp8_column_amax_kernel, dim3(ceil_div(f, 256), dv.E_loc, slices_d), dim3(256), 0, st, Wu, d, f,
+                     reinterpret_cast<uint32_t *>(s_gu + f), 2 * f);
+  hipLaunchKernelGGL(fp8_column_amax_kernel, dim3(ceil_div(d, 256), dv.E_loc, slices_f), dim3(256), 0, st, Wd, f, d,
+                     reinterpret_cast<uint32_t *>(s_dn), d);
+  hipLaunchKernelGGL(fp8_scales_from_amax_kernel, dim3(256), dim3(256), 0, st, s_gu, n_gu);
+  hipLaunchKernelGGL(fp8_scales_from_amax_kernel, dim3(256), dim3(256), 0, st, s_dn, n_dn);
   if ((rc = launch_status()) != MOE_OK) return rc;
   hipLaunchKernelGGL(pack_fp8_kernel<true>, dim3(kt1, nt1, dv.E_loc), dim3(256), 0, st, Wg, Wu, s_gu, s_gu + f, 2 * f,
                      gu, d, f, nt1, kt1);

@@ -51,15 +51,29 @@ __global__ __launch_bounds__(256) void fp8_quantize_rows_kernel(const uint4 *__r
   }
 }
 
-// Scale of every output column of W [E_loc][K][N] (bf16): scales [E_loc][N].  grid (ceil(N / 256), E_loc).
-__global__ __launch_bounds__(256) void fp8_column_scales_kernel(const bf16_t *__restrict__ W, int K, int N,
-                                                                float *__restrict__ scales, int scale_pitch) {
+// Largest magnitude of every output column of W [E_loc][K][N] (bf16) over one slice of the reduction index
+// (blockIdx.z of gridDim.z slices), folded into amax [E_loc][pitch] with an integer atomic max (bit patterns of
+// non-negative floats order like the floats, and a maximum does not depend on the order of its operands).  amax
+// must be zero on entry.  grid (ceil(N / 256), E_loc, slices).
+__global__ __launch_bounds__(256) void fp8_column_amax_kernel(const bf16_t *__restrict__ W, int K, int N,
+                                                              uint32_t *__restrict__ amax, int pitch) {
   const int col = blockIdx.x * 256 + threadIdx.x, le = blockIdx.y;
   if (col >= N) return;
+  const int per = (K + gridDim.z - 1) / gridDim.z;
+  const int k0 = blockIdx.z * per, k1 = min(K, k0 + per);
   const bf16_t *w = W + (size_t)le * K * N + col;
-  float amax = 0.f;
-  for (int kk = 0; kk < K; ++kk) amax = fmaxf(amax, fabsf((float)w[(size_t)kk * N]));
-  scales[(size_t)le * scale_pitch + col] = amax > 0.f ? amax / 448.0f : 1.0f;
+  float m = 0.f;
+#pragma unroll 8
+  for (int kk = k0; kk < k1; ++kk) m = fmaxf(m, fabsf((float)w[(size_t)kk * N]));
+  atomicMax(&amax[(size_t)le * pitch + col], __float_as_uint(m));
+}
+
+// amax -> scale in place: largest magnitude / 448, 1 for an all-zero column.
+__global__ void fp8_scales_from_amax_kernel(float *__restrict__ s, size_t n) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+    const float a = s[i];
+    s[i] = a > 0.f ? a / 448.0f : 1.0f;
+  }
 }
 
 // Quantise and re-tile the weights (one-off).  The tile image is that of pack_bf16_kernel with 16 codes in every
