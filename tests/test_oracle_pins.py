@@ -618,3 +618,14 @@ def test_route_backward_vs_finite_differences_and_closed_form(oracle):
     mask = np.zeros((T, E), bool)
     np.put_along_axis(mask, idx.astype(np.int64), True, axis=1)
     assert np.all(dl[~mask] == 0)
+
+
+def test_fp8_landmarks_from_the_format_specification(oracle):
+    with open(os.path.join(os.path.dirname(__file__), "golden", "e4m3_landmarks.json")) as f:
+        gold = json.load(f)
+    codes = np.array([int(c, 16) for c in gold["codes"]], dtype=np.uint8)
+    np.testing.assert_array_equal(oracle.fp8_decode(codes), np.array(list(gold["codes"].values())))
+    assert np.isnan(oracle.fp8_decode(np.array([int(c, 16) for c in gold["nan_codes"]], dtype=np.uint8))).all()
+    for case in gold["round_to_nearest_even"]:
+        got = int(oracle.fp8_encode(np.array([case["value"]], dtype=np.float32))[0])
+        assert got == int(case["code"], 16), case
