@@ -326,23 +326,41 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      // gate weights of the 16 rows this lane holds accumulators for (rows past the end: 0, the math stays finite
+      // and nothing of them is stored)
+      float wv[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row_l = blk_row0 + (r >> 2) * 8 + khalf * 4 + (r & 3);
+        wv[r] = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
+      }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
+        // all reads of this half first, then the arithmetic, then all writes: the LDS operations of one kind go
+        // out back to back instead of waiting on one another
+        const int cb = (j * 32 + l31) * 2;
+        float gv[16], uv[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
-          const int row_l = blk_row0 + rl;
-          bf16_t *pg = reinterpret_cast<bf16_t *>(blk + rl * 144 + (j * 32 + l31) * 2);
-          bf16_t *pu = reinterpret_cast<bf16_t *>(blk + 4608 + rl * 144 + (j * 32 + l31) * 2);
-          bf16_t *ph = reinterpret_cast<bf16_t *>(blk + 9216 + rl * 144 + (j * 32 + l31) * 2);
-          const bool in = row_l < rows && col0 + j * 32 + l31 < g.N;  // outside: never stored, keep the math finite
-          const float wv = in ? g.row_w[m0 + row_l] : 0.f;
-          const float gv = in ? (float)*pg : 0.f, uv = in ? (float)*pu : 0.f;
-          const float sg = 1.0f / (1.0f + __expf(-gv)), silu = gv * sg;
-          const float dh = wv * acc[mi][j][r];
-          *pg = (bf16_t)(dh * uv * (sg * (1.0f + gv * (1.0f - sg))));
-          *pu = (bf16_t)(dh * silu);
-          *ph = (bf16_t)(wv * silu * uv);
+          gv[r] = (float)*reinterpret_cast<const bf16_t *>(blk + rl * 144 + cb);
+          uv[r] = (float)*reinterpret_cast<const bf16_t *>(blk + 4608 + rl * 144 + cb);
+        }
+        bf16_t o_dg[16], o_du[16], o_hw[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float sg = 1.0f / (1.0f + __expf(-gv[r])), silu = gv[r] * sg;
+          const float dh = wv[r] * acc[mi][j][r];
+          o_dg[r] = (bf16_t)(dh * uv[r] * (sg * (1.0f + gv[r] * (1.0f - sg))));
+          o_du[r] = (bf16_t)(dh * silu);
+          o_hw[r] = (bf16_t)(wv[r] * silu * uv[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
+          *reinterpret_cast<bf16_t *>(blk + rl * 144 + cb) = o_dg[r];
+          *reinterpret_cast<bf16_t *>(blk + 4608 + rl * 144 + cb) = o_du[r];
+          *reinterpret_cast<bf16_t *>(blk + 9216 + rl * 144 + cb) = o_hw[r];
         }
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
