@@ -549,7 +549,7 @@ def test_fp8_rejects_what_it_does_not_cover():
                              np.zeros((cfg.E_loc, 40, 72), np.uint16), wl.fp8_h_scale(cfg))
 
 
-@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 64), ("qwen3", 48)])
+@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 64), ("qwen3", 48), ("mixtral", 24), ("gpt_oss", 48)])
 def test_fp8_forward_full_size_sampled_tokens(oracle, name, nsample):
     cfg = wl.CONFIGS[name]
     say(f"fp8 forward full size {name}")
@@ -724,7 +724,7 @@ def test_backward_weight_gradients_match_oracle_small(oracle, name):
     assert all(torch.equal(a, b) for a, b in zip(g0, (lay.dW_gate, lay.dW_up, lay.dW_down)))
 
 
-@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 48), ("qwen3", 32)])
+@pytest.mark.parametrize("name,nsample", [("deepseek_v3", 48), ("qwen3", 32), ("mixtral", 16), ("gpt_oss", 32)])
 def test_backward_full_size_sampled(oracle, name, nsample):
     """Full-size layers: dx and d_topk_w on sampled tokens (half with one local slot, half with several), weight
     gradients of the fullest and of the emptiest non-empty local expert on a 64-wide range of hidden indices."""
