@@ -83,7 +83,12 @@ typedef struct {
   int32_t *pair_to_dedup;
 } moe_dispatch;
 
-/* Host-only size queries (no HIP call).  Return 0 for an invalid shape. */
+/*
+ * Host-only size queries (no HIP call).  Return 0 for an invalid shape.  moe_workspace_bytes is enough for every
+ * call of a step (moe_build_dispatch, then moe_fused_forward, on one stream with one buffer); the two specific
+ * queries let a caller that keeps the buffers apart size the small one (dispatch: a few hundred KiB) on its own.
+ */
+MOE355_API size_t moe_workspace_bytes(const moe_shape *shape);
 MOE355_API size_t moe_dispatch_workspace_bytes(const moe_shape *shape);
 MOE355_API size_t moe_forward_workspace_bytes(const moe_shape *shape);
 /* Bytes of the packed gate/up buffer (which = 0) or the packed down buffer (which = 1). */
@@ -149,7 +154,8 @@ MOE355_API int moe_pack_weights(const moe_shape *shape, const void *W_gate, cons
  * workgroups: a GEMM-2 tile starts as soon as the h rows of its 256-row tile are complete (per-tile readiness
  * counters in the workspace), the one-GPU form of the tile-granular GEMM-1 => GEMM-2 hand-over of the fused
  * kernel (Sec. IV-A, IV-B); otherwise the two GEMMs are two launches.  The result is the same either way.
- * Int 24 of the workspace is 0 after the call unless a wait inside the resident kernel gave up (corrupt tables).
+ * A wait inside the resident kernel is bounded; if one gives up (corrupt tables; it cannot happen otherwise) the rows
+ * computed from the incomplete tile are written as NaN and moe_forward_status reports 1 for this workspace.
  * `tables` must come from moe_build_dispatch on the same shape and topk_idx.
  * workspace >= moe_forward_workspace_bytes(shape), 256-byte aligned; its contents are scratch.  x, y and the
  * packed weights must be 16-byte aligned (MOE_ERR_INVALID_ARG otherwise).
@@ -170,6 +176,22 @@ MOE355_API int moe_fused_forward_timed(const moe_shape *shape, const void *x, co
                                        const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
                                        const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
                                        void *stream, void *const *events);
+
+/*
+ * *flag (host) = 0, or 1 if a wait inside the resident GEMM kernel of the last forward call that used `workspace`
+ * gave up.  The one call of this library that copies to the host and synchronises with `stream`; for diagnostics.
+ *
+ * moe_fused_forward_bounded: moe_fused_forward_one_launch with the bound on the polls of one wait given by the caller
+ * (max_polls >= 1, each poll about a microsecond; the library's default is several seconds) and with every GEMM-2 tile
+ * waiting for wait_extra more GEMM-1 tiles than exist (0 = the real count).  With wait_extra > 0 and a small bound
+ * every wait gives up, all kernels still exit normally, y holds NaN in every row with a local slot and
+ * moe_forward_status reports 1: the way the give-up path is tested.
+ */
+MOE355_API int moe_forward_status(const void *workspace, int32_t *flag, void *stream);
+MOE355_API int moe_fused_forward_bounded(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                         const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                         const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                         void *stream, int max_polls, int wait_extra);
 
 /* 1 or 2: GEMM launches of moe_fused_forward for this shape (host-only; 0 for an invalid shape). */
 MOE355_API int moe_forward_gemm_launches(const moe_shape *shape);
@@ -298,17 +320,20 @@ MOE355_API int moe_fused_backward(const moe_shape *shape, const void *x, const v
 MOE355_API int moe_route_backward(const moe_shape *shape, const int32_t *topk_idx, const float *topk_w,
                                   const float *d_topk_w, float *dlogits, void *stream);
 
-/*
- * For the measurement harness (no part of the layer calls it): one launch of `workgroups` x 512 threads in which every
- * wave issues `iters` rounds of eight independent bf16 32x32x16 matrix-core instructions on pseudo-random register
- * operands, the rate this device's matrix cores sustain when nothing has to be loaded.  *flops (host) receives the
- * floating point operations of the launch; the caller times it.  sink: device scratch of >= workgroups * 512 floats.
- */
-MOE355_API int moe_probe_mfma_rate(int workgroups, int iters, float *sink, size_t sink_floats, double *flops,
-                                   void *stream);
-
 /* Static string for a status code. */
 MOE355_API const char *moe_status_string(int status);
+
+/*
+ * Measurement harness only (define MOE355_BENCH before including this header; no part of the layer calls it): one
+ * launch of `workgroups` x 512 threads in which every wave issues `iters` rounds of eight independent bf16 32x32x16
+ * matrix-core instructions on pseudo-random register operands, the rate this device's matrix cores sustain when
+ * nothing has to be loaded.  *flops (host) receives the floating point operations of the launch; the caller times it.
+ * sink: device scratch of >= workgroups * 512 floats.
+ */
+#ifdef MOE355_BENCH
+MOE355_API int moe_probe_mfma_rate(int workgroups, int iters, float *sink, size_t sink_floats, double *flops,
+                                   void *stream);
+#endif
 
 #ifdef __cplusplus
 }

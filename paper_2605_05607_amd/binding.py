@@ -68,6 +68,12 @@ def lib() -> C.CDLL:
         L.moe_route_topk.argtypes = [sp, vp, vp, vp, vp]
         L.moe_build_dispatch.restype = i32
         L.moe_build_dispatch.argtypes = [sp, vp, dp, vp, sz, vp]
+        L.moe_workspace_bytes.restype = sz
+        L.moe_workspace_bytes.argtypes = [sp]
+        L.moe_forward_status.restype = i32
+        L.moe_forward_status.argtypes = [vp, C.POINTER(C.c_int32), vp]
+        L.moe_fused_forward_bounded.restype = i32
+        L.moe_fused_forward_bounded.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, i32, i32]
         L.moe_pack_weights.restype = i32
         L.moe_pack_weights.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         for name in ("moe_fused_forward", "moe_unfused_forward"):
@@ -204,6 +210,28 @@ def moe_build_dispatch(shape, topk_idx, tables: DispatchTables, workspace, works
     nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     _check(lib().moe_build_dispatch(C.byref(shape), _ptr(topk_idx), C.byref(tables.struct), _ptr(workspace), nbytes,
                                     _stream(stream)), "moe_build_dispatch")
+
+
+def moe_workspace_bytes(shape: moe_shape) -> int:
+    return int(lib().moe_workspace_bytes(C.byref(shape)))
+
+
+def moe_forward_status(workspace, stream=None) -> int:
+    """0, or 1 if a wait inside the resident GEMM kernel of the last forward call on this workspace gave up.
+    Synchronises with the stream."""
+    flag = C.c_int32(-1)
+    _check(lib().moe_forward_status(_ptr(workspace), C.byref(flag), _stream(stream)), "moe_forward_status")
+    return int(flag.value)
+
+
+def moe_fused_forward_bounded(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                              max_polls: int, wait_extra: int = 0, workspace_bytes=None, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().moe_fused_forward_bounded(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
+                                           C.byref(tables.struct), _ptr(packed_gate_up), _ptr(packed_down), _ptr(y),
+                                           _ptr(workspace), nbytes, _stream(stream), int(max_polls),
+                                           int(wait_extra)),
+           "moe_fused_forward_bounded")
 
 
 def moe_pack_weights(shape, W_gate, W_up, W_down, packed_gate_up, packed_down, stream=None) -> None:

@@ -1,4 +1,6 @@
 // Host-side pieces of the C ABI that touch no device: shape validation, workspace geometry, status strings.
+#include <algorithm>
+
 #include "common.h"
 
 namespace moe355 {
@@ -59,6 +61,11 @@ extern "C" size_t moe_forward_workspace_bytes(const moe_shape *shape) {
   Derived dv;
   if (check_shape(shape, &dv) != MOE_OK) return 0;
   return forward_layout(shape, dv).total;
+}
+
+extern "C" size_t moe_workspace_bytes(const moe_shape *shape) {
+  // one buffer for both calls of a step: the dispatch scratch is dead once moe_build_dispatch's kernels have run
+  return std::max(moe_dispatch_workspace_bytes(shape), moe_forward_workspace_bytes(shape));
 }
 
 extern "C" int moe_forward_gemm_launches(const moe_shape *shape) {

@@ -51,6 +51,18 @@ static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch
   return launch_status();
 }
 
+// Compute units of the current device, looked up once per device (0 on failure).
+static int compute_units() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 0;
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
 // FP8 form of the GEMMs: quantised x with its per-token scales, the column scales that follow the packed tiles,
 // and the per-expert scale of h.
 struct Fp8Operands {
@@ -68,7 +80,8 @@ static size_t fp8_tile_bytes(const moe_shape *s, const Derived &dv, int which) {
 static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, const int32_t *a1_map, int a1_ld,
                         const void *packed_gu, const void *packed_down, const Ws &w, const int32_t *sole, void *y,
                         hipStream_t st, void *const *events = nullptr, bool pipelined = false,
-                        const Fp8Operands *q = nullptr, void *keep_gu = nullptr, float *keep_o = nullptr) {
+                        const Fp8Operands *q = nullptr, void *keep_gu = nullptr, float *keep_o = nullptr,
+                        int max_polls = kMaxPolls, int wait_extra = 0) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
@@ -98,13 +111,12 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
     g1.n_ntiles = ceil_div(s->f, kBN / 2); g1.n_ktiles = ceil_div(s->d, kFp8KStep);
     g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kFp8KStep);
     if (pipelined) {
-      int dev = 0, n_cu = 0;
-      if (hipGetDevice(&dev) != hipSuccess ||
-          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
-        return MOE_ERR_HIP;
+      const int n_cu = compute_units();
+      if (n_cu < 1) return MOE_ERR_HIP;
       PipelineArgs pa;
       pa.g1 = g1; pa.g2 = g2;
-      pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1;
+      pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1 + wait_extra;
+      pa.max_polls = max_polls;
       hipLaunchKernelGGL(gemm_fp8_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st, pa);
       mark(2);
       mark(3);
@@ -129,13 +141,12 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
     g2.n_ntiles = ceil_div(s->d, kBN);     g2.n_ktiles = ceil_div(s->f, kBK);
     if (pipelined) {
       // one resident workgroup per CU (each takes most of a CU's LDS)
-      int dev = 0, n_cu = 0;
-      if (hipGetDevice(&dev) != hipSuccess ||
-          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
-        return MOE_ERR_HIP;
+      const int n_cu = compute_units();
+      if (n_cu < 1) return MOE_ERR_HIP;
       PipelineArgs pa;
       pa.g1 = g1; pa.g2 = g2;
-      pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1;
+      pa.tickets = w.header + 8; pa.tile_ready = w.tile_ready; pa.error = w.header + 24; pa.nt1 = dv.nt1 + wait_extra;
+      pa.max_polls = max_polls;
       if (keep_gu) {
         static std::atomic<uint64_t> done_tp{0};
         if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_train_pipeline_kernel), 2 * kStageBytes, done_tp))
@@ -234,7 +245,7 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
                           const moe_dispatch *tables, const void *packed_gate_up, const void *packed_down, void *y,
                           void *workspace, size_t workspace_bytes, void *stream, bool fused,
                           void *const *events = nullptr, int gemm_launches = 0, const float *h_scale = nullptr,
-                          void *keep = nullptr) {
+                          void *keep = nullptr, int max_polls = kMaxPolls, int wait_extra = 0) {
   Derived dv;
   int rc = check_shape(shape, &dv);
   if (rc != MOE_OK) return rc;
@@ -299,7 +310,7 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
   mark(1);
   if (fused) {
     if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, sole, y, st,
-                           events, pipelined, fp8 ? &q : nullptr, keep_gu, keep_o)) != MOE_OK)
+                           events, pipelined, fp8 ? &q : nullptr, keep_gu, keep_o, max_polls, wait_extra)) != MOE_OK)
       return rc;
     rc = launch_combine(shape, dv, keep ? keep_o : w.o, topk_idx, tables, y, sole != nullptr, st);
     mark(4);
@@ -411,6 +422,28 @@ extern "C" int moe_fused_forward(const moe_shape *shape, const void *x, const in
                                  void *y, void *workspace, size_t workspace_bytes, void *stream) {
   return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
                         workspace_bytes, stream, true);
+}
+
+extern "C" int moe_fused_forward_bounded(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                         const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                         const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                         void *stream, int max_polls, int wait_extra) {
+  if (max_polls < 1 || wait_extra < 0) return MOE_ERR_INVALID_ARG;
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, nullptr, 1, nullptr, nullptr, max_polls, wait_extra);
+}
+
+extern "C" int moe_forward_status(const void *workspace, int32_t *flag, void *stream) {
+  if (!workspace || !flag) return MOE_ERR_INVALID_ARG;
+  // header word 24 of the forward workspace (see FwdLayout): raised by a wait of the resident kernel that gave up
+  const int32_t *word = static_cast<const int32_t *>(workspace) + 24;
+  hipStream_t st = (hipStream_t)stream;
+  if (hipMemcpyAsync(flag, word, sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess) {
+    (void)hipGetLastError();
+    return MOE_ERR_HIP;
+  }
+  return MOE_OK;
 }
 
 extern "C" int moe_fused_forward_timed(const moe_shape *shape, const void *x, const int32_t *topk_idx,

@@ -41,6 +41,16 @@ __device__ __forceinline__ f32x16 mfma_fp8_pair(bf16x8 a_lo, bf16x8 a_hi, bf16x8
 }
 
 constexpr int kGemmThreads = 512;
+
+// s_waitcnt immediate of the gfx9 encoding (gfx950 included) for "vmcnt(0)": the vector-memory counter at zero (bits
+// 3:0 and 15:14), the export and LDS/scalar counters left at their maxima (bits 6:4 = 7, bits 11:8 = 15).  Used where
+// a wait has to be spelled out around the device-scope hand-over of the resident kernel (see gemm_bf16_drain); any
+// other instruction set encodes the counters differently, so the build is pinned to the target the waits were
+// written for.
+#if defined(__HIP_DEVICE_COMPILE__) && !defined(__gfx950__)
+#error "the explicit s_waitcnt encodings of the hand-over are written for gfx950"
+#endif
+constexpr int kWaitVmcnt0 = 0x0F70;
 constexpr int kAStageBytes = kBM * kBK * 2;               // 32 KiB
 constexpr int kStageBytes = kAStageBytes + kTileBytes;    // 64 KiB: A slab then B slab
 constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue patch (fits 8 x in the stages)
@@ -56,7 +66,7 @@ constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue p
 //            g.aux2 = w silu(g) u [rows, N] bf16 (the h operand of the down-projection weight gradient, weight folded in).
 template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
-                                               int rows, int nblk_total) {
+                                               int rows, int nblk_total, int poison = 0) {
   // RESIDENT (the kernel that loops over items): the thread index goes through an empty asm so that nothing
   // derived from it counts as loop invariant; hoisting those values across items costs more registers than the
   // tile has to spare.
@@ -458,7 +468,8 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const int row_l = blk_row0 + rl;
-        const float wgt = row_l < rows ? (g.row_w ? g.row_w[m0 + row_l] : 1.f) : 0.f;
+        float wgt = row_l < rows ? (g.row_w ? g.row_w[m0 + row_l] : 1.f) : 0.f;
+        if (poison) wgt = __builtin_nanf("");  // the wait for this item's h gave up: mark what it writes
         *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = FP8 ? acc[mi][0][r] * cs0 * wgt : acc[mi][0][r] * wgt;
         *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) =
             FP8 ? acc[mi][1][r] * cs1 * wgt : acc[mi][1][r] * wgt;
@@ -490,15 +501,17 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 }
 
 // One work item on the matrix cores.  Wave-uniform dispatch on the number of valid 32-row blocks: every variant
-// executes the same sequence of barriers.
+// executes the same sequence of barriers.  poison != 0 (GEMM-2 inside the resident kernel, after a wait that gave up):
+// the rows are written as NaN.
 template <bool GATED, bool RESIDENT, bool FP8 = false, bool TRAIN = false>
-__device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item) {
+__device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item,
+                                               int poison = 0) {
   const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
 #define MOE355_TILE(NB_, NA_) \
-  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN>(g, smem, nt, le, m0, rows, nblk_total)
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN>(g, smem, nt, le, m0, rows, nblk_total, poison)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -545,16 +558,17 @@ struct PipelineArgs {
   int32_t *tickets;     // [16]: queues of GEMM-1, then of GEMM-2
   int32_t *tile_ready;  // [M tiles] GEMM-1 items finished per M tile
   int32_t *error;       // set if a wait gave up (cannot happen unless the lists are corrupt)
-  int nt1;              // GEMM-1 items per M tile
+  int nt1;              // GEMM-1 items per M tile a GEMM-2 item waits for
+  int max_polls;        // bound on the polls of one wait (x ~1 us), so that no wave can wait forever
 };
 
-constexpr int kMaxPolls = 1 << 22;  // x ~1 us: a bound so that no wave can wait forever
+constexpr int kMaxPolls = 1 << 22;  // default bound: several seconds
 
 // All items of one GEMM that this workgroup can get hold of: home queue first, then the other queues.
 template <bool GATED, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char *smem, int *s_item,
                                                 int32_t *__restrict__ tickets, int32_t *__restrict__ tile_ready,
-                                                int32_t *__restrict__ error, int nt1) {
+                                                int32_t *__restrict__ error, int nt1, int max_polls) {
   const int home = blockIdx.x & 7;
   const int n_items = *g.n_items;
   const int n_virtual = (n_items + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk);
@@ -599,58 +613,66 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
     const int tile = item.w >> kTileShift;
     if (GATED) {
       gemm_bf16_item<true, true, FP8, TRAIN>(g, smem, item);
-      // every wave first waits until its own h stores have been acknowledged (vmcnt(0); gfx9 encoding with the
-      // other counters left at their maxima), so that the one write-back below cannot overtake any of them
-      __builtin_amdgcn_s_waitcnt(0x0F70);
+      // Release side of the hand-over.  Every wave first waits until its own h stores have been acknowledged, so that
+      // the one write-back below cannot overtake any of them (a workgroup barrier alone does not wait for global
+      // stores).
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
       __syncthreads();  // every thread's h stores happen before thread 0's release ...
       if (threadIdx.x == 0) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // ... which makes them visible device-wide ...
-        // The write-back the fence issues has to be complete before the counter moves.  The compiler does not put
-        // a wait between the two here (it has just waited for the stores in front of the barrier and does not
-        // count the write-back as outstanding), so the wait is spelled out: vmcnt(0).
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        atomicAdd(&tile_ready[tile], 1);                     // ... before the item is counted
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // ... which writes this XCD's L2 back: visible device-wide
+        // The write-back has to be complete before the counter moves.  The compiler places no wait between the two
+        // here (the wave has just waited for its stores, and the write-back is not counted as outstanding), so the
+        // wait is spelled out.
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        __hip_atomic_fetch_add(&tile_ready[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // ... then counted
       }
     } else {
+      // Acquire side: thread 0 polls with relaxed device-scope loads (an acquire per poll would invalidate the L2
+      // every time), then one acquire fence orders the loads of h after the counter; the barrier hands the result to
+      // the workgroup.  A wait that gives up (corrupt lists; cannot happen otherwise) raises the error word and the
+      // item runs with a NaN in place of the gate weight, so that nothing computed from incomplete h can pass as a
+      // result.
       if (threadIdx.x == 0) {
-        int polls = 0;
+        int polls = 0, gave_up = 0;
         while (__hip_atomic_load(&tile_ready[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < nt1) {
           __builtin_amdgcn_s_sleep(32);
-          if (++polls > kMaxPolls) {
-            *error = 1;
+          if (++polls > max_polls) {
+            __hip_atomic_store(error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            gave_up = 1;
             break;
           }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // order the loads of h after the counter
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // the invalidate is complete before the barrier lets the others load
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // the invalidate is complete before the barrier lets the others load
+        s_item[1] = gave_up;
       }
       __syncthreads();
-      gemm_bf16_item<false, true, FP8>(g, smem, item);
+      gemm_bf16_item<false, true, FP8>(g, smem, item, s_item[1]);
     }
   }
 }
 
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item;
-  gemm_bf16_drain<true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
-  gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
+  __shared__ int s_item[2];  // [0] list position drawn by thread 0, [1] its wait gave up
+  gemm_bf16_drain<true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
+  gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
 }
 
 // The same resident kernel for the training forward: GEMM-1 also keeps g and u.
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_train_pipeline_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item;
-  gemm_bf16_drain<true, false, true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
-  gemm_bf16_drain<false>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
+  __shared__ int s_item[2];
+  gemm_bf16_drain<true, false, true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
+  gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
 }
 
 // The same resident kernel on E4M3 operands.
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_fp8_pipeline_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item;
-  gemm_bf16_drain<true, true>(p.g1, smem, &s_item, p.tickets, p.tile_ready, p.error, p.nt1);
-  gemm_bf16_drain<false, true>(p.g2, smem, &s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1);
+  __shared__ int s_item[2];
+  gemm_bf16_drain<true, true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
+  gemm_bf16_drain<false, true>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
 }
 
 }  // namespace moe355

@@ -1,6 +1,7 @@
 // moe_probe_mfma_rate: what the matrix cores of this device sustain with operands already in registers, the
 // reference point for the MFMA fractions that the GEMM kernels are priced against (a figure for the measurement
 // harness; nothing on the layer's path calls it).
+#define MOE355_BENCH  // the declaration of the probe sits in the bench section of the public header
 #include "forward_types.h"
 
 namespace moe355 {

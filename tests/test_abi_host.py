@@ -242,3 +242,27 @@ def test_mfma_rate_probe_arguments():
     assert lib.moe_probe_mfma_rate(4, 0, 4096, 1 << 20, C.byref(fl), None) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_probe_mfma_rate(4, 10, None, 1 << 20, C.byref(fl), None) == B.MOE_ERR_INVALID_ARG
     assert lib.moe_probe_mfma_rate(4, 10, 4096, 4 * 512 - 1, C.byref(fl), None) == B.MOE_ERR_WORKSPACE
+
+
+def test_one_workspace_query_covers_both_calls():
+    for kw in (dict(), dict(T=4096, d=7168, f=2048, E=256, k=8, R=8, local_rank_begin=4, local_rank_end=5),
+               dict(T=0), dict(dtype=B.MOE_F32)):
+        s = good_shape(**kw)
+        assert B.moe_workspace_bytes(s) == max(B.moe_dispatch_workspace_bytes(s), B.moe_forward_workspace_bytes(s))
+        assert B.moe_workspace_bytes(s) > 0
+    assert B.moe_workspace_bytes(good_shape(k=0)) == 0
+
+
+def test_forward_status_and_bounded_forward_reject_bad_arguments():
+    lib = B.lib()
+    flag = C.c_int32(7)
+    assert lib.moe_forward_status(None, C.byref(flag), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_forward_status(4096, None, None) == B.MOE_ERR_INVALID_ARG
+    s = good_shape()
+    tb = B.moe_dispatch(*([4096] * 9))
+    args = (C.byref(s), 4096, 4096, 4096, C.byref(tb), 4096, 4096, 4096, 4096, 1 << 30, None)
+    assert lib.moe_fused_forward_bounded(*args, 0, 0) == B.MOE_ERR_INVALID_ARG       # bound below 1
+    assert lib.moe_fused_forward_bounded(*args, 10, -1) == B.MOE_ERR_INVALID_ARG     # negative extra count
+    f32 = good_shape(dtype=B.MOE_F32)
+    args32 = (C.byref(f32),) + args[1:]
+    assert lib.moe_fused_forward_bounded(*args32, 10, 0) == B.MOE_ERR_UNSUPPORTED    # resident kernel: bf16 only

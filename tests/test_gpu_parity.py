@@ -242,8 +242,7 @@ def test_dispatch_gather_and_combine_reduce_full_size(oracle, name):
 
 # ---------------------------------------------------------------- the two forms of the GEMM-1 => GEMM-2 hand-over
 def ws_error_flag(lay):
-    import torch
-    return int(lay.forward_ws[24 * 4:25 * 4].view(torch.int32).item())
+    return B.moe_forward_status(lay.forward_ws)
 
 
 @pytest.mark.parametrize("name", ["deepseek_like", "qwen_like", "mixtral_like", "gpt_oss_like", "k_tail_bf16",
@@ -291,6 +290,35 @@ def test_one_and_two_launch_forward_full_size(oracle, name):
         fwd(x)
         torch.cuda.synchronize()
         assert torch.equal(lay.y, y_auto) and ws_error_flag(lay) == 0
+
+
+def test_resident_kernel_wait_gives_up_cleanly(oracle):
+    """The bounded wait of the GEMM-1 => GEMM-2 hand-over, forced from the host: every GEMM-2 tile waits for one more
+    GEMM-1 tile than exists and the bound is a handful of polls, so every wait gives up.  All kernels still exit,
+    the call returns, the status word reads 1 and nothing computed from the incomplete tiles looks like a result
+    (NaN rows); the next ordinary call on the same workspace is correct again and the status word reads 0."""
+    import torch
+    cfg = SMALL["deepseek_like"]
+    say("resident kernel: forced give-up")
+    w, lay, x, lg, idx, tw, y, ref = run_forward(cfg, oracle)
+    y_good = lay.y.clone()
+    assert B.moe_forward_status(lay.forward_ws) == 0
+    lay.y.fill_(123.0)
+    B.moe_fused_forward_bounded(lay.shape, x, lay.topk_idx, lay.topk_w, lay.tables, lay.packed_gate_up,
+                                lay.packed_down, lay.y, lay.forward_ws, max_polls=4, wait_extra=1)
+    torch.cuda.synchronize()
+    assert B.moe_forward_status(lay.forward_ws) == 1
+    local = ((idx // cfg.epr >= cfg.local_rank_begin) & (idx // cfg.epr < cfg.local_rank_end)).any(axis=1)
+    yb = lay.y[: cfg.T].float().cpu().numpy()
+    assert np.isnan(yb[local]).all(), "a row computed after a wait gave up is not marked"
+    assert np.all(yb[~local] == 0)
+    # an ample bound and the real count: the ordinary result
+    lay.y.fill_(float("nan"))
+    B.moe_fused_forward_bounded(lay.shape, x, lay.topk_idx, lay.topk_w, lay.tables, lay.packed_gate_up,
+                                lay.packed_down, lay.y, lay.forward_ws, max_polls=1 << 22, wait_extra=0)
+    torch.cuda.synchronize()
+    assert B.moe_forward_status(lay.forward_ws) == 0
+    assert torch.equal(lay.y, y_good)
 
 
 def test_one_launch_forward_rejects_fp32_layers():
