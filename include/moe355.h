@@ -136,6 +136,18 @@ MOE355_API int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_id
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * moe_build_dispatch for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same tables, bit for bit; the scratch (chunk histograms) is a static
+ * device array of 64 * MOE_NOALLOC_MAX_COUNTERS int32 (256 KiB, held by every GPU the library runs on until the
+ * process ends) instead of a caller workspace, so shapes with E + R > MOE_NOALLOC_MAX_COUNTERS are rejected with
+ * MOE_ERR_UNSUPPORTED.  The call allocates and frees nothing.  All calls on one GPU share that GPU's array: calls
+ * that overlap in time on the same GPU (different streams, different threads) race; calls on one stream do not.
+ */
+#define MOE_NOALLOC_MAX_COUNTERS 1024
+MOE355_API int moe_build_dispatch_noalloc(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
+                                          void *stream);
+
+/*
  * One-off re-tiling of the static expert weights into the layout the GEMM kernels stream
  * (not part of the per-step path).  Inputs are the plain "input x output" matrices of the local experts:
  * W_gate, W_up [E_loc, d, f], W_down [E_loc, f, d].  Outputs are opaque buffers of

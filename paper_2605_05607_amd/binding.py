@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
         L.moe_route_topk.argtypes = [sp, vp, vp, vp, vp]
         L.moe_build_dispatch.restype = i32
         L.moe_build_dispatch.argtypes = [sp, vp, dp, vp, sz, vp]
+        L.moe_build_dispatch_noalloc.restype = i32
+        L.moe_build_dispatch_noalloc.argtypes = [sp, vp, dp, vp]
         L.moe_workspace_bytes.restype = sz
         L.moe_workspace_bytes.argtypes = [sp]
         L.moe_forward_status.restype = i32
@@ -210,6 +212,11 @@ def moe_build_dispatch(shape, topk_idx, tables: DispatchTables, workspace, works
     nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     _check(lib().moe_build_dispatch(C.byref(shape), _ptr(topk_idx), C.byref(tables.struct), _ptr(workspace), nbytes,
                                     _stream(stream)), "moe_build_dispatch")
+
+
+def moe_build_dispatch_noalloc(shape, topk_idx, tables: DispatchTables, stream=None) -> None:
+    _check(lib().moe_build_dispatch_noalloc(C.byref(shape), _ptr(topk_idx), C.byref(tables.struct), _stream(stream)),
+           "moe_build_dispatch_noalloc")
 
 
 def moe_workspace_bytes(shape: moe_shape) -> int:

@@ -261,22 +261,15 @@ extern "C" size_t moe_dispatch_workspace_bytes(const moe_shape *shape) {
   return align_up((size_t)kMaxChunks * (shape->E + shape->R) * sizeof(int32_t), 256);
 }
 
-extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
-                                  void *workspace, size_t workspace_bytes, void *stream) {
-  Derived dv;
-  int rc = check_shape(shape, &dv);
-  if (rc != MOE_OK) return rc;
-  if (!topk_idx || !out) return MOE_ERR_INVALID_ARG;
-  if (!out->counts || !out->offsets || !out->perm || !out->inv_perm || !out->rank_counts || !out->rank_offsets ||
-      !out->dedup_tok || !out->dedup_mask || !out->pair_to_dedup)
-    return MOE_ERR_INVALID_ARG;
-  if (!workspace || workspace_bytes < moe_dispatch_workspace_bytes(shape)) return MOE_ERR_WORKSPACE;
+// Both forms of the call: the chunk histograms live in `chunk_ws` (kMaxChunks * (E + R) int32).
+static int build_dispatch_launches(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
+                                   int32_t *chunk_ws, hipStream_t st) {
   const int T = shape->T, E = shape->E, k = shape->k, R = shape->R;
   int tpc;
   const int nch = chunking(T, &tpc);
-  int32_t *chunk_cnt = static_cast<int32_t *>(workspace);
+  int32_t *chunk_cnt = chunk_ws;
   int32_t *chunk_rcnt = chunk_cnt + (size_t)kMaxChunks * E;
-  hipStream_t st = (hipStream_t)stream;
+  int rc;
   begin_launches();
   const size_t sm_wave = (size_t)(E + R) * sizeof(int);
   if (nch > 0) {
@@ -301,6 +294,62 @@ extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_id
                      nwalk, chunk_cnt,
                      chunk_rcnt, out->counts, out->offsets, out->rank_counts, out->rank_offsets, out->perm,
                      out->inv_perm, out->dedup_tok, out->dedup_mask, out->pair_to_dedup);
-  if ((rc = launch_status()) != MOE_OK) return rc;
-  return MOE_OK;
+  return launch_status();
+}
+
+static bool dispatch_outputs_ok(const moe_dispatch *out) {
+  return out && out->counts && out->offsets && out->perm && out->inv_perm && out->rank_counts && out->rank_offsets &&
+         out->dedup_tok && out->dedup_mask && out->pair_to_dedup;
+}
+
+extern "C" int moe_build_dispatch(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
+                                  void *workspace, size_t workspace_bytes, void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!topk_idx || !dispatch_outputs_ok(out)) return MOE_ERR_INVALID_ARG;
+  if (!workspace || workspace_bytes < moe_dispatch_workspace_bytes(shape)) return MOE_ERR_WORKSPACE;
+  return build_dispatch_launches(shape, topk_idx, out, static_cast<int32_t *>(workspace), (hipStream_t)stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// The same call for callers that cannot allocate device memory (code under HIP graph capture, serving loops,
+// harnesses that forbid hipMalloc): the chunk histograms live in a file-scope device array instead of a caller
+// workspace.  Every GPU holds its own copy of the array at its own address; the address is looked up once per device
+// (hipGetSymbolAddress with that device current) and kept.  In host code the array's name is only a handle for that
+// lookup: kernels and copies always get the looked-up pointer.
+// ------------------------------------------------------------------------------------------------
+namespace moe355 {
+constexpr int kStaticMaxCounters = MOE_NOALLOC_MAX_COUNTERS;  // limit on E + R
+static __device__ __align__(256) unsigned char scratch[(size_t)kMaxChunks * kStaticMaxCounters * sizeof(int32_t)];
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];  // zero-initialised: not looked up yet
+
+// Device address of `scratch` on the current device (nullptr on failure).  Allocates nothing.
+static void *scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  g_scratch_ptr[dev].store(p, std::memory_order_release);  // every thread looks up the same address
+  return p;
+}
+}  // namespace moe355
+
+extern "C" int moe_build_dispatch_noalloc(const moe_shape *shape, const int32_t *topk_idx, const moe_dispatch *out,
+                                          void *stream) {
+  Derived dv;
+  int rc = check_shape(shape, &dv);
+  if (rc != MOE_OK) return rc;
+  if (!topk_idx || !dispatch_outputs_ok(out)) return MOE_ERR_INVALID_ARG;
+  if (shape->E + shape->R > kStaticMaxCounters) return MOE_ERR_UNSUPPORTED;  // beyond the static scratch
+  void *ws = scratch_on_current_device();
+  if (!ws) return MOE_ERR_HIP;
+  // Nothing has to start at zero: the histogram kernel overwrites the rows of every chunk that exists and the
+  // placement kernel ignores the others.
+  return build_dispatch_launches(shape, topk_idx, out, static_cast<int32_t *>(ws), (hipStream_t)stream);
 }

@@ -244,6 +244,24 @@ def test_mfma_rate_probe_arguments():
     assert lib.moe_probe_mfma_rate(4, 10, 4096, 4 * 512 - 1, C.byref(fl), None) == B.MOE_ERR_WORKSPACE
 
 
+def test_noalloc_dispatch_rejects_bad_arguments_before_any_device_call():
+    lib = B.lib()
+    s = good_shape()
+    tb = B.moe_dispatch(*([4096] * 9))
+    assert lib.moe_build_dispatch_noalloc(None, 4096, C.byref(tb), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_build_dispatch_noalloc(C.byref(s), None, C.byref(tb), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_build_dispatch_noalloc(C.byref(s), 4096, None, None) == B.MOE_ERR_INVALID_ARG
+    holes = B.moe_dispatch(*([4096] * 8 + [None]))
+    assert lib.moe_build_dispatch_noalloc(C.byref(s), 4096, C.byref(holes), None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_build_dispatch_noalloc(C.byref(good_shape(E=10, R=4)), 4096, C.byref(tb), None) \
+        == B.MOE_ERR_INVALID_ARG
+    # beyond the static scratch (E + R counters per chunk): a clear error, nothing launched
+    big = good_shape(E=1024, R=1, k=2, local_rank_begin=0, local_rank_end=1)
+    assert lib.moe_build_dispatch_noalloc(C.byref(big), 4096, C.byref(tb), None) == B.MOE_ERR_UNSUPPORTED
+    big = good_shape(E=2048, R=2, k=2, local_rank_begin=0, local_rank_end=1)
+    assert lib.moe_build_dispatch_noalloc(C.byref(big), 4096, C.byref(tb), None) == B.MOE_ERR_UNSUPPORTED
+
+
 def test_one_workspace_query_covers_both_calls():
     for kw in (dict(), dict(T=4096, d=7168, f=2048, E=256, k=8, R=8, local_rank_begin=4, local_rank_end=5),
                dict(T=0), dict(dtype=B.MOE_F32)):
