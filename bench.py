@@ -26,11 +26,12 @@ def algorithmic_work(cfg, idx, counts_local):
     local = (idx // epr >= cfg.local_rank_begin) & (idx // epr < cfg.local_rank_end)
     P = int(local.sum())
     U_tok = int(local.any(axis=1).sum())
+    n_sole = int((local.sum(axis=1) == 1).sum())  # rows that GEMM-2 writes straight to y in the output type
     ne = int((counts_local > 0).sum())  # experts whose weights have to be streamed at all
     b = 2 if cfg.dtype == 1 else 4
     d, f, T = cfg.d, cfg.f, cfg.T
     g1 = dict(flops=4.0 * P * d * f, bytes=ne * 2.0 * d * f * b + U_tok * d * b + P * f * b)
-    g2 = dict(flops=2.0 * P * d * f, bytes=ne * 1.0 * d * f * b + P * f * b + P * d * 4)
+    g2 = dict(flops=2.0 * P * d * f, bytes=ne * 1.0 * d * f * b + P * f * b + (P - n_sole) * d * 4 + n_sole * d * b)
     cb = dict(flops=float(P * d), bytes=P * d * 4.0 + T * d * b)
     return P, U_tok, ne, g1, g2, cb
 
@@ -157,6 +158,23 @@ def timed_value(lay, lg, x, K, ev_first, ev_last, every):
     return wall * 1e3 / K, float(durs.mean()), (len(sampled), float(np.median(durs)), float(durs.min()))
 
 
+def step_statistics(lay, lg, x, K):
+    """Per-step durations of K further steps (one event record per step boundary, outside the timed region)."""
+    import numpy as np
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    for e in ev:
+        e.record()
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(K):
+        lay.step(lg, x)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    d = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(K)])
+    return float(np.median(d)), float(d.min())
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +186,9 @@ def main():
     ap.add_argument("--topk", type=int, default=0, help="override k (sweeps)")
     ap.add_argument("--router", default="", help="override the router kind: normal | zipf | forced (sweeps)")
     ap.add_argument("--zipf-s", type=float, default=-1.0, help="override the Zipf exponent of the zipf router (sweeps)")
+    ap.add_argument("--load-std", type=float, default=-1.0, help="training-load model: normal spread of the token "
+                    "distribution across experts with this standard deviation (0.032 typical, 0.01-0.05 swept); "
+                    "selects the loadstd router")
     ap.add_argument("--no-8x-point", action="store_true", help="skip the extra run of the layer at 8 x the tokens")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed extras (phase-split entry points, "
                     "unfused path, reference figures)")
@@ -198,7 +219,7 @@ def main():
     from paper_2605_05607_amd import workloads as wl
 
     cfg = wl.CONFIGS[args.config]
-    swept = bool(args.tokens or args.topk or args.router or args.zipf_s >= 0)
+    swept = bool(args.tokens or args.topk or args.router or args.zipf_s >= 0 or args.load_std >= 0)
     if args.tokens:
         cfg = cfg.scaled(T=args.tokens)
     if args.topk:
@@ -207,6 +228,8 @@ def main():
         cfg = cfg.scaled(router=args.router)
     if args.zipf_s >= 0:
         cfg = cfg.scaled(zipf_s=args.zipf_s)
+    if args.load_std >= 0:
+        cfg = cfg.scaled(router="loadstd", load_std=args.load_std)
     torch.cuda.set_device(0)
     w = wl.make_workload(cfg)
     lay = L.MoELayer(cfg)
@@ -229,6 +252,7 @@ def main():
     # the clocks of a box that has just started working take some tens of steps to settle)
     ms_instr, (prep_ms, g1_ms, g2_ms, cb_ms), front_ms, step_ms = timed_steps(lay, lg, x, 20)
     ms_per_step, gk_ms, n_sampled = timed_value(lay, lg, x, K, 1, 3 if one_launch else 2, every)
+    ms_median, ms_min = step_statistics(lay, lg, x, K)
 
     idx = lay.topk_idx.cpu().numpy().reshape(cfg.T, cfg.k)
     counts = lay.tables.counts.cpu().numpy()
@@ -256,14 +280,17 @@ def main():
 
     out = {
         "metric": "fused MoE layer tokens/s on 1 MI355X", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": ms_median, "ms_per_step_min": ms_min, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if cfg.dtype == wl.BF16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} d={cfg.d} f={cfg.f} E={cfg.E} local={cfg.E_loc} k={cfg.k} "
                                f"R={cfg.R} router={cfg.router}", "step": "moe_route_topk + moe_build_dispatch + "
                    "moe_fused_forward", "weights": "re-tiled once by moe_pack_weights (untimed, static)",
                    "local_pairs_P": P, "tokens_with_local_expert": U_tok, "nonempty_local_experts": ne,
-                   "rows_per_expert_max": int(counts_local.max()), "seed": cfg.seed},
+                   "rows_per_expert_max": int(counts_local.max()), "seed": cfg.seed,
+                   "step_statistics": "ms_per_step_median / _min: a second loop of the same K steps with one event "
+                                      "record per step boundary (outside the timed region)"},
         "roofline": roof,
         "phases_ms": {"note": "separate untimed loop of 20 steps with six event records per step (they slow the step itself), run before the timed region",
                       "instrumented_step": ms_instr, "route_and_tables": front_ms, "tile_table": float(prep_ms), "gemms": float(g1_ms + g2_ms),
@@ -297,13 +324,29 @@ def main():
 
     b = 2 if cfg.dtype == wl.BF16 else 4
     P_cap = cfg.T * min(cfg.k, cfg.E_loc)
-    xs = torch.empty((P_cap, cfg.d), dtype=lay.elt_dtype, device="cuda")
-    t_disp = timed(lambda: B.moe_dispatch_gather(lay.shape, x, lay.tables, xs), 20)
-    disp_bytes = U_tok * cfg.d * b + P * cfg.d * b  # each needed token row read once, every layout row written
+    # Dispatch on its own: every needed token row read once, every layout row written.  Timed twice: on one pair of
+    # buffers (x and xs together fit the 256 MB Infinity Cache, as x does right after the layer that produced it) and
+    # rotating over pairs whose bytes together exceed that cache several times (every read from HBM).
+    disp_bytes = U_tok * cfg.d * b + P * cfg.d * b
+    live = (cfg.T + max(1, P)) * cfg.d * b  # bytes one call touches: x and the P layout rows it writes
+    npair = max(2, min(16, -(-(768 << 20) // live)))
+    xs_bufs = [torch.empty((max(1, P), cfg.d), dtype=lay.elt_dtype, device="cuda") for _ in range(npair)]
+    x_bufs = [x] + [x.clone() for _ in range(npair - 1)]
+    t_disp_warm = timed(lambda: B.moe_dispatch_gather(lay.shape, x, lay.tables, xs_bufs[0]), 20)
+    dturn = [0]
+
+    def dispatch_next():
+        dturn[0] = (dturn[0] + 1) % npair
+        B.moe_dispatch_gather(lay.shape, x_bufs[dturn[0]], lay.tables, xs_bufs[dturn[0]])
+
+    t_disp = timed(dispatch_next, 4 * npair)
     out["dispatch_phase"] = {"entry": "moe_dispatch_gather", "ms": t_disp, "hbm_gbs": disp_bytes / (t_disp * 1e-3) / 1e9,
                              "hbm_frac_of_peak": disp_bytes / (t_disp * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "ms_same_buffers": t_disp_warm,
+                             "hbm_frac_of_peak_same_buffers": disp_bytes / (t_disp_warm * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                             "buffer_pairs_rotated": npair,
                              "bytes": disp_bytes, "bytes_without_dedup": 2 * P * cfg.d * b}
-    del xs
+    del xs_bufs, x_bufs
     # Combine on its own: every weighted row read, every token row written.  (Inside the fused call GEMM-2 writes
     # the rows of tokens with a single local slot itself, so the fused combine kernel moves less than this.)
     # Timed twice: on one buffer (rows partly resident in the 256 MB Infinity Cache, as they are right after GEMM-2
@@ -429,6 +472,31 @@ def main():
                      "dW_down"):
             delattr(lay, name)
         del dy, dWg, dWu, dWd
+    # Two more ranks of the same skewed routing (DeepSeek-shaped workload only): the rank that receives the most pairs
+    # under this seed, and the "hot rank" corner (popular experts first: nearly every pair on rank 0).  Same shapes
+    # and the same packed weight buffers (their values do not matter for the time); labelled extras, not `value`.
+    if cfg.name == "deepseek_v3" and not swept:
+        rank_pairs = counts.reshape(cfg.R, cfg.epr).sum(axis=1)
+        pts = {}
+        for label, cfg_x in (("max_load_rank", cfg.scaled(local_rank_begin=int(rank_pairs.argmax()),
+                                                          local_rank_end=int(rank_pairs.argmax()) + 1)),
+                             ("hot_rank", cfg.scaled(router="zipf_hot", local_rank_begin=0, local_rank_end=1))):
+            wx = w if cfg_x.router == cfg.router else wl.make_workload(cfg_x, weights=False)
+            lay_x = L.MoELayer(cfg_x)
+            lay_x.packed_gate_up, lay_x.packed_down = lay.packed_gate_up, lay.packed_down
+            lgx = lg if wx is w else L.to_device(wx.logits)
+            for _ in range(3):
+                lay_x.step(lgx, x)
+            t_x = timed(lambda: lay_x.step(lgx, x), 10)
+            cx = lay_x.tables.counts.cpu().numpy()[cfg_x.first_local_expert:cfg_x.first_local_expert + cfg_x.E_loc]
+            Px = int(cx.sum())
+            pts[label] = {"local_rank": cfg_x.local_rank_begin, "router": cfg_x.router, "local_pairs_P": Px,
+                          "rows_per_expert_max": int(cx.max()), "nonempty_local_experts": int((cx > 0).sum()),
+                          "gemm_launches": B.moe_forward_gemm_launches(lay_x.shape), "ms_per_step": t_x,
+                          "tokens_per_s": cfg.T / (t_x * 1e-3),
+                          "mfma_tflops_whole_step": 6.0 * Px * cfg.d * cfg.f / (t_x * 1e-3) / 1e12}
+            del lay_x
+        out["skew_points"] = pts
     # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):

@@ -33,6 +33,13 @@ class MoEConfig:
     ``"zipf"``    N(0, 1) + bias[e], bias[e] = -s * ln(1 + pi(e)), pi a seeded permutation of the experts
     ``"forced"``  N(0, 1); a Bernoulli(force_p) subset of tokens gets +16 on every logit of one uniformly
                   drawn virtual rank, so all of its top-k picks fall on that rank
+    ``"zipf_hot"`` as ``"zipf"`` with the identity permutation: the popular experts are the first ones, so nearly all
+                  pairs land on rank 0 (the "hot rank" corner of the skewed load)
+    ``"loadstd"`` the training-load model of the evaluation (token distribution across experts ~ normal, quoted by its
+                  standard deviation, 0.032 for a typical job, swept over 0.01-0.05): expert load fractions
+                  p_e = (1 + c z_e) / E with z_e ~ N(0, 1) and c = load_std / 0.125 (the figure is quoted for groups of
+                  eight experts, where the mean fraction is 1/8), clipped at 0.05 / E and renormalised; logits =
+                  ln p_e + Gumbel noise, so the k picks of a token are draws without replacement in proportion to p
     """
 
     name: str
@@ -49,6 +56,7 @@ class MoEConfig:
     seed: int
     zipf_s: float = 1.1
     force_p: float = 0.1
+    load_std: float = 0.032
 
     @property
     def epr(self) -> int:
@@ -163,6 +171,15 @@ def make_workload(cfg: MoEConfig, weights: bool = True, threads: int = 8) -> Wor
             for t in rows:
                 r = int(rank[t])
                 logits[t, r * epr:(r + 1) * epr] += np.float32(16.0)
+        elif cfg.router == "zipf_hot":
+            bias = (-cfg.zipf_s * np.log1p(np.arange(cfg.E, dtype=np.float64))).astype(np.float32)
+            logits = (logits + bias[None, :]).astype(np.float32)
+        elif cfg.router == "loadstd":
+            p = expert_load_fractions(cfg.E, cfg.load_std, ss_perm)
+            # standard normal -> uniform -> Gumbel, per element (keeps the chunked, thread-independent draw above)
+            from scipy.special import ndtr
+            u = np.clip(ndtr(logits.astype(np.float64)), 1e-12, 1.0 - 1e-12)
+            logits = (np.log(p)[None, :] - np.log(-np.log(u))).astype(np.float32)
         elif cfg.router != "normal":
             raise ValueError(f"unknown router kind {cfg.router!r}")
     logits = np.ascontiguousarray(logits, dtype=np.float32)
@@ -174,6 +191,13 @@ def make_workload(cfg: MoEConfig, weights: bool = True, threads: int = 8) -> Wor
         Wu = _fill_normal((El, cfg.d, cfg.f), cfg.d ** -0.5, ss_u, cfg.dtype, threads)
         Wd = _fill_normal((El, cfg.f, cfg.d), cfg.f ** -0.5, ss_d, cfg.dtype, threads)
     return Workload(cfg, x, logits, Wg, Wu, Wd)
+
+
+def expert_load_fractions(E: int, load_std: float, ss: np.random.SeedSequence) -> np.ndarray:
+    """Expected share of the pairs per expert under the ``"loadstd"`` router (sums to 1)."""
+    z = np.random.default_rng(ss).standard_normal(E)
+    p = np.maximum(1.0 + (load_std / 0.125) * z, 0.05) / E
+    return p / p.sum()
 
 
 def fp8_h_scale(cfg: MoEConfig) -> np.ndarray:

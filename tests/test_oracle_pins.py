@@ -629,3 +629,29 @@ def test_fp8_landmarks_from_the_format_specification(oracle):
     for case in gold["round_to_nearest_even"]:
         got = int(oracle.fp8_encode(np.array([case["value"]], dtype=np.float32))[0])
         assert got == int(case["code"], 16), case
+
+
+# ---------------------------------------------------------------- load models of the synthetic routers (inputs only)
+@pytest.mark.parametrize("std", [0.01, 0.032, 0.05])
+def test_loadstd_router_spreads_the_load_as_requested(oracle, std):
+    """The training-load router: the pairs an expert receives follow its drawn share p_e (top-k of ln p + Gumbel
+    noise = draws without replacement in proportion to p), so the measured spread of the load grows with the
+    requested standard deviation and the measured shares correlate with the drawn ones."""
+    cfg = wl.CONFIGS["table1_m"].scaled(router="loadstd", load_std=std, T=8192)
+    w = wl.make_workload(cfg, weights=False)
+    idx, _ = oracle.route_topk(w.logits, cfg.k)
+    share = np.bincount(idx.ravel(), minlength=cfg.E) / idx.size
+    p = wl.expert_load_fractions(cfg.E, std, np.random.SeedSequence(cfg.seed).spawn(7)[2])
+    assert abs(p.sum() - 1) < 1e-12 and p.min() > 0
+    cv_want = std / 0.125
+    cv_got = share.std() / share.mean()
+    assert 0.6 * cv_want < cv_got < 1.3 * cv_want + 0.03, (cv_want, cv_got)
+    assert np.corrcoef(share, p)[0, 1] > 0.8  # 512 pairs per expert: a few per cent of sampling noise
+
+
+def test_hot_rank_router_puts_nearly_all_pairs_on_rank_zero(oracle):
+    cfg = wl.CONFIGS["deepseek_v3"].scaled(router="zipf_hot", T=1024)
+    w = wl.make_workload(cfg, weights=False)
+    idx, _ = oracle.route_topk(w.logits, cfg.k)
+    on_rank0 = (idx // cfg.epr == 0).mean()
+    assert on_rank0 > 0.85
