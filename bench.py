@@ -402,7 +402,22 @@ def main():
     out["router_logits"] = {"entry": "moe_router_logits", "ms": t_gate, "bytes": gate_bytes,
                             "hbm_gbs": gate_bytes / (t_gate * 1e-3) / 1e9,
                             "hbm_frac_of_peak": gate_bytes / (t_gate * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    del W_r, lg2, ws_r
+    # gate network and routing in one call (the logits never reach memory), against the two calls it replaces
+    ws_x = torch.empty((B.moe_route_from_x_workspace_bytes(lay.shape),), dtype=torch.uint8, device="cuda")
+    idx_x, w_x = torch.empty_like(lay.topk_idx), torch.empty_like(lay.topk_w)
+    t_fused = timed(lambda: B.moe_route_from_x(lay.shape, x, W_r, None, idx_x, w_x, ws_x), 20)
+
+    def two_calls():
+        B.moe_router_logits(lay.shape, x, W_r, lg2, ws_r)
+        B.moe_route_topk(lay.shape, lg2, idx_x, w_x)
+
+    t_two_calls = timed(two_calls, 20)
+    x_bytes = (cfg.T * cfg.d + cfg.E * cfg.d) * b + 2 * cfg.T * cfg.k * 4
+    out["route_from_x"] = {"entry": "moe_route_from_x", "ms": t_fused, "bytes": x_bytes,
+                           "hbm_gbs": x_bytes / (t_fused * 1e-3) / 1e9,
+                           "hbm_frac_of_peak": x_bytes / (t_fused * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                           "ms_router_logits_then_route_topk": t_two_calls}
+    del W_r, lg2, ws_r, ws_x, idx_x, w_x
     # The same step with the FP8 (E4M3) form of the expert GEMMs (weights quantised once, untimed; x quantised inside
     # the step): half the weight bytes, the same number of matrix-core instructions.  Not `value`: the metric is
     # the bf16 layer.

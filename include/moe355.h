@@ -106,6 +106,18 @@ MOE355_API int moe_router_logits(const moe_shape *shape, const void *x, const vo
                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Gate network and routing in one call (the "gate network" of Sec. II-A that selects each token's experts, from the
+ * token rows to the picks): topk_idx / topk_w are those moe_route_topk gives on the logits moe_router_logits gives,
+ * bit for bit (the same partial products, added in the same order), but the logits are summed inside the kernel that
+ * picks and are written to `logits` [T,E] fp32 only if that pointer is not NULL.  x, W_r as for moe_router_logits;
+ * workspace >= moe_route_from_x_workspace_bytes(shape), 16-byte aligned.
+ */
+MOE355_API size_t moe_route_from_x_workspace_bytes(const moe_shape *shape);
+MOE355_API int moe_route_from_x(const moe_shape *shape, const void *x, const void *W_r, float *logits,
+                                int32_t *topk_idx, float *topk_w, void *workspace, size_t workspace_bytes,
+                                void *stream);
+
+/*
  * Routing (Sec. II-A: each token activates the top-k experts chosen by the gate).
  * logits [T,E] fp32.  For each token the k largest logits are selected (ties: lower expert index first)
  * and reported in descending order in topk_idx [T,k]; topk_w [T,k] is the softmax over the logits

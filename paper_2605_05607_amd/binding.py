@@ -66,6 +66,10 @@ def lib() -> C.CDLL:
         L.moe_router_logits.argtypes = [sp, vp, vp, vp, vp, sz, vp]
         L.moe_route_topk.restype = i32
         L.moe_route_topk.argtypes = [sp, vp, vp, vp, vp]
+        L.moe_route_from_x_workspace_bytes.restype = sz
+        L.moe_route_from_x_workspace_bytes.argtypes = [sp]
+        L.moe_route_from_x.restype = i32
+        L.moe_route_from_x.argtypes = [sp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.moe_build_dispatch.restype = i32
         L.moe_build_dispatch.argtypes = [sp, vp, dp, vp, sz, vp]
         L.moe_build_dispatch_noalloc.restype = i32
@@ -201,6 +205,17 @@ def moe_router_logits(shape, x, W_r, logits, workspace, workspace_bytes=None, st
     nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     _check(lib().moe_router_logits(C.byref(shape), _ptr(x), _ptr(W_r), _ptr(logits), _ptr(workspace), nbytes,
                                    _stream(stream)), "moe_router_logits")
+
+
+def moe_route_from_x_workspace_bytes(shape: moe_shape) -> int:
+    return int(lib().moe_route_from_x_workspace_bytes(C.byref(shape)))
+
+
+def moe_route_from_x(shape, x, W_r, logits, topk_idx, topk_w, workspace, workspace_bytes=None, stream=None) -> None:
+    """`logits` may be None: the logits then never reach memory."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().moe_route_from_x(C.byref(shape), _ptr(x), _ptr(W_r), _ptr(logits), _ptr(topk_idx), _ptr(topk_w),
+                                  _ptr(workspace), nbytes, _stream(stream)), "moe_route_from_x")
 
 
 def moe_route_topk(shape, logits, topk_idx, topk_w, stream=None) -> None:

@@ -284,3 +284,19 @@ def test_forward_status_and_bounded_forward_reject_bad_arguments():
     f32 = good_shape(dtype=B.MOE_F32)
     args32 = (C.byref(f32),) + args[1:]
     assert lib.moe_fused_forward_bounded(*args32, 10, 0) == B.MOE_ERR_UNSUPPORTED    # resident kernel: bf16 only
+
+
+def test_route_from_x_rejects_bad_arguments():
+    lib = B.lib()
+    s = good_shape()
+    need = B.moe_route_from_x_workspace_bytes(s)
+    assert need >= s.T * s.E * 4 and B.moe_route_from_x_workspace_bytes(good_shape(k=0)) == 0
+    ok = (4096, 4096, None, 4096, 4096, 4096, need, None)
+    assert lib.moe_route_from_x(C.byref(good_shape(E=10, R=4)), *ok) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_from_x(C.byref(s), None, *ok[1:]) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_from_x(C.byref(s), 4096, None, *ok[2:]) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_from_x(C.byref(s), 4096, 4096, None, None, 4096, 4096, need, None) == B.MOE_ERR_INVALID_ARG
+    assert lib.moe_route_from_x(C.byref(s), 4104, *ok[1:]) == B.MOE_ERR_INVALID_ARG            # x not 16-byte aligned
+    assert lib.moe_route_from_x(C.byref(s), 4096, 4096, None, 4096, 4096, None, need, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_route_from_x(C.byref(s), 4096, 4096, None, 4096, 4096, 4096, need - 1, None) == B.MOE_ERR_WORKSPACE
+    assert lib.moe_route_from_x(C.byref(good_shape(T=0)), *ok) == B.MOE_OK                      # empty layer: a no-op

@@ -501,6 +501,69 @@ def test_router_logits_deepseek_shape_all_tokens(oracle):
     assert n_safe > n // 2
 
 
+def check_route_from_x(oracle, T, d, E, k, dtype, seed, want_logits):
+    """The fused call against the two-call form on the GPU (bit for bit: same partial products, same order) and
+    against the oracle (picks equal wherever the oracle's margins exceed the fp32 deviation, valid elsewhere)."""
+    import torch
+    x, W = router_case(T, d, E, k, dtype, seed)
+    cfg = cfg_of(T=T, d=d, f=8, E=E, k=k, R=1, local_rank_begin=0, local_rank_end=1, dtype=dtype)
+    s = B.shape_of(cfg)
+    xd, Wd = L.to_device(x), L.to_device(W)
+    logits2 = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    ws2 = torch.full((B.moe_router_workspace_bytes(s),), 0xFF, dtype=torch.uint8, device="cuda")
+    idx2 = torch.empty((T, k), dtype=torch.int32, device="cuda")
+    w2 = torch.empty((T, k), dtype=torch.float32, device="cuda")
+    B.moe_router_logits(s, xd, Wd, logits2, ws2)
+    B.moe_route_topk(s, logits2, idx2, w2)
+    ws = torch.full((B.moe_route_from_x_workspace_bytes(s),), 0xFF, dtype=torch.uint8, device="cuda")
+    idx = torch.full((T, k), -1, dtype=torch.int32, device="cuda")
+    w = torch.full((T, k), float("nan"), dtype=torch.float32, device="cuda")
+    logits = torch.full((T, E), float("nan"), dtype=torch.float32, device="cuda") if want_logits else None
+    B.moe_route_from_x(s, xd, Wd, logits, idx, w, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(w, w2), "fused and two-call routing differ"
+    if want_logits:
+        assert torch.equal(logits, logits2)
+    # against the oracle
+    ref = oracle.router_logits(x, W)
+    got = logits2.cpu().numpy().astype(np.float64)
+    ridx, rw = oracle.route_topk(ref.astype(np.float32), k)
+    order = np.argsort(-ref, axis=1, kind="stable")
+    srt = np.take_along_axis(ref, order, axis=1)
+    tmax = np.abs(got - ref).max(axis=1)
+    top = srt[:, :min(k + 1, E)]
+    safe = (top[:, :-1] - top[:, 1:]).min(axis=1) > 2 * tmax if top.shape[1] > 1 else np.ones(T, bool)
+    ih, wh = idx.cpu().numpy(), w.cpu().numpy()
+    assert np.array_equal(ih[safe], ridx[safe])
+    assert np.abs(wh[safe] - rw[safe]).max() <= 1e-5 if safe.any() else True  # weights follow logits that differ by tmax
+    picked = np.take_along_axis(ref, ih.astype(np.int64), axis=1)
+    assert np.all(picked >= (srt[:, k - 1] - 2 * tmax)[:, None])
+    assert all(len(set(r)) == k for r in ih.tolist())
+    return int(safe.sum())
+
+
+@pytest.mark.parametrize("T,d,E,k,dtype,want_logits", [(1, 8, 1, 1, wl.BF16, True), (70, 72, 6, 3, wl.BF16, False),
+                                                       (130, 24, 65, 4, wl.BF16, True),
+                                                       (300, 520, 128, 8, wl.BF16, False),
+                                                       (90, 136, 300, 4, wl.BF16, True),
+                                                       (700, 64, 640, 6, wl.BF16, True),    # beyond a wave's registers
+                                                       (2100, 64, 16, 2, wl.BF16, False),
+                                                       (33, 40, 12, 2, wl.F32, True)])
+def test_route_from_x_small(oracle, T, d, E, k, dtype, want_logits):
+    say(f"route from x T={T} d={d} E={E} k={k} dtype={dtype} logits={want_logits}")
+    n_safe = check_route_from_x(oracle, T, d, E, k, dtype, seed=T + d + 1, want_logits=want_logits)
+    say(f"  {n_safe} of {T} tokens compared pick by pick with the oracle")
+
+
+@pytest.mark.parametrize("name", ["deepseek_v3", "qwen3", "gpt_oss"])
+def test_route_from_x_full_size(oracle, name):
+    cfg = wl.CONFIGS[name]
+    say(f"route from x at the {name} shape, every token")
+    n_safe = check_route_from_x(oracle, cfg.T, cfg.d, cfg.E, cfg.k, wl.BF16, seed=78, want_logits=False)
+    say(f"  {n_safe} of {cfg.T} tokens compared pick by pick with the oracle")
+    assert n_safe > cfg.T // 2
+
+
 # ---------------------------------------------------------------- FP8 form of the expert GEMMs
 @pytest.mark.parametrize("rows,cols", [(1, 8), (37, 72), (300, 448), (64, 7168)])
 def test_fp8_quantize_rows_bit_exact(oracle, rows, cols):
