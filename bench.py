@@ -390,7 +390,18 @@ def main():
     out["hand_over_comparison"] = {"default_gemm_launches": 1 if one_launch else 2, "two_launch_forward_ms": t_two,
                                    "gemm1_ms": ev2[1].elapsed_time(ev2[2]), "gemm2_ms": ev2[2].elapsed_time(ev2[3])}
     if cfg.dtype == wl.BF16:
-        out["hand_over_comparison"]["one_launch_forward_ms"] = timed(lambda: lay.forward_one_launch(x), 5)
+        # the three forms in rotating order (the clock drifts with load), median of the rounds
+        forms = [("two_launch_forward_ms", lay.forward_two_launch), ("one_launch_forward_ms", lay.forward_one_launch),
+                 ("resident_with_combine_forward_ms", lay.forward_resident)]
+        rounds = {k: [] for k, _ in forms}
+        for _ in range(6):
+            forms = forms[1:] + forms[:1]
+            for key, fn in forms:
+                rounds[key].append(timed(lambda: fn(x), 5))
+        for key, v in rounds.items():
+            out["hand_over_comparison"][key] = float(np.median(v))
+        out["hand_over_comparison"]["note"] = ("forward call = tile table + GEMMs + Combine; resident_with_combine = "
+                                               "GEMM-1, GEMM-2 and Combine in one launch (moe_fused_forward_resident)")
     del lay_u
     # The gate network ahead of the routing (not part of the timed step: the logits are an input of the layer):
     # a skinny product bound by reading x once.

@@ -239,6 +239,25 @@ MOE355_API int moe_fused_forward_one_launch(const moe_shape *shape, const void *
                                             void *const *events);
 
 /*
+ * moe_fused_forward_resident: the tile table, then ONE launch of resident workgroups (one per compute unit) that runs
+ * GEMM-1 (token gather fused), GEMM-2 and Combine: the fused-kernel structure of Sec. IV-A with readiness-gated issue
+ * (Sec. IV-B, IV-C) on one GPU.  A workgroup that finds no GEMM-1 item left takes GEMM-2 items (each waits for the
+ * counter of its M tile's GEMM-1 items), and one that finds no GEMM-2 item left reduces tokens, one wave per token:
+ * the wave waits for the counters of finished GEMM-2 items of every M tile that holds one of the token's rows, then
+ * sums the rows in slot order.  y is bit-identical to moe_fused_forward's.  bf16 layers with at most 4091 local experts (the
+ * tile table's LDS), MOE_ERR_UNSUPPORTED otherwise.  Arguments as
+ * moe_fused_forward_one_launch ([2] and [3] of `events` are recorded together after the launch, [4] right after);
+ * max_polls: bound on the polls of one wait (0 = the library's default of several seconds); wait_extra: every wait
+ * expects that many more finished tiles than exist (0 in normal use; > 0 with a small bound is the test of the
+ * give-up path: all kernels still exit, rows computed from incomplete data are NaN, moe_forward_status reports 1).
+ */
+MOE355_API int moe_fused_forward_resident(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                          const float *topk_w, const moe_dispatch *tables,
+                                          const void *packed_gate_up, const void *packed_down, void *y,
+                                          void *workspace, size_t workspace_bytes, void *stream,
+                                          void *const *events, int max_polls, int wait_extra);
+
+/*
  * Phase-split entry points, used to measure Dispatch and Combine on their own (Sec. VI "pure
  * communication" test) and as building blocks of the unfused comparison path.
  *

@@ -90,6 +90,8 @@ def lib() -> C.CDLL:
             fn = getattr(L, name)
             fn.restype = i32
             fn.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp)]
+        L.moe_fused_forward_resident.restype = i32
+        L.moe_fused_forward_resident.argtypes = [sp, vp, vp, vp, dp, vp, vp, vp, vp, sz, vp, C.POINTER(vp), i32, i32]
         L.moe_route_topk_gate.restype = i32
         L.moe_route_topk_gate.argtypes = [sp, vp, vp, i32, vp, vp, vp]
         L.moe_probe_mfma_rate.restype = i32
@@ -310,6 +312,18 @@ def moe_fused_forward_one_launch(shape, x, topk_idx, topk_w, tables, packed_gate
     """`events`: None or five raw hipEvent_t handles as for moe_fused_forward_timed."""
     _forward_choice("moe_fused_forward_one_launch", shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down,
                     y, workspace, events, workspace_bytes, stream)
+
+
+def moe_fused_forward_resident(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                               events=None, max_polls: int = 0, wait_extra: int = 0, workspace_bytes=None,
+                               stream=None) -> None:
+    """Tile table, then ONE launch for GEMM-1, GEMM-2 and Combine.  max_polls 0 = the library's default bound."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    arr = None if events is None else (C.c_void_p * 5)(*[C.c_void_p(int(e)) if e else None for e in events])
+    _check(lib().moe_fused_forward_resident(C.byref(shape), _ptr(x), _ptr(topk_idx), _ptr(topk_w),
+                                            C.byref(tables.struct), _ptr(packed_gate_up), _ptr(packed_down), _ptr(y),
+                                            _ptr(workspace), nbytes, _stream(stream), arr, int(max_polls),
+                                            int(wait_extra)), "moe_fused_forward_resident")
 
 
 def moe_unfused_forward(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,

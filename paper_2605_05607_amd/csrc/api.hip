@@ -47,6 +47,8 @@ FwdLayout forward_layout(const moe_shape *s, const Derived &dv) {
   L.row_w = take(rows * sizeof(float));
   L.row_sole = take(rows * sizeof(int32_t));
   L.tile_ready = take((size_t)dv.max_mtiles * sizeof(int32_t));
+  L.row_tile = take(rows * sizeof(int32_t));
+  L.tile_done = take((size_t)dv.max_mtiles * sizeof(int32_t));
   L.h = take(rows * (size_t)s->f * dv.elt);
   L.o = take(rows * (size_t)s->d * sizeof(float));
   L.total = off;

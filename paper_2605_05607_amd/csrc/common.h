@@ -70,6 +70,8 @@ struct FwdLayout {
   size_t row_w;     // float[P_cap]       gate weight of each local row
   size_t row_sole;  // int32[P_cap]       the row's token if it is that token's only local slot, else -1
   size_t tile_ready;  // int32[max_mtiles] GEMM-1 items finished per M tile (hand-over inside the resident kernel)
+  size_t row_tile;    // int32[P_cap]      M tile of each local row        } resident kernel that also runs
+  size_t tile_done;   // int32[max_mtiles] GEMM-2 items finished per M tile } Combine
   size_t h;         // elt  [P_cap, f]
   size_t o;         // float[P_cap, d]
   size_t total;

@@ -19,7 +19,7 @@ namespace moe355 {
 // Host-side launch helpers
 // ------------------------------------------------------------------------------------------------
 struct Ws {
-  int32_t *header, *row_tok, *row_sole, *tile_ready;
+  int32_t *header, *row_tok, *row_sole, *tile_ready, *row_tile, *tile_done;
   int4 *work1, *work2;
   float *row_w;
   void *h;
@@ -36,18 +36,28 @@ static Ws carve(void *workspace, const FwdLayout &L) {
   w.row_w = reinterpret_cast<float *>(b + L.row_w);
   w.row_sole = reinterpret_cast<int32_t *>(b + L.row_sole);
   w.tile_ready = reinterpret_cast<int32_t *>(b + L.tile_ready);
+  w.row_tile = reinterpret_cast<int32_t *>(b + L.row_tile);
+  w.tile_done = reinterpret_cast<int32_t *>(b + L.tile_done);
   w.h = b + L.h;
   w.o = reinterpret_cast<float *>(b + L.o);
   return w;
 }
 
-// sole != nullptr: also mark the rows GEMM-2 may write straight to y (see the GEMM-2 epilogue)
+// LDS of the tile-table kernel: three (with the row -> tile map: four) per-expert arrays and the scan scratch.
+static size_t prep_lds_bytes(const Derived &dv, bool combine_tables) {
+  return (size_t)((combine_tables ? 4 : 3) * dv.E_loc + 1 + 17) * sizeof(int);
+}
+
+// sole != nullptr: also mark the rows GEMM-2 may write straight to y (see the GEMM-2 epilogue);
+// combine_tables: also the row -> M tile map and the cleared GEMM-2 counters of the resident kernel's Combine stage
 static int launch_prep(const moe_shape *s, const Derived &dv, const moe_dispatch *tb, const int32_t *topk_idx,
-                       const float *topk_w, const Ws &w, int32_t *sole, hipStream_t st) {
+                       const float *topk_w, const Ws &w, int32_t *sole, hipStream_t st,
+                       bool combine_tables = false) {
   const int blocks = (int)std::min<int64_t>(1024, std::max<int64_t>(1, (dv.P_cap + 255) / 256));
-  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), (size_t)(3 * dv.E_loc + 1 + 17) * sizeof(int), st,
+  hipLaunchKernelGGL(fwd_prep_kernel, dim3(blocks), dim3(256), prep_lds_bytes(dv, combine_tables), st,
                      tb->offsets, tb->perm, topk_w, s->T, s->k, dv.e_lo, dv.E_loc, dv.bm, (int)dv.P_cap, dv.max_mtiles,
-                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w, topk_idx, sole, w.tile_ready);
+                     dv.nt1, dv.nt2, w.header, w.work1, w.work2, w.row_tok, w.row_w, topk_idx, sole, w.tile_ready,
+                     combine_tables ? w.row_tile : nullptr, combine_tables ? w.tile_done : nullptr);
   return launch_status();
 }
 
@@ -81,7 +91,8 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
                         const void *packed_gu, const void *packed_down, const Ws &w, const int32_t *sole, void *y,
                         hipStream_t st, void *const *events = nullptr, bool pipelined = false,
                         const Fp8Operands *q = nullptr, void *keep_gu = nullptr, float *keep_o = nullptr,
-                        int max_polls = kMaxPolls, int wait_extra = 0) {
+                        int max_polls = kMaxPolls, int wait_extra = 0, const moe_dispatch *combine_tb = nullptr,
+                        const int32_t *topk_idx = nullptr) {
   auto mark = [&](int i) {
     if (events && events[i]) (void)hipEventRecord((hipEvent_t)events[i], st);
   };
@@ -152,6 +163,18 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
         if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_train_pipeline_kernel), 2 * kStageBytes, done_tp))
           return MOE_ERR_HIP;
         hipLaunchKernelGGL(gemm_train_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
+                           pa);
+      } else if (combine_tb) {
+        // Combine as the third stage of the same launch (wait_extra also raises its target, for the give-up test)
+        static std::atomic<uint64_t> done_c{0};
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_combine_kernel), 2 * kStageBytes, done_c))
+          return MOE_ERR_HIP;
+        pa.tile_done = w.tile_done; pa.row_tile = w.row_tile;
+        pa.topk_idx = topk_idx; pa.inv_perm = combine_tb->inv_perm; pa.offsets = combine_tb->offsets;
+        pa.header = w.header;
+        pa.T = s->T; pa.k = s->k; pa.e_lo = dv.e_lo; pa.E_loc = dv.E_loc; pa.P_cap = (int)dv.P_cap;
+        pa.nt2 = dv.nt2 + wait_extra; pa.n_mtiles_cap = dv.max_mtiles;
+        hipLaunchKernelGGL(gemm_bf16_combine_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
                            pa);
       } else {
         hipLaunchKernelGGL(gemm_bf16_pipeline_kernel, dim3((unsigned)n_cu), dim3(kGemmThreads), 2 * kStageBytes, st,
@@ -263,9 +286,13 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
        reinterpret_cast<uintptr_t>(packed_down)) % 16 != 0)
     return MOE_ERR_INVALID_ARG;
   if ((int64_t)dv.max_mtiles * std::max(dv.nt1, dv.nt2) > (int64_t)1 << 30) return MOE_ERR_UNSUPPORTED;
-  // gemm_launches: 0 = by shape, 1 = resident kernel with the tile-level hand-over (bf16 only), 2 = two launches
-  if (gemm_launches == 1 && shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
-  const bool pipelined = (gemm_launches ? gemm_launches : moe_forward_gemm_launches(shape)) == 1;
+  // gemm_launches: 0 = by shape, 1 = resident kernel with the tile-level hand-over (bf16 only), 2 = two launches,
+  // 3 = resident kernel that also runs Combine (bf16 inference forward only)
+  if ((gemm_launches == 1 || gemm_launches == 3) && shape->dtype != MOE_BF16) return MOE_ERR_UNSUPPORTED;
+  const bool with_combine = gemm_launches == 3;
+  if (with_combine && (!fused || fp8 || keep)) return MOE_ERR_UNSUPPORTED;
+  if (with_combine && prep_lds_bytes(dv, true) > 64 * 1024) return MOE_ERR_UNSUPPORTED;  // the tile table's LDS
+  const bool pipelined = with_combine || (gemm_launches ? gemm_launches : moe_forward_gemm_launches(shape)) == 1;
   // a work item packs its N tile and its M-tile id into one word
   if (std::max(dv.nt1, dv.nt2) >= 1 << kTileShift || dv.max_mtiles >= 1 << (31 - kTileShift)) return MOE_ERR_UNSUPPORTED;
   // the GEMM kernels address A rows with 32-bit element offsets (row * row length)
@@ -306,13 +333,14 @@ static int forward_common(const moe_shape *shape, const void *x, const int32_t *
                                                    align_up(fp8_tile_bytes(shape, dv, 1), 256));
     q.h_scale = h_scale;
   }
-  if ((rc = launch_prep(shape, dv, tables, topk_idx, topk_w, w, sole, st)) != MOE_OK) return rc;
+  if ((rc = launch_prep(shape, dv, tables, topk_idx, topk_w, w, sole, st, with_combine)) != MOE_OK) return rc;
   mark(1);
   if (fused) {
     if ((rc = launch_gemms(shape, dv, x, w.row_tok, shape->d, packed_gate_up, packed_down, w, sole, y, st,
-                           events, pipelined, fp8 ? &q : nullptr, keep_gu, keep_o, max_polls, wait_extra)) != MOE_OK)
+                           events, pipelined, fp8 ? &q : nullptr, keep_gu, keep_o, max_polls, wait_extra,
+                           with_combine ? tables : nullptr, topk_idx)) != MOE_OK)
       return rc;
-    rc = launch_combine(shape, dv, keep ? keep_o : w.o, topk_idx, tables, y, sole != nullptr, st);
+    if (!with_combine) rc = launch_combine(shape, dv, keep ? keep_o : w.o, topk_idx, tables, y, sole != nullptr, st);
     mark(4);
     return rc;
   }
@@ -473,6 +501,16 @@ extern "C" int moe_fused_forward_one_launch(const moe_shape *shape, const void *
                         workspace_bytes, stream, true, events, 1);
 }
 
+extern "C" int moe_fused_forward_resident(const moe_shape *shape, const void *x, const int32_t *topk_idx,
+                                          const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
+                                          const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
+                                          void *stream, void *const *events, int max_polls, int wait_extra) {
+  if (max_polls < 0 || wait_extra < 0) return MOE_ERR_INVALID_ARG;
+  return forward_common(shape, x, topk_idx, topk_w, tables, packed_gate_up, packed_down, y, workspace,
+                        workspace_bytes, stream, true, events, 3, nullptr, nullptr, max_polls ? max_polls : kMaxPolls,
+                        wait_extra);
+}
+
 extern "C" int moe_unfused_forward(const moe_shape *shape, const void *x, const int32_t *topk_idx,
                                    const float *topk_w, const moe_dispatch *tables, const void *packed_gate_up,
                                    const void *packed_down, void *y, void *workspace, size_t workspace_bytes,
@@ -523,6 +561,7 @@ static BwdLayout backward_layout(const moe_shape *s, const Derived &dvb) {
   L.t.row_w = take(rows * sizeof(float));
   L.t.row_sole = take(rows * sizeof(int32_t));
   L.t.tile_ready = take((size_t)dvb.max_mtiles * sizeof(int32_t));
+  L.t.row_tile = L.t.tile_done = 0;  // forward only
   L.t.h = L.t.o = 0;
   L.dgu = take(rows * 2 * (size_t)s->f * 2);
   L.hw = take(rows * (size_t)s->f * 2);

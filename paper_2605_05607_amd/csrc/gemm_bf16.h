@@ -560,15 +560,24 @@ struct PipelineArgs {
   int32_t *error;       // set if a wait gave up (cannot happen unless the lists are corrupt)
   int nt1;              // GEMM-1 items per M tile a GEMM-2 item waits for
   int max_polls;        // bound on the polls of one wait (x ~1 us), so that no wave can wait forever
+  // Combine stage (gemm_bf16_combine_kernel only)
+  int32_t *tile_done;         // [M tiles] GEMM-2 items finished per M tile
+  const int32_t *row_tile;    // [P] M tile of each local row
+  const int32_t *topk_idx, *inv_perm, *offsets, *header;
+  int T, k, e_lo, E_loc, P_cap, nt2, n_mtiles_cap;
 };
 
 constexpr int kMaxPolls = 1 << 22;  // default bound: several seconds
 
 // All items of one GEMM that this workgroup can get hold of: home queue first, then the other queues.
+// tile_done (GEMM-2 only, may be null): counter per M tile that every finished item of the tile is counted in, for
+// the Combine stage that follows in the same launch; s_done: kDoneCap ints of LDS (tiles of the finished items).
+constexpr int kDoneCap = 256;
 template <bool GATED, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char *smem, int *s_item,
                                                 int32_t *__restrict__ tickets, int32_t *__restrict__ tile_ready,
-                                                int32_t *__restrict__ error, int nt1, int max_polls) {
+                                                int32_t *__restrict__ error, int nt1, int max_polls,
+                                                int32_t *__restrict__ tile_done = nullptr, int *s_done = nullptr) {
   const int home = blockIdx.x & 7;
   const int n_items = *g.n_items;
   const int n_virtual = (n_items + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk);
@@ -600,6 +609,23 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
       qsel = next;
     }
     return q;
+  };
+  // GEMM-2 items that feed Combine in the same launch: the o rows (and the y rows of sole slots) of all items this
+  // workgroup has finished become visible device-wide with ONE release, then every item is counted in its M tile's
+  // counter.  (A release per item costs an L2 write-back of the fp32 rows each time: measured 4 % of the launch.)
+  // Counting late is safe: the items are in the hands of a running workgroup until they are counted.
+  int n_pending = 0;  // finished, not yet counted (the same in every thread)
+  auto flush_done = [&]() {
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // this wave's stores have been acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0 && n_pending > 0) {
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // the write-back is complete before the counters move
+      for (int i = 0; i < n_pending; ++i)
+        __hip_atomic_fetch_add(&tile_done[s_done[i]], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    n_pending = 0;
+    __syncthreads();  // the list may be overwritten
   };
   // (Drawing the next ticket one item ahead, to hide the latency of the atomic, was measured slower: a workgroup
   // that holds a long item while it finishes another one keeps that item from an idle workgroup.)
@@ -648,6 +674,121 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
       }
       __syncthreads();
       gemm_bf16_item<false, true, FP8>(g, smem, item, s_item[1]);
+      if (tile_done) {
+        // remembered, counted later (flush_done): one write-back for all the items of this workgroup
+        if (threadIdx.x == 0) s_done[n_pending] = tile;
+        // (every thread counts: a uniform decision.)  Counting every item at once towards the end of the launch, so
+        // that idle workgroups can reduce tokens while the last items run, was measured: no gain, the rows of the
+        // last items are what the reduction waits for.
+        if (++n_pending == kDoneCap) flush_done();
+      }
+    }
+  }
+  if (!GATED && tile_done) flush_done();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Combine as the last stage of the resident kernel (readiness-gated issue of Sec. IV-C on one GPU): a workgroup
+// that has seen every GEMM-2 queue empty turns to the tokens.  One wave per token, tokens dealt round-robin over all
+// resident waves.  The wave resolves the token's local slots (one lane per slot), waits until the GEMM-2 items of
+// every M tile that holds one of those rows have been counted in tile_done (all of them are in the hands of running
+// workgroups by then, so the wait ends), and sums the rows in slot order in fp32, exactly as combine_kernel does:
+// bit-identical y.  Tokens with one local slot were written by GEMM-2 itself; tokens with none get zeros.
+// Acquire side as in the GEMM-2 wait: relaxed device-scope polls, one acquire fence, then the loads.
+// A wait that gives up raises the error word and the token's row is written as NaN.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void resident_combine(const PipelineArgs &p) {
+  int tid = threadIdx.x;
+  asm volatile("" : "+v"(tid));
+  const int lane = tid & 63;
+  const int n_waves = gridDim.x * (kGemmThreads / 64);
+  const int base = p.offsets[p.e_lo];
+  const int P = min(p.header[1], p.P_cap);
+  const int d = p.g2.N;
+  const float *rows = static_cast<const float *>(p.g2.out);
+  bf16_t *y = static_cast<bf16_t *>(p.g2.y);
+  for (int t = blockIdx.x * (kGemmThreads / 64) + (tid >> 6); t < p.T; t += n_waves) {  // t is wave-uniform
+    int row = -1, tile = 0;
+    if (lane < p.k) {
+      const int e = p.topk_idx[(size_t)t * p.k + lane];
+      if (e >= p.e_lo && e < p.e_lo + p.E_loc) {
+        const int r = p.inv_perm[(size_t)t * p.k + lane] - base;
+        if (r >= 0 && r < P) {
+          row = r;
+          tile = min(max(p.row_tile[r], 0), p.n_mtiles_cap - 1);
+        }
+      }
+    }
+    uint64_t slots = __ballot(row >= 0);
+    const int n = __popcll(slots);
+    if (n == 1) continue;  // GEMM-2 has written this token's row
+    bf16_t *yrow = y + (size_t)t * d;
+    int poison = 0;
+    if (n > 1) {
+      int polls = 0;
+      for (;;) {
+        const bool ok = row < 0 || __hip_atomic_load(&p.tile_done[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= p.nt2;
+        if (__ballot(!ok) == 0) break;
+        __builtin_amdgcn_s_sleep(32);
+        if (++polls > p.max_polls) {
+          if (lane == 0) __hip_atomic_store(p.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          poison = 1;
+          break;
+        }
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
+    // 4 pieces of 512 columns at a time (8 per lane each); two slots' loads are in flight together
+    for (int c0 = lane * 8; c0 < d; c0 += 4 * 512) {
+      float acc[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc[u][q] = 0.f;
+      uint64_t s = slots;
+      while (s) {
+        const int j0 = __builtin_ctzll(s);
+        s &= s - 1;
+        const float *src0 = rows + (size_t)__builtin_amdgcn_readlane(row, j0) * d;
+        const bool two = s != 0;
+        const int j1 = two ? __builtin_ctzll(s) : j0;
+        s &= s - 1;  // (0 stays 0)
+        const float *src1 = rows + (size_t)__builtin_amdgcn_readlane(row, j1) * d;
+        f32x4 a[4][2], b[4][2];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int c = c0 + u * 512;
+          if (c < d) {
+            a[u][0] = *reinterpret_cast<const f32x4 *>(src0 + c);
+            a[u][1] = *reinterpret_cast<const f32x4 *>(src0 + c + 4);
+            if (two) {
+              b[u][0] = *reinterpret_cast<const f32x4 *>(src1 + c);
+              b[u][1] = *reinterpret_cast<const f32x4 *>(src1 + c + 4);
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (c0 + u * 512 < d) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc[u][q] += a[u][q >> 2][q & 3];
+            if (two) {
+#pragma unroll
+              for (int q = 0; q < 8; ++q) acc[u][q] += b[u][q >> 2][q & 3];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = c0 + u * 512;
+        if (c < d) {
+          bf16x8 o;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) o[q] = poison ? (bf16_t)__builtin_nanf("") : (bf16_t)acc[u][q];
+          *reinterpret_cast<bf16x8 *>(yrow + c) = o;
+        }
+      }
     }
   }
 }
@@ -657,6 +798,17 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(con
   __shared__ int s_item[2];  // [0] list position drawn by thread 0, [1] its wait gave up
   gemm_bf16_drain<true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
   gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
+}
+
+// The resident kernel with Combine as its third stage: the whole layer after the tile table in one launch.
+__global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_combine_kernel(const PipelineArgs p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
+  __shared__ int s_item[2];
+  gemm_bf16_drain<true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
+  __shared__ int s_done[kDoneCap];
+  gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls, p.tile_done,
+                         s_done);
+  resident_combine(p);
 }
 
 // The same resident kernel for the training forward: GEMM-1 also keeps g and u.

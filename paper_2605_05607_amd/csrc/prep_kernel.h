@@ -8,7 +8,9 @@ namespace moe355 {
 // Work lists and per-row metadata of the local layout segment.
 // header[0] = work items of GEMM-1, header[1] = P (local rows), header[2] = first layout row of the segment,
 // header[3] = work items of GEMM-2, header[4] = M tiles; header[8..15] / [16..23] = ticket counters of the GEMM-1 /
-// GEMM-2 queues and header[24] = error flag of the resident GEMM kernel (all cleared here).
+// GEMM-2 queues and header[24] = error flag of the resident GEMM kernel (all cleared here).  row_tile / tile_done
+// (both may be null): M tile of every local row and the per-tile counter of finished GEMM-2 items, for the resident
+// kernel that also runs Combine.
 //
 // A work item is one output tile (expert, M tile, N tile): int4 (local expert, first local row, valid rows,
 // N tile | M-tile id << 12).  Full M tiles come first and the partial tile of each
@@ -35,15 +37,19 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
                                                        float *__restrict__ row_w,
                                                        const int32_t *__restrict__ topk_idx,
                                                        int32_t *__restrict__ row_sole,
-                                                       int32_t *__restrict__ tile_ready) {
+                                                       int32_t *__restrict__ tile_ready,
+                                                       int32_t *__restrict__ row_tile,
+                                                       int32_t *__restrict__ tile_done) {
   // LDS: full0[E_loc + 1] first full M tile of each expert | part[E_loc] rows of its partial tile (0 = none) |
   //      order[E_loc] partial tiles: first the large ones (> kStreamRows rows), largest first, then the
-  //      streaming ones, largest first | 17 ints of scan scratch
+  //      streaming ones, largest first | only with row_tile: pos[E_loc] place of each expert's partial tile in
+  //      `order` | 17 ints of scan scratch
   extern __shared__ int lds[];
   int *full0 = lds;
   int *part = full0 + E_loc + 1;
   int *order = part + E_loc;
-  int *scratch = order + E_loc;
+  int *pos = order + E_loc;
+  int *scratch = row_tile ? pos + E_loc : pos;
   const int base = offsets[e_lo];
   const int P = max(0, min(P_cap, offsets[e_lo + E_loc] - base));
   const long long npairs = (long long)T * k;
@@ -99,6 +105,7 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       rank += E_loc <= 1024 ? (po > mine || (po == mine && o < le)) : (o < le);
     }
     order[(small ? n_big : 0) + rank] = le;
+    if (row_tile) pos[le] = (small ? n_big : 0) + rank;
   }
   __syncthreads();
   n_full = min(n_full, max_mtiles);
@@ -114,7 +121,26 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     header[4] = n_tiles;
     for (int i = 8; i <= 24; ++i) header[i] = 0;
   }
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles; i += gridDim.x * blockDim.x) tile_ready[i] = 0;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles; i += gridDim.x * blockDim.x) {
+    tile_ready[i] = 0;
+    if (tile_done) tile_done[i] = 0;
+  }
+  // M tile of every local row (the resident kernel's Combine stage looks up the tile whose GEMM-2 items it waits for)
+  if (row_tile) {
+    for (int r = blockIdx.x * blockDim.x + threadIdx.x; r < P; r += gridDim.x * blockDim.x) {
+      // expert of row r: largest le whose first row is <= r
+      int a = 0, b = E_loc;
+      while (b - a > 1) {
+        const int mid = (a + b) >> 1;
+        if (min(P, offsets[e_lo + mid] - base) <= r) a = mid; else b = mid;
+      }
+      const int start = min(P, offsets[e_lo + a] - base);
+      const int cnt = min(P, offsets[e_lo + a + 1] - base) - start;
+      const int mt = (r - start) / bm;
+      const int tile = mt < cnt / bm ? full0[a] + mt : n_full + pos[a];
+      row_tile[r] = min(tile, max(n_tiles - 1, 0));
+    }
+  }
   for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < n1 + n2; q += gridDim.x * blockDim.x) {
     const bool second = q >= n1;
     const int Nt = second ? nt2 : nt1;

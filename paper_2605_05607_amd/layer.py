@@ -119,6 +119,11 @@ class MoELayer:
         B.moe_fused_forward_one_launch(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
                                        self.packed_down, self.y, self.forward_ws, events)
 
+    def forward_resident(self, x, events=None) -> None:
+        """GEMM-1, GEMM-2 and Combine in one launch."""
+        B.moe_fused_forward_resident(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
+                                     self.packed_down, self.y, self.forward_ws, events)
+
     def forward_unfused(self, x) -> None:
         B.moe_unfused_forward(self.shape, x, self.topk_idx, self.topk_w, self.tables, self.packed_gate_up,
                               self.packed_down, self.y, self.forward_ws)

@@ -281,7 +281,14 @@ def test_forward_status_and_bounded_forward_reject_bad_arguments():
     args = (C.byref(s), 4096, 4096, 4096, C.byref(tb), 4096, 4096, 4096, 4096, 1 << 30, None)
     assert lib.moe_fused_forward_bounded(*args, 0, 0) == B.MOE_ERR_INVALID_ARG       # bound below 1
     assert lib.moe_fused_forward_bounded(*args, 10, -1) == B.MOE_ERR_INVALID_ARG     # negative extra count
+    ev = (C.c_void_p * 5)()
+    assert lib.moe_fused_forward_resident(*args, ev, -1, 0) == B.MOE_ERR_INVALID_ARG   # negative bound
+    assert lib.moe_fused_forward_resident(*args, ev, 0, -1) == B.MOE_ERR_INVALID_ARG   # negative extra count
+    assert lib.moe_fused_forward_resident(C.byref(s), None, *args[2:], None, 0, 0) == B.MOE_ERR_INVALID_ARG
+    small_ws = args[:9] + (16, None)
+    assert lib.moe_fused_forward_resident(*small_ws, None, 0, 0) == B.MOE_ERR_WORKSPACE
     f32 = good_shape(dtype=B.MOE_F32)
+    assert lib.moe_fused_forward_resident(C.byref(f32), *args[1:], None, 0, 0) == B.MOE_ERR_UNSUPPORTED  # bf16 only
     args32 = (C.byref(f32),) + args[1:]
     assert lib.moe_fused_forward_bounded(*args32, 10, 0) == B.MOE_ERR_UNSUPPORTED    # resident kernel: bf16 only
 

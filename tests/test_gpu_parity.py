@@ -191,7 +191,7 @@ def full_size_forward_case(oracle, cfg):
     assert np.isfinite(y).all() and np.abs(y[local]).max(axis=1).min() > 0
     y_auto = lay.y.clone()
     if cfg.dtype == wl.BF16:  # the other launch form of the GEMMs: same tiles, same arithmetic, same bits
-        for fwd in (lay.forward_two_launch, lay.forward_one_launch):
+        for fwd in (lay.forward_two_launch, lay.forward_one_launch, lay.forward_resident):
             lay.y.fill_(float("nan"))
             lay.forward_ws.fill_(0xFF)
             fwd(x)
@@ -292,7 +292,7 @@ def test_one_and_two_launch_forward_match_oracle_and_each_other(oracle, name):
     w, lay, x, lg, idx, tw, y, ref = run_forward(cfg, oracle)
     y_auto = lay.y.clone()
     for rep in range(2):  # the second round starts from the counters and tickets the first one left
-        for fwd in (lay.forward_two_launch, lay.forward_one_launch):
+        for fwd in (lay.forward_two_launch, lay.forward_one_launch, lay.forward_resident):
             lay.y.fill_(float("nan"))
             fwd(x)
             torch.cuda.synchronize()
@@ -309,6 +309,61 @@ def test_one_and_two_launch_forward_match_oracle_and_each_other(oracle, name):
         lay.forward_one_launch(x)
         torch.cuda.synchronize()
         assert torch.equal(lay.y, y_auto), f"hand-over call {rep} differs"
+    # the same for the second hand-over (GEMM-2 => Combine) of the launch that also reduces the tokens: a token summed
+    # before its rows are visible would pick up the trash
+    for rep in range(40):
+        lay.y.fill_(float("nan"))
+        lay.forward_ws.fill_(0xFF if rep % 2 else 0x3C)
+        lay.forward_resident(x)
+        torch.cuda.synchronize()
+        assert torch.equal(lay.y, y_auto), f"resident call {rep} differs"
+
+
+@pytest.mark.parametrize("kw", [dict(T=1, E=8, k=2, R=2, local_rank_begin=0, local_rank_end=1, d=64, f=64),
+                                dict(T=7, E=8, k=8, R=1, local_rank_begin=0, local_rank_end=1, d=520, f=72),  # all tokens, all experts
+                                dict(T=300, E=16, k=4, R=4, d=136, f=200, router="zipf"),
+                                dict(T=513, E=64, k=6, R=8, d=1032, f=264, local_rank_begin=2, local_rank_end=5),
+                                dict(T=64, E=8, k=1, R=2, local_rank_begin=0, local_rank_end=2, d=256, f=128),  # sole rows only
+                                dict(T=2000, E=4, k=2, R=1, local_rank_begin=0, local_rank_end=1, d=264, f=128)])  # full M tiles
+def test_resident_forward_with_combine_edge_shapes(oracle, kw):
+    """GEMM-1, GEMM-2 and Combine in one launch against the oracle and, bit for bit, against the form with kernel
+    boundaries, on shapes with ragged tails, empty experts, tokens without a local slot and more tokens than waves."""
+    import torch
+    cfg = cfg_of(**kw)
+    say(f"resident forward edge {kw}")
+    w, lay, x, lg, idx, tw, y, ref = run_forward(cfg, oracle)
+    y_auto = lay.y.clone()
+    for rep in range(3):
+        lay.y.fill_(float("nan"))
+        lay.forward_ws.fill_(0xA5)
+        lay.forward_resident(x)
+        torch.cuda.synchronize()
+        G.check_y(lay.y_host(), ref, cfg.dtype)
+        assert torch.equal(lay.y, y_auto) and ws_error_flag(lay) == 0
+
+
+def test_resident_forward_combine_wait_gives_up_cleanly(oracle):
+    """As the give-up test of the GEMM-2 wait, for the launch that also runs Combine: every wait (GEMM-2 items for h,
+    tokens for their rows) expects one more finished tile than exists and gives up after a handful of polls."""
+    import torch
+    cfg = SMALL["deepseek_like"]
+    say("resident kernel with Combine: forced give-up")
+    w, lay, x, lg, idx, tw, y, ref = run_forward(cfg, oracle)
+    y_good = lay.y.clone()
+    lay.y.fill_(123.0)
+    B.moe_fused_forward_resident(lay.shape, x, lay.topk_idx, lay.topk_w, lay.tables, lay.packed_gate_up,
+                                 lay.packed_down, lay.y, lay.forward_ws, max_polls=4, wait_extra=1)
+    torch.cuda.synchronize()
+    assert B.moe_forward_status(lay.forward_ws) == 1
+    local = ((idx // cfg.epr >= cfg.local_rank_begin) & (idx // cfg.epr < cfg.local_rank_end)).any(axis=1)
+    yb = lay.y[: cfg.T].float().cpu().numpy()
+    assert np.isnan(yb[local]).all(), "a row computed after a wait gave up is not marked"
+    assert np.all(yb[~local] == 0)
+    lay.y.fill_(float("nan"))
+    lay.forward_resident(x)
+    torch.cuda.synchronize()
+    assert B.moe_forward_status(lay.forward_ws) == 0
+    assert torch.equal(lay.y, y_good)
 
 
 def test_resident_kernel_wait_gives_up_cleanly(oracle):
