@@ -192,6 +192,11 @@ def main():
     ap.add_argument("--no-8x-point", action="store_true", help="skip the extra run of the layer at 8 x the tokens")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed extras (phase-split entry points, "
                     "unfused path, reference figures)")
+    ap.add_argument("--operand-probe", default="", choices=["", "normal", "one_row"],
+                    help="only run the forward call 10 times in the two-launch form (to be run under rocprofv3 --pmc): "
+                    "'normal' on the real tables, 'one_row' with every layout row mapped to token 0, so that GEMM-1's "
+                    "A operand comes out of the caches and the difference of the two FETCH_SIZE readings is the HBM "
+                    "traffic of the gathered token rows")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a 1 GiB device-to-device copy (reference point for the HBM byte counters)")
     args = ap.parse_args()
@@ -240,6 +245,15 @@ def main():
     for _ in range(args.warmup):
         lay.step(lg, x)
     torch.cuda.synchronize()
+
+    if args.operand_probe:
+        if args.operand_probe == "one_row":
+            lay.tables.perm.zero_()  # every layout row now holds pair 0, i.e. token 0 (results are meaningless)
+        for _ in range(10):
+            lay.forward_two_launch(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"operand_probe": args.operand_probe, "config": cfg.name, "forward_calls": 10}))
+        return
 
     K = args.steps
     # Dominant kernel: where the library runs GEMM-1 and GEMM-2 as one launch (resident workgroups, tile-level

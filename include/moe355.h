@@ -11,8 +11,12 @@
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller; nothing is allocated, freed, copied to
- *     the host or synchronised by the library.  `stream` is a hipStream_t passed as void* (NULL = the
- *     default stream).  Work is enqueued on that stream only.
+ *     the host or synchronised by the library (one exception, stated where it is declared:
+ *     moe_forward_status).  `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on that stream only.
+ *   - State the library keeps between calls: per-device caches of two launch properties (the number of
+ *     compute units, and that a kernel's dynamic-LDS limit has been raised) and the static device scratch
+ *     of moe_build_dispatch_noalloc.  Nothing else: every result depends on the arguments only.
  *   - Arrays are dense and row-major.  Inputs are never modified.  Outputs are fully overwritten.
  *   - Return value: MOE_OK (0) or a negative moe_status.  Argument validation happens before the first
  *     HIP call, so the error paths can be exercised on a host without a GPU.  No exception or abort

@@ -3,6 +3,7 @@
 #pragma once
 #include <type_traits>
 
+#include "combine_kernels.h"
 #include "forward_types.h"
 
 namespace moe355 {
@@ -708,18 +709,9 @@ __device__ __forceinline__ void resident_combine(const PipelineArgs &p) {
   const float *rows = static_cast<const float *>(p.g2.out);
   bf16_t *y = static_cast<bf16_t *>(p.g2.y);
   for (int t = blockIdx.x * (kGemmThreads / 64) + (tid >> 6); t < p.T; t += n_waves) {  // t is wave-uniform
-    int row = -1, tile = 0;
-    if (lane < p.k) {
-      const int e = p.topk_idx[(size_t)t * p.k + lane];
-      if (e >= p.e_lo && e < p.e_lo + p.E_loc) {
-        const int r = p.inv_perm[(size_t)t * p.k + lane] - base;
-        if (r >= 0 && r < P) {
-          row = r;
-          tile = min(max(p.row_tile[r], 0), p.n_mtiles_cap - 1);
-        }
-      }
-    }
-    uint64_t slots = __ballot(row >= 0);
+    const int row = combine_slot_row(p.topk_idx, p.inv_perm, t, p.k, lane, p.e_lo, p.E_loc, base, P);
+    const int tile = row >= 0 ? min(max(p.row_tile[row], 0), p.n_mtiles_cap - 1) : 0;
+    const uint64_t slots = __ballot(row >= 0);
     const int n = __popcll(slots);
     if (n == 1) continue;  // GEMM-2 has written this token's row
     bf16_t *yrow = y + (size_t)t * d;
@@ -738,58 +730,7 @@ __device__ __forceinline__ void resident_combine(const PipelineArgs &p) {
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    // 4 pieces of 512 columns at a time (8 per lane each); two slots' loads are in flight together
-    for (int c0 = lane * 8; c0 < d; c0 += 4 * 512) {
-      float acc[4][8];
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-#pragma unroll
-        for (int q = 0; q < 8; ++q) acc[u][q] = 0.f;
-      uint64_t s = slots;
-      while (s) {
-        const int j0 = __builtin_ctzll(s);
-        s &= s - 1;
-        const float *src0 = rows + (size_t)__builtin_amdgcn_readlane(row, j0) * d;
-        const bool two = s != 0;
-        const int j1 = two ? __builtin_ctzll(s) : j0;
-        s &= s - 1;  // (0 stays 0)
-        const float *src1 = rows + (size_t)__builtin_amdgcn_readlane(row, j1) * d;
-        f32x4 a[4][2], b[4][2];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int c = c0 + u * 512;
-          if (c < d) {
-            a[u][0] = *reinterpret_cast<const f32x4 *>(src0 + c);
-            a[u][1] = *reinterpret_cast<const f32x4 *>(src0 + c + 4);
-            if (two) {
-              b[u][0] = *reinterpret_cast<const f32x4 *>(src1 + c);
-              b[u][1] = *reinterpret_cast<const f32x4 *>(src1 + c + 4);
-            }
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          if (c0 + u * 512 < d) {
-#pragma unroll
-            for (int q = 0; q < 8; ++q) acc[u][q] += a[u][q >> 2][q & 3];
-            if (two) {
-#pragma unroll
-              for (int q = 0; q < 8; ++q) acc[u][q] += b[u][q >> 2][q & 3];
-            }
-          }
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int c = c0 + u * 512;
-        if (c < d) {
-          bf16x8 o;
-#pragma unroll
-          for (int q = 0; q < 8; ++q) o[q] = poison ? (bf16_t)__builtin_nanf("") : (bf16_t)acc[u][q];
-          *reinterpret_cast<bf16x8 *>(yrow + c) = o;
-        }
-      }
-    }
+    combine_token_rows<bf16_t>(rows, row, slots, d, yrow, lane, poison);
   }
 }
 
