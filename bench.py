@@ -190,6 +190,8 @@ def main():
                     "distribution across experts with this standard deviation (0.032 typical, 0.01-0.05 swept); "
                     "selects the loadstd router")
     ap.add_argument("--no-8x-point", action="store_true", help="skip the extra run of the layer at 8 x the tokens")
+    ap.add_argument("--no-skew-points", action="store_true", help="skip the two extra ranks of the skewed routing "
+                    "(counter runs: their launches would enter the per-kernel averages)")
     ap.add_argument("--no-extras", action="store_true", help="skip the untimed extras (phase-split entry points, "
                     "unfused path, reference figures)")
     ap.add_argument("--operand-probe", default="", choices=["", "normal", "one_row"],
@@ -515,7 +517,7 @@ def main():
     # Two more ranks of the same skewed routing (DeepSeek-shaped workload only): the rank that receives the most pairs
     # under this seed, and the "hot rank" corner (popular experts first: nearly every pair on rank 0).  Same shapes
     # and the same packed weight buffers (their values do not matter for the time); labelled extras, not `value`.
-    if cfg.name == "deepseek_v3" and not swept:
+    if cfg.name == "deepseek_v3" and not swept and not args.no_skew_points:
         rank_pairs = counts.reshape(cfg.R, cfg.epr).sum(axis=1)
         pts = {}
         for label, cfg_x in (("max_load_rank", cfg.scaled(local_rank_begin=int(rank_pairs.argmax()),

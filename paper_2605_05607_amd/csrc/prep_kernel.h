@@ -13,9 +13,11 @@ namespace moe355 {
 // kernel that also runs Combine.
 //
 // A work item is one output tile (expert, M tile, N tile): int4 (local expert, first local row, valid rows,
-// N tile | M-tile id << 12).  Full M tiles come first and the partial tile of each
-// expert (its last rows) afterwards, largest first, so that the launch ends with its shortest items; partial
-// tiles of at most 64 rows (pure weight streaming) are mixed into the full tiles (see the list order below).
+// N tile | M-tile id << 12).  An expert's partial tile (its last rows) walks with the expert's full tiles when it has
+// more than 64 rows: it needs the same weight panels, and running it in the same chunks fetches them once instead of
+// twice (measured on layers whose experts hold one or two full tiles and a partial one: the L2 fills of GEMM-1 were
+// twice the weights).  Partial tiles of at most 64 rows (pure weight streaming) are mixed into those chunks or
+// trail them (see the list order below).
 // The order of the list is also what keeps the L2 useful:
 // the chip has 8 XCDs with a private 4 MiB L2 each and workgroup i runs on XCD i % 8, so every GEMM workgroup
 // maps its index to a list position such that XCD x works through the 32-item chunks x, x + 8, x + 16, ...;
@@ -74,12 +76,11 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
   const int ipt = (E_loc + blockDim.x - 1) / blockDim.x;
   const int lo = min(E_loc, (int)threadIdx.x * ipt);
   const int hi = min(E_loc, lo + ipt);
-  int local_full = 0, local_big = 0, local_small = 0;
+  int local_full = 0, local_small = 0;
   for (int le = lo; le < hi; ++le) {
     const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
     part[le] = cnt % bm;
-    local_full += cnt / bm;
-    local_big += (cnt % bm) > kStreamRows;
+    local_full += cnt / bm + ((cnt % bm) > kStreamRows);  // a large partial tile walks with the expert's full tiles
     local_small += (cnt % bm) != 0 && (cnt % bm) <= kStreamRows;
   }
   int n_full, n_big, n_small;
@@ -87,25 +88,24 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
   for (int le = lo; le < hi; ++le) {
     const int cnt = max(0, min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base));
     full0[le] = run;
-    run += cnt / bm;
+    run += cnt / bm + ((cnt % bm) > kStreamRows);
   }
   if (threadIdx.x == 0) full0[E_loc] = n_full;
-  (void)block_exclusive_scan(local_big, scratch, &n_big);
+  n_big = 0;  // (no separate class any more: see the list order below)
   (void)block_exclusive_scan(local_small, scratch, &n_small);
   __syncthreads();
-  // rank sort inside the two classes of partial tiles (for very many experts keep the expert order)
+  // rank sort of the streaming partial tiles (for very many experts keep the expert order)
   for (int le = lo; le < hi; ++le) {
     const int mine = part[le];
-    if (mine == 0) continue;
-    const bool small = mine <= kStreamRows;
+    if (mine == 0 || mine > kStreamRows) continue;
     int rank = 0;
     for (int o = 0; o < E_loc; ++o) {
       const int po = part[o];
-      if (po == 0 || (po <= kStreamRows) != small) continue;
+      if (po == 0 || po > kStreamRows) continue;
       rank += E_loc <= 1024 ? (po > mine || (po == mine && o < le)) : (o < le);
     }
-    order[(small ? n_big : 0) + rank] = le;
-    if (row_tile) pos[le] = (small ? n_big : 0) + rank;
+    order[rank] = le;
+    if (row_tile) pos[le] = rank;
   }
   __syncthreads();
   n_full = min(n_full, max_mtiles);
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       const int start = min(P, offsets[e_lo + a] - base);
       const int cnt = min(P, offsets[e_lo + a + 1] - base) - start;
       const int mt = (r - start) / bm;
-      const int tile = mt < cnt / bm ? full0[a] + mt : n_full + pos[a];
+      const int tile = (mt < cnt / bm || part[a] > kStreamRows) ? full0[a] + mt : n_full + pos[a];
       row_tile[r] = min(tile, max(n_tiles - 1, 0));
     }
   }
@@ -145,7 +145,8 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
     const bool second = q >= n1;
     const int Nt = second ? nt2 : nt1;
     const int qq = second ? q - n1 : q;
-    // List order.  Classes: F = full tiles, B = big partial tiles, S = streaming partial tiles.
+    // List order.  Classes: F = full tiles and partial tiles of more than kStreamRows rows, S = streaming partial
+    // tiles (class B, partial tiles as a list of their own, is empty: n_big = 0).
     //   [ mixed chunks: each 32-item chunk holds 8 items of S, then 24 items of F, so that some CUs of every XCD
     //     stream weights from HBM while the others multiply; only when S is at least half as large as F,
     //     otherwise the few S items would just push full tiles into an extra round ]
@@ -188,8 +189,17 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       const int ng = r / (Mcur * G);
       r -= ng * Mcur * G;
       const int Gcur = min(G, Nt - ng * G);
-      mt = mg * Mg + r / Gcur;
-      nt = ng * G + r % Gcur;
+      // Inside the group the shorter side runs fastest.  The workgroups of an XCD start a few microseconds apart
+      // (one whenever a CU becomes free), and the L2 keeps only the last few k-steps of what they stream; two items
+      // share a panel through it only if they sit within a few list positions of each other, and with the shorter
+      // side innermost both the A sharers and the B sharers do.
+      if (Gcur <= Mcur) {
+        mt = mg * Mg + r / Gcur;
+        nt = ng * G + r % Gcur;
+      } else {
+        mt = mg * Mg + r % Mcur;
+        nt = ng * G + r / Mcur;
+      }
       rows = bm;
       tile = full0[le] + mt;
     } else {
@@ -199,6 +209,11 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       const int cnt = min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base);
       mt = cnt / bm;
       rows = part[le];
+    }
+    if (cls == 0) {
+      // the expert's last tile of this class may be its large partial tile
+      const int cnt = min(P, offsets[e_lo + le + 1] - base) - min(P, offsets[e_lo + le] - base);
+      if (mt >= cnt / bm) rows = part[le];
     }
     const int start = min(P, offsets[e_lo + le] - base);
     const int4 item = make_int4(le, start + mt * bm, rows, nt | (tile << kTileShift));
