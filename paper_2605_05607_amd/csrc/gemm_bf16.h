@@ -193,13 +193,35 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // 0x200 DS write).
 #define MOE355_ORDER(NW)                                                                                \
   do {                                                                                                 \
-    if (NB > 0) {                                                                                      \
-      __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);                                          \
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                          \
-    }                                                                                                  \
-    if ((NW) > 0) {                                                                                    \
-      __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                            \
-      __builtin_amdgcn_sched_group_barrier(0x020, (NW), 0);                                            \
+    if (NB >= 3) {                                                                                     \
+      /* the LDS reads two behind each of the first MFMAs, then one staging store and one global load  \
+         behind each of the next ones, the rest of the MFMAs last: the LDS queue never sees more than  \
+         two requests in a row (measured 3-4 % faster than all reads, all MFMAs, all stores, all       \
+         loads; the stores as early as the reads: 7 % slower, they wait for the global loads) */       \
+      _Pragma("unroll") for (int i_ = 0; i_ < (NB + 2) / 2; ++i_) {                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                             \
+        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                             \
+      }                                                                                                \
+      if ((NB + 2) & 1) {                                                                              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                             \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                             \
+      }                                                                                                \
+      _Pragma("unroll") for (int i_ = 0; i_ < (NW); ++i_) {                                            \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                             \
+        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                             \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                             \
+      }                                                                                                \
+      if (2 * NB - (NB + 3) / 2 - (NW) > 0)                                                            \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB - (NB + 3) / 2 - (NW), 0);                  \
+    } else {                                                                                           \
+      if (NB > 0) {                                                                                    \
+        __builtin_amdgcn_sched_group_barrier(0x100, NB + 2, 0);                                        \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * NB, 0);                                        \
+      }                                                                                                \
+      if ((NW) > 0) {                                                                                  \
+        __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                          \
+        __builtin_amdgcn_sched_group_barrier(0x020, (NW), 0);                                          \
+      }                                                                                                \
     }                                                                                                  \
   } while (0)
 #define MOE355_KSTEP(S, KT_, KPRE)                                                                      \

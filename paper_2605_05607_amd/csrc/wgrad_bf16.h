@@ -164,14 +164,20 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
     rb[(J0)] = *reinterpret_cast<const u32x4 *>(bp[(J0)] + (size_t)(KP) * b_step);                 \
     if ((J1) >= 0) rb[(J1) < 0 ? 0 : (J1)] = *reinterpret_cast<const u32x4 *>(bp[(J1) < 0 ? 0 : (J1)] + (size_t)(KP) * b_step); \
   } while (0)
+  /* order as in the forward tile: reads two behind each of the first three MFMAs, a store and a load behind each of
+     the next NW, the remaining MFMAs last */
 #define MOE355_W_ORDER(NW)                                                                         \
   do {                                                                                             \
-    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);                                             \
-    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                             \
-    if ((NW) > 0) {                                                                                \
-      __builtin_amdgcn_sched_group_barrier(0x200, (NW), 0);                                        \
-      __builtin_amdgcn_sched_group_barrier(0x020, (NW), 0);                                        \
+    _Pragma("unroll") for (int i_ = 0; i_ < 3; ++i_) {                                             \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                           \
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);                                           \
     }                                                                                              \
+    _Pragma("unroll") for (int i_ = 0; i_ < (NW); ++i_) {                                          \
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                           \
+      __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                           \
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                           \
+    }                                                                                              \
+    __builtin_amdgcn_sched_group_barrier(0x008, 5 - (NW), 0);                                      \
   } while (0)
   {
     const int kt_last = KT - 1;  // KT > kThinSteps >= 1
