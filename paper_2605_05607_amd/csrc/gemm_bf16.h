@@ -67,7 +67,8 @@ constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue p
 //            g.aux2 = w silu(g) u [rows, N] bf16 (the h operand of the down-projection weight gradient, weight folded in).
 template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
-                                               int rows, int nblk_total, int poison = 0) {
+                                               int rows, int nblk_total, int poison = 0,
+                                               int32_t *pre_ctr = nullptr, int *pre_slot = nullptr) {
   // RESIDENT (the kernel that loops over items): the thread index goes through an empty asm so that nothing
   // derived from it counts as loop invariant; hoisting those values across items costs more registers than the
   // tile has to spare.
@@ -332,6 +333,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // owns one column.  Each wave turns its blocks around through a private LDS patch (the stages are dead now)
   // so that the global stores are 16 bytes per lane along a row instead of one element per lane.
   __syncthreads();  // every wave has finished reading the stages
+  // RESIDENT: the ticket of this workgroup's next item is drawn now, by thread 0, so that the atomic's round trip
+  // runs under the epilogue instead of in front of the next item; the value is parked in the LDS at the very end.
+  int pre_v = -1;
+  if (RESIDENT && pre_ctr && threadIdx.x == 0) pre_v = atomicAdd(pre_ctr, 1);
   unsigned char *patch = smem + w8 * kPatchBytes;
 #pragma unroll
   for (int mi = 0; mi < NB; ++mi) {
@@ -521,6 +526,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the patch is reused by the next block
   }
+  if (RESIDENT && pre_ctr && threadIdx.x == 0) *pre_slot = pre_v;
 }
 
 // One work item on the matrix cores.  Wave-uniform dispatch on the number of valid 32-row blocks: every variant
@@ -528,13 +534,15 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
 // the rows are written as NaN.
 template <bool GATED, bool RESIDENT, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item,
-                                               int poison = 0) {
+                                               int poison = 0, int32_t *pre_ctr = nullptr,
+                                               int *pre_slot = nullptr) {
   const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
 #define MOE355_TILE(NB_, NA_) \
-  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN>(g, smem, nt, le, m0, rows, nblk_total, poison)
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN>(g, smem, nt, le, m0, rows, nblk_total, poison, \
+                                                                          pre_ctr, pre_slot)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -606,11 +614,13 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
   const int n_virtual = (n_items + 8 * kChunk - 1) / (8 * kChunk) * (8 * kChunk);
   int qsel = 0;  // queues tried so far, in the order home, home + 1, ... (only thread 0's copy is used)
   // Next list position for this workgroup, or -1 when every queue is empty (thread 0 only).
-  auto draw = [&]() {
+  // pre >= 0: a ticket of the queue this workgroup is on, drawn ahead under the previous item's epilogue
+  auto draw = [&](int pre) {
     int q = -1;
     while (qsel < 8) {
       const int queue = (home + qsel) & 7;
-      const int v = queue + 8 * atomicAdd(&tickets[queue], 1);
+      const int v = queue + 8 * (pre >= 0 ? pre : atomicAdd(&tickets[queue], 1));
+      pre = -1;
       if (v < n_virtual) {
         if ((q = chunked_item(v, n_items)) >= 0) break;
         continue;  // a virtual block without an item
@@ -650,18 +660,24 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
     n_pending = 0;
     __syncthreads();  // the list may be overwritten
   };
-  // (Drawing the next ticket one item ahead, to hide the latency of the atomic, was measured slower: a workgroup
-  // that holds a long item while it finishes another one keeps that item from an idle workgroup.)
+  // (Drawing the next ticket a whole item ahead, to hide the latency of the atomic, was measured slower: a workgroup
+  // that holds a long item while it finishes another one keeps that item from an idle workgroup.  What is drawn
+  // ahead here is drawn under the epilogue of the item that is being finished, a few microseconds before it is used.)
+  if (threadIdx.x == 0) s_item[2] = -1;
   for (;;) {
     __syncthreads();  // the previous item is done with the LDS (and with *s_item)
-    if (threadIdx.x == 0) *s_item = draw();
+    if (threadIdx.x == 0) {
+      *s_item = draw(s_item[2]);
+      s_item[2] = -1;
+    }
     __syncthreads();
     const int q = *s_item;
     if (q < 0) break;  // nothing left in any queue
     const int4 item = g.work[q];
     const int tile = item.w >> kTileShift;
+    int32_t *pre_ctr = tickets + ((home + qsel) & 7);  // (thread 0's value is the one that is used)
     if (GATED) {
-      gemm_bf16_item<true, true, FP8, TRAIN>(g, smem, item);
+      gemm_bf16_item<true, true, FP8, TRAIN>(g, smem, item, 0, pre_ctr, s_item + 2);
       // Release side of the hand-over.  Every wave first waits until its own h stores have been acknowledged, so that
       // the one write-back below cannot overtake any of them (a workgroup barrier alone does not wait for global
       // stores).
@@ -696,7 +712,7 @@ __device__ __forceinline__ void gemm_bf16_drain(const GemmArgs &g, unsigned char
         s_item[1] = gave_up;
       }
       __syncthreads();
-      gemm_bf16_item<false, true, FP8>(g, smem, item, s_item[1]);
+      gemm_bf16_item<false, true, FP8>(g, smem, item, s_item[1], pre_ctr, s_item + 2);
       if (tile_done) {
         // remembered, counted later (flush_done): one write-back for all the items of this workgroup
         if (threadIdx.x == 0) s_done[n_pending] = tile;
@@ -758,7 +774,7 @@ __device__ __forceinline__ void resident_combine(const PipelineArgs &p) {
 
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item[2];  // [0] list position drawn by thread 0, [1] its wait gave up
+  __shared__ int s_item[3];  // [0] list position drawn by thread 0, [1] its wait gave up, [2] ticket drawn ahead
   gemm_bf16_drain<true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
   gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
 }
@@ -766,7 +782,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_pipeline_kernel(con
 // The resident kernel with Combine as its third stage: the whole layer after the tile table in one launch.
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_combine_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item[2];
+  __shared__ int s_item[3];
   gemm_bf16_drain<true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
   __shared__ int s_done[kDoneCap];
   gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls, p.tile_done,
@@ -777,7 +793,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_bf16_combine_kernel(cons
 // The same resident kernel for the training forward: GEMM-1 also keeps g and u.
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_train_pipeline_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item[2];
+  __shared__ int s_item[3];
   gemm_bf16_drain<true, false, true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
   gemm_bf16_drain<false>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
 }
@@ -785,7 +801,7 @@ __global__ __launch_bounds__(kGemmThreads, 1) void gemm_train_pipeline_kernel(co
 // The same resident kernel on E4M3 operands.
 __global__ __launch_bounds__(kGemmThreads, 1) void gemm_fp8_pipeline_kernel(const PipelineArgs p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages x 64 KiB
-  __shared__ int s_item[2];
+  __shared__ int s_item[3];
   gemm_bf16_drain<true, true>(p.g1, smem, s_item, p.tickets, p.tile_ready, p.error, p.nt1, p.max_polls);
   gemm_bf16_drain<false, true>(p.g2, smem, s_item, p.tickets + 8, p.tile_ready, p.error, p.nt1, p.max_polls);
 }
