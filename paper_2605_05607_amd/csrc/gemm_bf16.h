@@ -338,6 +338,45 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   int pre_v = -1;
   if (RESIDENT && pre_ctr && threadIdx.x == 0) pre_v = atomicAdd(pre_ctr, 1);
   unsigned char *patch = smem + w8 * kPatchBytes;
+  // GEMM-2: the gate weights and the sole-slot marks of this wave's 128 rows come in once, coalesced, and wait in the
+  // LDS behind the patches (1 KiB per wave), instead of 24 scattered loads in front of every 32-row block
+  float *meta_w = reinterpret_cast<float *>(smem + 8 * kPatchBytes + w8 * 1024);
+  int *meta_s = reinterpret_cast<int *>(meta_w + 128);
+  if (!GATED && !TRAIN && NB > 0) {
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int row_l = wm * 128 + hh * 64 + lane;
+      meta_w[hh * 64 + lane] = row_l < rows ? (g.row_w ? g.row_w[m0 + row_l] : 1.f) : 0.f;
+      meta_s[hh * 64 + lane] = (g.row_sole && row_l < rows) ? g.row_sole[m0 + row_l] : -1;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  if (!GATED && TRAIN && NB > 0) {
+    // first backward GEMM: the gate weights of this wave's rows, parked behind the wave's three blocks (which take
+    // 13824 of its 16 KiB)
+    meta_w = reinterpret_cast<float *>(smem + w8 * 16384 + 13824);
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int row_l = wm * 128 + hh * 64 + lane;
+      meta_w[hh * 64 + lane] = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+  if (GATED && FP8 && NB > 0) {
+    // FP8 GEMM-1: the same for the scales of the tokens behind this wave's rows (rows past the end repeat the last)
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const int row_l = min(wm * 128 + hh * 64 + lane, rows - 1);
+      meta_w[hh * 64 + lane] = g.a_scale[g.row_map ? g.row_map[m0 + row_l] : m0 + row_l];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
 #pragma unroll
   for (int mi = 0; mi < NB; ++mi) {
     const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
@@ -368,9 +407,10 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       // and nothing of them is stored)
       float wv[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row_l = blk_row0 + (r >> 2) * 8 + khalf * 4 + (r & 3);
-        wv[r] = row_l < rows ? g.row_w[m0 + row_l] : 0.f;
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 w4 = *reinterpret_cast<const f32x4 *>(meta_w + mi * 32 + q * 8 + khalf * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wv[q * 4 + e] = w4[e];
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
@@ -424,11 +464,13 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       const float *bs = g.b_scale + (size_t)le * 2 * g.N;
       const float sg = col_h < g.N ? bs[col_h] : 0.f, su = col_h < g.N ? bs[g.N + col_h] : 0.f;
       const float sh = g.h_scale[le];
+      f32x4 sx4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sx4[q] = *reinterpret_cast<const f32x4 *>(meta_w + mi * 32 + q * 8 + khalf * 4);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
-        const int row_l = min(blk_row0 + rl, rows - 1);
-        const float sx = g.a_scale[g.row_map ? g.row_map[m0 + row_l] : m0 + row_l];
+        const float sx = sx4[r >> 2][r & 3];
         const float gv = acc[mi][0][r] * (sx * sg), uv = acc[mi][1][r] * (sx * su);
         patch[rl * 48 + l31] = to_e4m3(((gv / (1.0f + __expf(-gv))) * uv) / sh);
       }
@@ -488,15 +530,14 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       }
       int sole[8];
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int row_l = blk_row0 + it * 4 + (lane >> 4);
-        sole[it] = (g.row_sole && row_l < rows) ? g.row_sole[m0 + row_l] : -1;
-      }
+      for (int it = 0; it < 8; ++it) sole[it] = meta_s[mi * 32 + it * 4 + (lane >> 4)];
+      f32x4 w4[4];  // gate weights of the 16 rows this lane holds accumulators for (0 past the end)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) w4[q] = *reinterpret_cast<const f32x4 *>(meta_w + mi * 32 + q * 8 + khalf * 4);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
-        const int row_l = blk_row0 + rl;
-        float wgt = row_l < rows ? (g.row_w ? g.row_w[m0 + row_l] : 1.f) : 0.f;
+        float wgt = w4[r >> 2][r & 3];
         if (poison) wgt = __builtin_nanf("");  // the wait for this item's h gave up: mark what it writes
         *reinterpret_cast<float *>(patch + rl * 288 + l31 * 4) = FP8 ? acc[mi][0][r] * cs0 * wgt : acc[mi][0][r] * wgt;
         *reinterpret_cast<float *>(patch + rl * 288 + 128 + l31 * 4) =
