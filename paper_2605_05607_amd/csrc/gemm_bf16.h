@@ -377,6 +377,23 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   }
+  // FP8: the scales of this lane's columns, read once (inside the loop over the blocks the compiler would have to
+  // read them again behind every global store).  GEMM-1: scale of the gate and of the up column of h column col_h
+  // and the expert's scale of h; GEMM-2: the expert's scale of h times the scales of the lane's two output columns.
+  float f8_s0 = 1.f, f8_s1 = 1.f, f8_sh = 1.f;
+  if (FP8 && GATED && NB > 0) {
+    const int col_h = nt * (kBN / 2) + wn * 32 + l31;
+    const float *bs = g.b_scale + (size_t)le * 2 * g.N;
+    f8_s0 = col_h < g.N ? bs[col_h] : 0.f;
+    f8_s1 = col_h < g.N ? bs[g.N + col_h] : 0.f;
+    f8_sh = g.h_scale[le];
+  }
+  if (FP8 && !GATED && NB > 0) {
+    const int c0 = nt * kBN + wn * 64 + l31;
+    const float sh = g.h_scale[le];
+    f8_s0 = c0 < g.N ? sh * g.b_scale[(size_t)le * g.N + c0] : 0.f;
+    f8_s1 = c0 + 32 < g.N ? sh * g.b_scale[(size_t)le * g.N + c0 + 32] : 0.f;
+  }
 #pragma unroll
   for (int mi = 0; mi < NB; ++mi) {
     const int blk_row0 = wm * 128 + mi * 32;  // first tile row of this 32-row block
@@ -460,10 +477,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     } else if (GATED && FP8) {
       // h block: 32 rows x 32 columns of E4M3 codes, row pitch 48 bytes.  g and u get the scales of their token
       // and of their columns; h = silu(g) * u is divided by the expert's scale for h and converted.
-      const int col_h = nt * (kBN / 2) + wn * 32 + l31;
-      const float *bs = g.b_scale + (size_t)le * 2 * g.N;
-      const float sg = col_h < g.N ? bs[col_h] : 0.f, su = col_h < g.N ? bs[g.N + col_h] : 0.f;
-      const float sh = g.h_scale[le];
+      const float sg = f8_s0, su = f8_s1, sh = f8_sh;
       f32x4 sx4[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) sx4[q] = *reinterpret_cast<const f32x4 *>(meta_w + mi * 32 + q * 8 + khalf * 4);
@@ -521,13 +535,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       // o block: 32 rows x 64 columns fp32, row pitch 288 bytes.  A row whose token has no other local slot
       // is final already (the Combine sum would have one term): it goes to y in the output type, skipping o.
       // FP8: the scale of the expert's h times the scale of the lane's two output columns
-      float cs0 = 1.f, cs1 = 1.f;
-      if (FP8) {
-        const int c0 = nt * kBN + wn * 64 + l31;
-        const float sh = g.h_scale[le];
-        cs0 = c0 < g.N ? sh * g.b_scale[(size_t)le * g.N + c0] : 0.f;
-        cs1 = c0 + 32 < g.N ? sh * g.b_scale[(size_t)le * g.N + c0 + 32] : 0.f;
-      }
+      const float cs0 = f8_s0, cs1 = f8_s1;
       int sole[8];
 #pragma unroll
       for (int it = 0; it < 8; ++it) sole[it] = meta_s[mi * 32 + it * 4 + (lane >> 4)];
