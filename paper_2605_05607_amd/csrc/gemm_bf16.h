@@ -444,7 +444,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         bf16_t o_dg[16], o_du[16], o_hw[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float sg = 1.0f / (1.0f + __expf(-gv[r])), silu = gv[r] * sg;
+          const float sg = __builtin_amdgcn_rcpf(1.0f + __expf(-gv[r])), silu = gv[r] * sg;
           const float dh = wv[r] * acc[mi][j][r];
           o_dg[r] = (bf16_t)(dh * uv[r] * (sg * (1.0f + gv[r] * (1.0f - sg))));
           o_du[r] = (bf16_t)(dh * silu);
@@ -477,7 +477,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
     } else if (GATED && FP8) {
       // h block: 32 rows x 32 columns of E4M3 codes, row pitch 48 bytes.  g and u get the scales of their token
       // and of their columns; h = silu(g) * u is divided by the expert's scale for h and converted.
-      const float sg = f8_s0, su = f8_s1, sh = f8_sh;
+      const float sg = f8_s0, su = f8_s1, rsh = __builtin_amdgcn_rcpf(f8_sh);
       f32x4 sx4[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) sx4[q] = *reinterpret_cast<const f32x4 *>(meta_w + mi * 32 + q * 8 + khalf * 4);
@@ -486,7 +486,7 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const float sx = sx4[r >> 2][r & 3];
         const float gv = acc[mi][0][r] * (sx * sg), uv = acc[mi][1][r] * (sx * su);
-        patch[rl * 48 + l31] = to_e4m3(((gv / (1.0f + __expf(-gv))) * uv) / sh);
+        patch[rl * 48 + l31] = to_e4m3((gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv))) * uv * rsh);
       }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
@@ -506,7 +506,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
       for (int r = 0; r < 16; ++r) {
         const int rl = (r >> 2) * 8 + khalf * 4 + (r & 3);
         const float gv = acc[mi][0][r], uv = acc[mi][1][r];
-        *reinterpret_cast<bf16_t *>(patch + rl * 80 + l31 * 2) = (bf16_t)((gv / (1.0f + __expf(-gv))) * uv);
+        // (the hardware reciprocal, 1 ulp, instead of the correctly rounded division: h is rounded to bf16 next)
+        *reinterpret_cast<bf16_t *>(patch + rl * 80 + l31 * 2) =
+            (bf16_t)((gv * __builtin_amdgcn_rcpf(1.0f + __expf(-gv))) * uv);
         if (TRAIN) {
           *reinterpret_cast<bf16_t *>(patch + 2560 + rl * 80 + l31 * 2) = (bf16_t)gv;
           *reinterpret_cast<bf16_t *>(patch + 5120 + rl * 80 + l31 * 2) = (bf16_t)uv;
