@@ -748,7 +748,8 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
     a.M = M; a.N = N; a.n_mt = ceil_div(M, kBM); a.n_nt = ceil_div(N, kBN);
     hipLaunchKernelGGL(wgrad_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(kGemmThreads), 2 * kStageBytes, st, a);
     a.n_mt = ceil_div(M, 128); a.n_nt = ceil_div(N, 128);  // experts with few or no rows: small tiles
-    hipLaunchKernelGGL(wgrad_thin_bf16_kernel, dim3(a.n_mt * a.n_nt, dv.E_loc), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(wgrad_thin_bf16_kernel, dim3(ceil_div(a.n_mt * a.n_nt, kThinTiles), dv.E_loc), dim3(256), 0, st,
+                       a);
   };
   product(xT, shape->d, dguT, 2 * shape->f, 0, shape->d, shape->f, dW_gate);         // x^T dg
   product(xT, shape->d, dguT, 2 * shape->f, shape->f, shape->d, shape->f, dW_up);    // x^T du
