@@ -13,10 +13,13 @@
  *   - All data pointers are DEVICE pointers owned by the caller; nothing is allocated, freed, copied to
  *     the host or synchronised by the library (one exception, stated where it is declared:
  *     moe_forward_status).  `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Work is enqueued on that stream only.
+ *     Work is enqueued on that stream only (one exception, stated where it is declared: moe_fused_backward
+ *     with weight gradients), and is complete in that stream's order when the stream reaches the end of it.
  *   - State the library keeps between calls: per-device caches of two launch properties (the number of
- *     compute units, and that a kernel's dynamic-LDS limit has been raised) and the static device scratch
- *     of moe_build_dispatch_noalloc.  Nothing else: every result depends on the arguments only.
+ *     compute units, and that a kernel's dynamic-LDS limit has been raised), the static device scratch
+ *     of moe_build_dispatch_noalloc, and moe_fused_backward's per-device side stream with its three events.
+ *     Nothing else: every result depends on the arguments only.  These are set up by the first call that
+ *     needs them on a device, which therefore must not run under stream capture.
  *   - Arrays are dense and row-major.  Inputs are never modified.  Outputs are fully overwritten.
  *   - Return value: MOE_OK (0) or a negative moe_status.  Argument validation happens before the first
  *     HIP call, so the error paths can be exercised on a host without a GPU.  No exception or abort
@@ -338,10 +341,15 @@ MOE355_API int moe_fp8_fused_forward(const moe_shape *shape, const void *x, cons
  *   packed_down_t (W_down^T) and packed_gate_up_t ([W_gate^T ; W_up^T]), moe_backward_packed_weight_bytes(shape, 0 / 1)
  *   bytes, 16-byte aligned.  Inputs as for moe_pack_weights.
  * moe_fused_backward: x, dy [T,d] bf16; the routing and tables of the forward; dx [T,d] bf16 and d_topk_w [T,k] fp32
- *   are written in full.  dW_gate, dW_up [E_loc,d,f] and dW_down [E_loc,f,d] (bf16, written in full, zero for an
- *   expert without rows) are computed when all three pointers are non-NULL and skipped when all three are NULL.
+ *   are written in full.  dW_gate, dW_up [E_loc,d,f] and dW_down [E_loc,f,d] (bf16, 16-byte aligned, written in full, zero for
+ *   an expert without rows) are computed when all three pointers are non-NULL and skipped when all three are NULL.
  *   workspace >= moe_backward_workspace_bytes(shape), 256-byte aligned.  Sums run in a fixed order: same inputs,
- *   same bits.
+ *   same bits.  With weight gradients, the transposed copies of the operands are made on a stream of the library's
+ *   own (one per device, default priority, created by the first such call and kept) beside the two GEMMs: it waits
+ *   for an event recorded on `stream` and `stream` waits for its last kernel before the products start, so the call's
+ *   work is ordered in `stream` like any other call's, also inside a stream capture (later calls only: see above).
+ *   Calls from several host threads on one device share that side stream: the library serialises their enqueueing
+ *   (a mutex held for the duration of the call) and their side work runs in turn; they still need separate workspaces.
  */
 MOE355_API size_t moe_train_kept_bytes(const moe_shape *shape);
 MOE355_API size_t moe_backward_workspace_bytes(const moe_shape *shape);

@@ -3,6 +3,8 @@
 // materialised copy), the gate weight applied in GEMM-2's epilogue (Sec. III-C), and the per-token reduction
 // with a single write-back (Combine; the one-GPU form of the in-switch reduction of Sec. II-C).
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 
 #include "backward_kernels.h"
 #include "combine_kernels.h"
@@ -640,6 +642,39 @@ extern "C" int moe_fused_forward_train(const moe_shape *shape, const void *x, co
                         workspace_bytes, stream, true, nullptr, 0, nullptr, kept);
 }
 
+// The backward pass runs its memory-bound preparation for the weight gradients (zero gradients of experts without
+// rows, transposed operands) beside its compute-bound GEMMs: those kernels need at most 16 registers and little or no
+// LDS, so their waves fit on a CU next to a GEMM workgroup.  They go to a stream of the library's own (one per device,
+// default priority, created on first use and kept), forked from and joined to the caller's stream by events.
+struct SideStream {
+  hipStream_t stream;
+  hipEvent_t fork, mid, join;
+  std::mutex enqueue;  // held by a call from its fork to its join: the events are re-recorded by every call
+};
+static SideStream *side_stream() {
+  static SideStream made[64];  // (the mutex makes the struct non-trivial: default-constructed once)
+  static std::atomic<int> state[64];  // 0 none, 1 being made, 2 ready
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  if (state[dev].load(std::memory_order_acquire) == 2) return &made[dev];
+  int expect = 0;
+  if (state[dev].compare_exchange_strong(expect, 1)) {
+    SideStream &m = made[dev];
+    if (hipStreamCreateWithFlags(&m.stream, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&m.fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m.mid, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&m.join, hipEventDisableTiming) != hipSuccess) {
+      state[dev].store(0);
+      return nullptr;
+    }
+    state[dev].store(2, std::memory_order_release);
+    return &m;
+  }
+  while (state[dev].load(std::memory_order_acquire) == 1) {
+  }
+  return state[dev].load(std::memory_order_acquire) == 2 ? &made[dev] : nullptr;
+}
+
 extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const void *dy, const int32_t *topk_idx,
                                   const float *topk_w, const moe_dispatch *tables, const void *packed_down_t,
                                   const void *packed_gate_up_t, const void *kept, size_t kept_bytes, void *dx,
@@ -666,7 +701,7 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   if (std::max(dvb.nt1, dvb.nt2) >= 1 << kTileShift || dvb.max_mtiles >= 1 << (31 - kTileShift)) return MOE_ERR_UNSUPPORTED;
   if (std::max<int64_t>(shape->T, dv.P_cap) * std::max(shape->d, 2 * shape->f) >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
   if (wgrad && (reinterpret_cast<uintptr_t>(dW_gate) | reinterpret_cast<uintptr_t>(dW_up) |
-                reinterpret_cast<uintptr_t>(dW_down)) % 8 != 0)
+                reinterpret_cast<uintptr_t>(dW_down)) % 16 != 0)
     return MOE_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   begin_launches();
@@ -689,18 +724,50 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   const float *kept_o = reinterpret_cast<const float *>(static_cast<const unsigned char *>(kept) +
                                                         align_up(rows * 2 * shape->f * 2, 256));
   if ((rc = launch_prep(shape, dvb, tables, topk_idx, topk_w, w, w.row_sole, st)) != MOE_OK) return rc;
+  // side stream: what the weight gradients need besides the products (nothing of it reads a GEMM's output before `mid`)
+  SideStream *side = nullptr;
+  std::unique_lock<std::mutex> side_lock;  // (released when the call returns)
+  int32_t *kb = reinterpret_cast<int32_t *>(b + L.kb);
+  bf16_t *xT = reinterpret_cast<bf16_t *>(b + L.xT), *dyT = reinterpret_cast<bf16_t *>(b + L.dyT);
+  bf16_t *hwT = reinterpret_cast<bf16_t *>(b + L.hwT), *dguT = reinterpret_cast<bf16_t *>(b + L.dguT);
+  const int kblocks = (int)(L.kpad / 64);
+  const auto transpose = [&](const bf16_t *src, const int32_t *map, int ld, int C, bf16_t *dst) {
+    hipLaunchKernelGGL(gather_transpose_kernel, dim3(ceil_div(C, 64), kblocks), dim3(256), 0, side->stream, src, map,
+                       ld, 0, C, tables->offsets, w.header, kb, dv.e_lo, dv.E_loc, dst);
+  };
+  // from the fork on, every return first makes the caller's stream wait for the side stream
+  const auto join = [&](int code) {
+    if (!side) return code;
+    if (hipEventRecord(side->join, side->stream) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess)
+      return code != MOE_OK ? code : (int)MOE_ERR_HIP;
+    return code;
+  };
+  if (wgrad) {
+    if (kblocks > 65535) return MOE_ERR_UNSUPPORTED;
+    if (!(side = side_stream())) return MOE_ERR_HIP;
+    side_lock = std::unique_lock<std::mutex>(side->enqueue);
+    if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->fork, 0) != hipSuccess) {
+      side = nullptr;
+      return MOE_ERR_HIP;
+    }
+    hipLaunchKernelGGL(wgrad_blocks_kernel, dim3(1), dim3(256), 0, side->stream, tables->offsets, w.header, dv.e_lo,
+                       dv.E_loc, kb);
+    transpose(static_cast<const bf16_t *>(x), w.row_tok, shape->d, shape->d, xT);
+    transpose(static_cast<const bf16_t *>(dy), w.row_tok, shape->d, shape->d, dyT);
+    if ((rc = launch_status()) != MOE_OK) return join(rc);
+  }
   // gradient of the gate weights (zero for the slots whose expert is not local)
   hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)std::min<size_t>(1024, (n_pairs + 255) / 256)), dim3(256), 0, st,
                      d_topk_w, n_pairs, 0.0f);
   hipLaunchKernelGGL(gate_weight_grad_kernel, dim3((unsigned)std::min<size_t>(4096, (rows + 3) / 4)), dim3(256), 0, st,
                      kept_o, static_cast<const bf16_t *>(dy), w.header, w.row_tok, w.row_w, tables->perm, shape->d,
                      d_topk_w);
-  if ((rc = launch_status()) != MOE_OK) return rc;
+  if ((rc = launch_status()) != MOE_OK) return join(rc);
   static std::atomic<uint64_t> done_b1{0}, done_b2{0};
   if (!allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<false, false, true>), 2 * kStageBytes,
                          done_b1) ||
       !allow_dynamic_lds(reinterpret_cast<const void *>(&gemm_bf16_kernel<false>), 2 * kStageBytes, done_b2))
-    return MOE_ERR_HIP;
+    return join(MOE_ERR_HIP);
   const auto grid_of = [&](int nt) { return dim3((unsigned)(((size_t)dvb.max_mtiles * nt + 255) / 256 * 256)); };
   // dh_raw = dy[token of the row] Wd^T, then the SwiGLU derivative with the kept g and u
   GemmArgs g1{};
@@ -711,7 +778,14 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   g1.n_ntiles = dvb.nt1; g1.n_ktiles = ceil_div(shape->d, kBK);
   hipLaunchKernelGGL((gemm_bf16_kernel<false, false, true>), grid_of(dvb.nt1), dim3(kGemmThreads), 2 * kStageBytes, st,
                      g1);
-  if ((rc = launch_status()) != MOE_OK) return rc;
+  if ((rc = launch_status()) != MOE_OK) return join(rc);
+  if (wgrad) {  // dg, du and w h are there: their transposes run beside the second GEMM
+    if (hipEventRecord(side->mid, st) != hipSuccess || hipStreamWaitEvent(side->stream, side->mid, 0) != hipSuccess)
+      return join(MOE_ERR_HIP);
+    transpose(hw, nullptr, shape->f, shape->f, hwT);
+    transpose(dgu, nullptr, 2 * shape->f, 2 * shape->f, dguT);
+    if ((rc = launch_status()) != MOE_OK) return join(rc);
+  }
   // rows of dx = [dg | du] [Wg^T ; Wu^T]; a row that is its token's only local slot goes straight to dx
   GemmArgs g2{};
   g2.A = dgu; g2.row_map = nullptr; g2.Bp = packed_gate_up_t; g2.out = dxr; g2.row_w = nullptr;
@@ -720,27 +794,18 @@ extern "C" int moe_fused_backward(const moe_shape *shape, const void *x, const v
   g2.K = 2 * shape->f; g2.N = shape->d; g2.lda = 2 * shape->f; g2.ldo = shape->d;
   g2.n_ntiles = dvb.nt2; g2.n_ktiles = 2 * (shape->f / kBK);
   hipLaunchKernelGGL(gemm_bf16_kernel<false>, grid_of(dvb.nt2), dim3(kGemmThreads), 2 * kStageBytes, st, g2);
-  if ((rc = launch_status()) != MOE_OK) return rc;
-  if ((rc = launch_combine(shape, dv, dxr, topk_idx, tables, dx, true, st)) != MOE_OK || !wgrad) return rc;
-  // weight gradients: transpose (and gather) the four operands, then one grouped product per weight matrix
+  if ((rc = launch_status()) != MOE_OK) return join(rc);
+  if ((rc = launch_combine(shape, dv, dxr, topk_idx, tables, dx, true, st)) != MOE_OK || !wgrad) return join(rc);
+  // weight gradients: one grouped product per weight matrix, over the transposed operands
   static std::atomic<uint64_t> done_w{0};
   if (!allow_dynamic_lds(reinterpret_cast<const void *>(&wgrad_bf16_kernel), 2 * kStageBytes, done_w))
-    return MOE_ERR_HIP;
-  int32_t *kb = reinterpret_cast<int32_t *>(b + L.kb);
-  bf16_t *xT = reinterpret_cast<bf16_t *>(b + L.xT), *dyT = reinterpret_cast<bf16_t *>(b + L.dyT);
-  bf16_t *hwT = reinterpret_cast<bf16_t *>(b + L.hwT), *dguT = reinterpret_cast<bf16_t *>(b + L.dguT);
-  const int kblocks = (int)(L.kpad / 64);
-  if (kblocks > 65535) return MOE_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(wgrad_blocks_kernel, dim3(1), dim3(256), 0, st, tables->offsets, w.header, dv.e_lo, dv.E_loc, kb);
-  const auto transpose = [&](const bf16_t *src, const int32_t *map, int ld, int C, bf16_t *dst) {
-    hipLaunchKernelGGL(gather_transpose_kernel, dim3(ceil_div(C, 64), kblocks), dim3(256), 0, st, src, map, ld, 0, C,
-                       tables->offsets, w.header, kb, dv.e_lo, dv.E_loc, dst);
-  };
-  transpose(static_cast<const bf16_t *>(x), w.row_tok, shape->d, shape->d, xT);
-  transpose(static_cast<const bf16_t *>(dy), w.row_tok, shape->d, shape->d, dyT);
-  transpose(hw, nullptr, shape->f, shape->f, hwT);
-  transpose(dgu, nullptr, 2 * shape->f, 2 * shape->f, dguT);
-  if ((rc = launch_status()) != MOE_OK) return rc;
+    return join(MOE_ERR_HIP);
+  if ((rc = join(MOE_OK)) != MOE_OK) return rc;
+  const size_t units = (size_t)shape->d * shape->f / 8;  // 16-byte units of one expert's gradient
+  hipLaunchKernelGGL(wgrad_zero_empty_kernel,
+                     dim3((unsigned)std::min<size_t>(1024, ceil_div(units, (size_t)8192)), dv.E_loc, 3), dim3(256), 0,
+                     st, kb, static_cast<u32x4 *>(dW_gate), static_cast<u32x4 *>(dW_up), static_cast<u32x4 *>(dW_down),
+                     units);
   const auto product = [&](const bf16_t *AT, int lda, const bf16_t *BT, int ldb, int b0, int M, int N, void *C) {
     WgradArgs a;
     a.AT = AT; a.BT = BT; a.C = static_cast<bf16_t *>(C); a.kb = kb;

@@ -93,11 +93,25 @@ struct WgradArgs {
   int M, N, n_mt, n_nt;
 };
 
-// Experts with at most kThinSteps blocks of 64 rows (and experts without rows, whose gradients are zero) are left to
-// wgrad_thin_bf16_kernel: their cost is writing the output, and that kernel's small workgroups overlap the stores of
+// Experts with at most kThinSteps blocks of 64 rows are left to wgrad_thin_bf16_kernel (those without rows to
+// wgrad_zero_empty_kernel): their cost is writing the output, and that kernel's small workgroups overlap the stores of
 // one tile with the loads of the next on the same CU.
 constexpr int kThinSteps = 2;
 constexpr int kThinTiles = 4;  // output tiles per workgroup of wgrad_thin_bf16_kernel
+
+// Zero gradients of the local experts without rows: grid (shares, E_loc, 3 matrices), each workgroup clears one
+// contiguous share of `units` 16-byte units.  Few registers and no LDS on purpose: its waves fit beside a GEMM
+// workgroup on the same CU.
+__global__ __launch_bounds__(256) void wgrad_zero_empty_kernel(const int32_t *__restrict__ kb, u32x4 *c0, u32x4 *c1,
+                                                               u32x4 *c2, size_t units) {
+  const int le = blockIdx.y;
+  if (kb[le + 1] != kb[le]) return;
+  u32x4 *C = (blockIdx.z == 0 ? c0 : blockIdx.z == 1 ? c1 : c2) + (size_t)le * units;
+  const size_t share = (units + gridDim.x - 1) / gridDim.x;
+  const size_t u0 = blockIdx.x * share, u1 = u0 + share < units ? u0 + share : units;
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  for (size_t u = u0 + threadIdx.x; u < u1; u += 256) C[u] = zero;
+}
 
 // One workgroup per (local expert, 256 x 256 output tile); 8 waves = 2 x 4, each 128 x 64 as 4 x 2 accumulators.
 // LDS: two stages of (A 256 x 64, B 256 x 64), rows of 128 bytes with the forward tile's chunk swizzle.
@@ -265,7 +279,7 @@ __global__ __launch_bounds__(256, 4) void wgrad_thin_bf16_kernel(const WgradArgs
   const int wm = w4 >> 1, wn = w4 & 1;
   const int le = blockIdx.y;
   const int kb0 = a.kb[le], KT = a.kb[le + 1] - kb0;
-  if (KT > kThinSteps) return;  // whole workgroup: wgrad_bf16_kernel owns this expert
+  if (KT > kThinSteps || KT == 0) return;  // whole workgroup: wgrad_bf16_kernel / wgrad_zero_empty_kernel own this expert
   const int chunk = tid & 7, row0 = tid >> 3;  // rows row0 + 32 i
   const int l31 = lane & 31, khalf = lane >> 5, sw = (lane >> 1) & 7;
   // kThinTiles consecutive tiles per workgroup (a tile is a few microseconds of dependent latencies: load, LDS,

@@ -920,6 +920,32 @@ def test_backward_full_size_whole_output(oracle, name):
         assert torch.isfinite(t.float()).all()
 
 
+@pytest.mark.parametrize("name", ["ragged", "empty_experts"])
+def test_backward_replays_from_a_hip_graph(oracle, name):
+    """The backward call forks part of its work to a stream of the library's own and joins it before it returns, so
+    a capture of the caller's stream takes in all of it.  Replays alternate with eager calls and synchronisations and
+    must give the eager call's bits every time."""
+    import torch
+    cfg = BWD_SMALL[name]
+    say(f"backward graph replay {name}")
+    w, lay, x, dy, dy_bits, idx, tw = run_backward(cfg, oracle, wgrad=True)   # eager; also the one-off set-up calls
+    outs = lambda: (lay.dx, lay.d_topk_w, lay.dW_gate, lay.dW_up, lay.dW_down)
+    want = [t.clone() for t in outs()]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lay.backward(x, dy)
+    for rep in range(3):
+        for t in outs():
+            t.fill_(float("nan"))
+        lay.backward_ws.fill_(0x3C + rep)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(want, outs())), f"replay {rep} differs from the eager call"
+        lay.backward(x, dy)   # eager work between the replays
+        torch.cuda.synchronize()
+        assert all(torch.equal(a, b) for a, b in zip(want, outs()))
+
+
 def test_backward_empty_layer_zeroes_the_weight_gradients():
     import torch
     cfg = cfg_of(T=0, d=64, f=64)
