@@ -217,6 +217,8 @@ def test_training_entry_points_arguments():
     assert lib.moe_fused_backward(*b_args, fake, None, None, fake, ws, None) == B.MOE_ERR_INVALID_ARG  # all three or none
     assert lib.moe_fused_backward(C.byref(s), fake, None, fake, fake, C.byref(tb), fake, fake, fake, kept, fake, fake,
                                   None, None, None, fake, ws, None) == B.MOE_ERR_INVALID_ARG           # no dy
+    # weight gradients leave in 16-byte stores: a pointer that is only 8-byte aligned is rejected
+    assert lib.moe_fused_backward(*b_args, fake, fake + 8, fake, fake, ws, None) == B.MOE_ERR_INVALID_ARG
     odd = good_shape(f=72)  # the backward needs whole 64-index reduction tiles over f
     assert lib.moe_fused_backward(C.byref(odd), fake, fake, fake, fake, C.byref(tb), fake, fake, fake, 1 << 30, fake,
                                   fake, None, None, None, fake, 1 << 30, None) == B.MOE_ERR_UNSUPPORTED
