@@ -946,6 +946,43 @@ def test_backward_replays_from_a_hip_graph(oracle, name):
         assert all(torch.equal(a, b) for a, b in zip(want, outs()))
 
 
+def test_backward_from_two_host_threads(oracle):
+    """Two host threads, each with its own layer, workspace and stream, call the backward at the same time.  The
+    library's side stream and its events are shared per device, so it serialises the two callers' enqueueing; each
+    must get the bits of its own single-threaded call."""
+    import threading
+
+    import torch
+    names = ["ragged", "deepseek_like"]
+    say(f"backward from two host threads: {names}")
+    runs = [run_backward(BWD_SMALL[n], oracle, wgrad=True) for n in names]   # eager, one after the other
+    outs = lambda lay: (lay.dx, lay.d_topk_w, lay.dW_gate, lay.dW_up, lay.dW_down)
+    want = [[t.clone() for t in outs(r[1])] for r in runs]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(i):
+        try:
+            lay, x, dy = runs[i][1], runs[i][2], runs[i][3]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for _ in range(25):
+                    lay.backward(x, dy)
+            stream.synchronize()
+        except Exception as exc:   # reported by the main thread
+            errors.append(exc)
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads) and not errors, errors
+    torch.cuda.synchronize()
+    for i, r in enumerate(runs):
+        assert all(torch.equal(a, b) for a, b in zip(want[i], outs(r[1]))), names[i]
+
+
 def test_backward_empty_layer_zeroes_the_weight_gradients():
     import torch
     cfg = cfg_of(T=0, d=64, f=64)
