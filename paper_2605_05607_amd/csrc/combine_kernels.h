@@ -9,7 +9,8 @@ namespace moe355 {
 // writes the y row once; tokens without a local slot get zeros.  The slots are resolved by the lanes of the wave
 // (one slot each), not serially.  (Measured against the earlier form, one workgroup per token with the slots resolved
 // by its first thread: the same 5.0-5.2 TB/s from HBM, i.e. the rate this machine copies at; loading the rows with
-// the non-temporal hint was 10 % slower.)
+// the non-temporal hint was 10 % slower.  The y row is stored with that hint: nothing of this call reads it again, and
+// in the fused call -1.6 % on the DeepSeek-shaped forward together with the same hint on GEMM-2's direct y rows.)
 // ------------------------------------------------------------------------------------------------
 template <typename OutT>
 __device__ __forceinline__ void store8(OutT *dst, const float (&v)[8]);
@@ -23,7 +24,7 @@ __device__ __forceinline__ void store8<bf16_t>(bf16_t *dst, const float (&v)[8])
   bf16x8 o;
 #pragma unroll
   for (int q = 0; q < 8; ++q) o[q] = (bf16_t)v[q];
-  *reinterpret_cast<bf16x8 *>(dst) = o;
+  __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(dst));
 }
 
 // The sum of one token's rows by one wave.  `row` holds, in the lanes named by `slots`, the layout rows of the token's

@@ -567,7 +567,9 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
             bf16x4 b;
 #pragma unroll
             for (int q = 0; q < 4; ++q) b[q] = (bf16_t)(v[q] + 0.0f);  // + 0 as in the sum that starts from zero
-            *reinterpret_cast<bf16x4 *>(static_cast<bf16_t *>(g.y) + (size_t)sole[it] * g.ldo + col) = b;
+            // (y is not read again by this launch: streamed past the L2, which the operands need)
+            __builtin_nontemporal_store(
+                b, reinterpret_cast<bf16x4 *>(static_cast<bf16_t *>(g.y) + (size_t)sole[it] * g.ldo + col));
           } else {
             *reinterpret_cast<f32x4 *>(static_cast<float *>(g.out) + (size_t)(m0 + row_l) * g.ldo + col) = v;
           }
