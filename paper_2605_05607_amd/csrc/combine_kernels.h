@@ -9,28 +9,30 @@ namespace moe355 {
 // writes the y row once; tokens without a local slot get zeros.  The slots are resolved by the lanes of the wave
 // (one slot each), not serially.  (Measured against the earlier form, one workgroup per token with the slots resolved
 // by its first thread: the same 5.0-5.2 TB/s from HBM, i.e. the rate this machine copies at; loading the rows with
-// the non-temporal hint was 10 % slower.  The y row is stored with that hint: nothing of this call reads it again, and
-// in the fused call -1.6 % on the DeepSeek-shaped forward together with the same hint on GEMM-2's direct y rows.)
+// the non-temporal hint was 10 % slower.)
 // ------------------------------------------------------------------------------------------------
-template <typename OutT>
-__device__ __forceinline__ void store8(OutT *dst, const float (&v)[8]);
-template <>
-__device__ __forceinline__ void store8<float>(float *dst, const float (&v)[8]) {
-  *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-  *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
-}
-template <>
-__device__ __forceinline__ void store8<bf16_t>(bf16_t *dst, const float (&v)[8]) {
-  bf16x8 o;
+// Eight consecutive outputs.  STREAM: with the non-temporal hint (a y row inside the fused call: nothing of the call
+// reads it again, and the next call's operands keep their place in the caches).
+template <typename OutT, bool STREAM = false>
+__device__ __forceinline__ void store8(OutT *dst, const float (&v)[8]) {
+  if constexpr (sizeof(OutT) == 4) {
+    *reinterpret_cast<float4 *>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  } else {
+    bf16x8 o;
 #pragma unroll
-  for (int q = 0; q < 8; ++q) o[q] = (bf16_t)v[q];
-  __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(dst));
+    for (int q = 0; q < 8; ++q) o[q] = (bf16_t)v[q];
+    if constexpr (STREAM)
+      __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(dst));
+    else
+      *reinterpret_cast<bf16x8 *>(dst) = o;
+  }
 }
 
 // The sum of one token's rows by one wave.  `row` holds, in the lanes named by `slots`, the layout rows of the token's
 // local slots (lane = slot index); the rows are added in slot order, starting from zero, in fp32.  Four pieces of 512
 // columns at a time (8 per lane each) and the loads of two slots in flight together.  poison: write NaN instead.
-template <typename OutT>
+template <typename OutT, bool STREAM = false>
 __device__ __forceinline__ void combine_token_rows(const float *__restrict__ rows, int row, uint64_t slots, int d,
                                                    OutT *__restrict__ yrow, int lane, int poison) {
   for (int c0 = lane * 8; c0 < d; c0 += 4 * 512) {
@@ -81,7 +83,7 @@ __device__ __forceinline__ void combine_token_rows(const float *__restrict__ row
 #pragma unroll
           for (int q = 0; q < 8; ++q) acc[u][q] = __builtin_nanf("");
         }
-        store8<OutT>(yrow + c, acc[u]);
+        store8<OutT, STREAM>(yrow + c, acc[u]);
       }
     }
   }
@@ -100,20 +102,23 @@ __device__ __forceinline__ int combine_slot_row(const int32_t *__restrict__ topk
 
 constexpr int kCombineWaves = 4;  // tokens per workgroup of combine_kernel: one per wave
 
-template <typename OutT>
+// FUSED (inside the fused calls): tokens with one local slot are skipped, GEMM-2 has written their rows, and the y rows
+// leave with the non-temporal hint; the stand-alone Combine writes every row with plain stores (measured from HBM on
+// rotated buffers it is 5 % slower with the hint, while the fused forward on the DeepSeek-shaped layer gains 1.3 %).
+template <typename OutT, bool FUSED>
 __global__ __launch_bounds__(kCombineWaves * 64) void combine_kernel(const float *__restrict__ rows,
                                                                      const int32_t *__restrict__ topk_idx,
                                                                      const int32_t *__restrict__ inv_perm,
                                                                      const int32_t *__restrict__ offsets, int T, int k,
                                                                      int d, int e_lo, int E_loc, int P_cap,
-                                                                     int skip_sole, OutT *__restrict__ y) {
+                                                                     OutT *__restrict__ y) {
   const int lane = threadIdx.x & 63;
   const int t = blockIdx.x * kCombineWaves + (threadIdx.x >> 6);  // wave-uniform
   if (t >= T) return;
   const int row = combine_slot_row(topk_idx, inv_perm, t, k, lane, e_lo, E_loc, offsets[e_lo], P_cap);
   const uint64_t slots = __ballot(row >= 0);
-  if (__popcll(slots) == 1 && skip_sole) return;  // GEMM-2 has written this token's row
-  combine_token_rows<OutT>(rows, row, slots, d, y + (size_t)t * d, lane, 0);
+  if (FUSED && __popcll(slots) == 1) return;  // GEMM-2 has written this token's row
+  combine_token_rows<OutT, FUSED>(rows, row, slots, d, y + (size_t)t * d, lane, 0);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -218,12 +218,15 @@ static int launch_gemms(const moe_shape *s, const Derived &dv, const void *a1, c
 static int launch_combine(const moe_shape *s, const Derived &dv, const float *rows, const int32_t *topk_idx,
                           const moe_dispatch *tb, void *y, bool skip_sole, hipStream_t st) {
   const dim3 grid((unsigned)ceil_div(s->T, kCombineWaves)), block(kCombineWaves * 64);
-  if (s->dtype == MOE_BF16)
-    hipLaunchKernelGGL(combine_kernel<bf16_t>, grid, block, 0, st, rows, topk_idx, tb->inv_perm, tb->offsets, s->T,
-                       s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, (int)skip_sole, static_cast<bf16_t *>(y));
-  else
-    hipLaunchKernelGGL(combine_kernel<float>, grid, block, 0, st, rows, topk_idx, tb->inv_perm, tb->offsets, s->T,
-                       s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, (int)skip_sole, static_cast<float *>(y));
+#define MOE355_COMBINE(T_, FUSED_)                                                                             \
+  hipLaunchKernelGGL((combine_kernel<T_, FUSED_>), grid, block, 0, st, rows, topk_idx, tb->inv_perm, tb->offsets, \
+                     s->T, s->k, s->d, dv.e_lo, dv.E_loc, (int)dv.P_cap, static_cast<T_ *>(y))
+  if (s->dtype == MOE_BF16) {
+    if (skip_sole) MOE355_COMBINE(bf16_t, true); else MOE355_COMBINE(bf16_t, false);
+  } else {
+    if (skip_sole) MOE355_COMBINE(float, true); else MOE355_COMBINE(float, false);
+  }
+#undef MOE355_COMBINE
   return launch_status();
 }
 

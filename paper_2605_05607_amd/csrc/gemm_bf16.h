@@ -821,7 +821,7 @@ __device__ __forceinline__ void resident_combine(const PipelineArgs &p) {
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
-    combine_token_rows<bf16_t>(rows, row, slots, d, yrow, lane, poison);
+    combine_token_rows<bf16_t, true>(rows, row, slots, d, yrow, lane, poison);
   }
 }
 
