@@ -255,15 +255,19 @@ __global__ __launch_bounds__(kGemmThreads, 1) void wgrad_bf16_kernel(const Wgrad
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-      const int rl = it * 4 + (lane >> 4), cc = lane & 15;  // 16 groups of 4 columns per row
-      const int m = m0 + wm * 128 + mi * 32 + rl, n = n0 + wn * 64 + cc * 4;
-      const f32x4 v = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 16);
-      if (m < a.M && n < a.N) {  // N % 8 == 0: the four columns are inside together
-        bf16x4 o;
+    for (int it = 0; it < 4; ++it) {
+      const int rl = it * 8 + (lane >> 3), cc = lane & 7;  // 8 groups of 8 columns per row: 16-byte stores
+      const int m = m0 + wm * 128 + mi * 32 + rl, n = n0 + wn * 64 + cc * 8;
+      const f32x4 v0 = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 32);
+      const f32x4 v1 = *reinterpret_cast<const f32x4 *>(patch + rl * 288 + cc * 32 + 16);
+      if (m < a.M && n < a.N) {  // N % 8 == 0: the eight columns are inside together
+        bf16x8 o;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) o[q] = (bf16_t)v[q];
-        __builtin_nontemporal_store(o, reinterpret_cast<bf16x4 *>(C + (size_t)m * a.N + n));
+        for (int q = 0; q < 4; ++q) {
+          o[q] = (bf16_t)v0[q];
+          o[4 + q] = (bf16_t)v1[q];
+        }
+        __builtin_nontemporal_store(o, reinterpret_cast<bf16x8 *>(C + (size_t)m * a.N + n));
       }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
