@@ -21,6 +21,9 @@ __device__ __forceinline__ uint8_t to_e4m3(float v) {
 constexpr int kTileBytes = kBN * kBK * 2;  // one packed weight tile = one LDS stage image of B (32 KiB)
 
 constexpr int kTileShift = 12;  // work item .w = N tile | M-tile id << kTileShift
+// work item .z = rows of the tile | kItemLone if the tile is its expert's only M tile (its weights are read once)
+constexpr int kItemRowsMask = 0xFFFF;
+constexpr int kItemLone = 1 << 16;
 constexpr int kChunk = 32;  // work items that are resident on one XCD at a time (one per CU)
 constexpr int kChunkM = 8;  // M tiles per chunk (at most)
 

@@ -65,7 +65,7 @@ constexpr int kPatchBytes = 32 * 288;                     // per-wave epilogue p
 //   !GATED : the first GEMM of the backward pass, dh_raw = dy Wd^T (N = f).  With the kept g, u and the gate weight w:
 //            dh = w dh_raw, dg = dh u silu'(g), du = dh silu(g)  ->  g.out = dgu [rows, 2 N] bf16 (dg, then du), and
 //            g.aux2 = w silu(g) u [rows, N] bf16 (the h operand of the down-projection weight gradient, weight folded in).
-template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false, bool TRAIN = false>
+template <bool GATED, bool RESIDENT, int NB, int NA, int DEPTH, bool FP8 = false, bool TRAIN = false, bool LONE = false>
 __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char *smem, int nt, int le, int m0,
                                                int rows, int nblk_total, int poison = 0,
                                                int32_t *pre_ctr = nullptr, int *pre_slot = nullptr) {
@@ -107,10 +107,11 @@ __device__ __forceinline__ void gemm_bf16_tile(const GemmArgs &g, unsigned char 
   // tile is zero there, so it contributes nothing and no select has to wait on the load
 #define MOE355_A_OFF(KT) ((KT) * KS + a_chunk * EPC < g.K ? (KT) * KS : -a_chunk * EPC)
   // NA = row loads per thread that reach valid rows (1: rows < 64, 2: rows < 128, 4: all); the others are skipped
-  // Weight tiles of a streaming item (at most 64 rows) are read once by one workgroup: loaded with the
-  // non-temporal hint so that they do not push the operands the full tiles share out of the L2.
+  // Weight tiles of a streaming item (at most 64 rows), and of any item that is its expert's only M tile (LONE), are
+  // read once by one workgroup: loaded with the non-temporal hint so that they do not push the operands that other
+  // tiles share out of the L2.
 #define MOE355_B_LOAD(PTR)                                                                          \
-  (NA == 1 ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(PTR))                        \
+  ((NA == 1 || LONE) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(PTR))                        \
            : *reinterpret_cast<const u32x4 *>(PTR))
 #define MOE355_LOAD_P0(S, KT)                                                                       \
   do {                                                                                              \
@@ -589,13 +590,21 @@ template <bool GATED, bool RESIDENT, bool FP8 = false, bool TRAIN = false>
 __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char *smem, const int4 item,
                                                int poison = 0, int32_t *pre_ctr = nullptr,
                                                int *pre_slot = nullptr) {
-  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
+  const int le = item.x, m0 = item.y, rows = item.z & kItemRowsMask, nt = item.w & ((1 << kTileShift) - 1);
+  // the expert's only M tile (uniform).  Only the resident kernels, which run the layers made of such tiles, have
+  // the variants with streaming weight loads: in the per-item kernels they cost six more registers, and those
+  // kernels leave 16 registers per SIMD to the kernels that run beside them in the backward pass.
+  const bool lone = (item.z & kItemLone) != 0;
   const int nblk_total = (rows + 31) >> 5;                        // 1..8
   const int wm = threadIdx.x >> 8;                                // wave row (wave-uniform)
   const int nb = max(0, min(4, nblk_total - 4 * wm));             // valid 32-row blocks of this wave
-#define MOE355_TILE(NB_, NA_) \
-  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN>(g, smem, nt, le, m0, rows, nblk_total, poison, \
-                                                                          pre_ctr, pre_slot)
+#define MOE355_TILE_(NB_, NA_, LONE_)                                                                              \
+  gemm_bf16_tile<GATED, RESIDENT, NB_, NA_, (NA_ == 1 ? 2 : 1), FP8, TRAIN, LONE_>(g, smem, nt, le, m0, rows, nblk_total, \
+                                                                                 poison, pre_ctr, pre_slot)
+#define MOE355_TILE(NB_, NA_)                                                                  \
+  do {                                                                                         \
+    if (RESIDENT && NA_ > 1 && lone) MOE355_TILE_(NB_, NA_, (RESIDENT && NA_ > 1)); else MOE355_TILE_(NB_, NA_, false); \
+  } while (0)
   if (nblk_total <= 2) {
     if (nb == 2) MOE355_TILE(2, 1); else if (nb == 1) MOE355_TILE(1, 1); else MOE355_TILE(0, 1);
   } else if (nblk_total <= 4) {
@@ -605,6 +614,7 @@ __device__ __forceinline__ void gemm_bf16_item(const GemmArgs &g, unsigned char 
     else MOE355_TILE(1, 4);
   }
 #undef MOE355_TILE
+#undef MOE355_TILE_
 }
 
 // One workgroup per work item; workgroup -> item by chunked_item.

@@ -15,7 +15,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const GemmArgs g) {
   const int q = chunked_item(blockIdx.x, *g.n_items);
   if (q < 0) return;
   const int4 item = g.work[q];
-  const int le = item.x, m0 = item.y, rows = item.z, nt = item.w & ((1 << kTileShift) - 1);
+  const int le = item.x, m0 = item.y, rows = item.z & kItemRowsMask, nt = item.w & ((1 << kTileShift) - 1);
   const int tid = threadIdx.x;
   const int ty = tid >> 4, tx = tid & 15;
   const float *A = static_cast<const float *>(g.A);

@@ -216,7 +216,8 @@ __global__ __launch_bounds__(256) void fwd_prep_kernel(const int32_t *__restrict
       if (mt >= cnt / bm) rows = part[le];
     }
     const int start = min(P, offsets[e_lo + le] - base);
-    const int4 item = make_int4(le, start + mt * bm, rows, nt | (tile << kTileShift));
+    const int cnt_le = min(P, offsets[e_lo + le + 1] - base) - start;
+    const int4 item = make_int4(le, start + mt * bm, rows | (cnt_le <= bm ? kItemLone : 0), nt | (tile << kTileShift));
     if (second) work2[qq] = item; else work1[qq] = item;
   }
 }
