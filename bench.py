@@ -528,7 +528,7 @@ def main():
             lay_x = L.MoELayer(cfg_x)
             lay_x.packed_gate_up, lay_x.packed_down = lay.packed_gate_up, lay.packed_down
             lgx = lg if wx is w else L.to_device(wx.logits)
-            for _ in range(3):
+            for _ in range(40):  # (the clocks take some tens of steps to settle after a change of load)
                 lay_x.step(lgx, x)
             t_x = timed(lambda: lay_x.step(lgx, x), 10)
             cx = lay_x.tables.counts.cpu().numpy()[cfg_x.first_local_expert:cfg_x.first_local_expert + cfg_x.E_loc]
@@ -540,6 +540,31 @@ def main():
                           "mfma_tflops_whole_step": 6.0 * Px * cfg.d * cfg.f / (t_x * 1e-3) / 1e12}
             del lay_x
         out["skew_points"] = pts
+        # The balanced load of the paper's training runs on the same shape (Table I Large: every expert equally
+        # likely; all 32 local experts stay below one M tile, so the GEMM launch streams every expert's weights once):
+        # the regime in which this launch is bound by HBM throughout.  A labelled extra, not `value`.
+        cfg_n = cfg.scaled(router="normal")
+        wn = wl.make_workload(cfg_n, weights=False)
+        lay_n = L.MoELayer(cfg_n)
+        lay_n.packed_gate_up, lay_n.packed_down = lay.packed_gate_up, lay.packed_down
+        lgn = L.to_device(wn.logits)
+        for _ in range(60):  # (the clocks take some tens of steps to settle after a change of load)
+            lay_n.step(lgn, x)
+        one_n = B.moe_forward_gemm_launches(lay_n.shape) == 1
+        # as for `value`: the GEMM launch (both GEMMs if they share one, else both brackets) on every fourth step
+        ms_n, gemm_n, _ = timed_value(lay_n, lgn, x, 40, 1, 3, 4)
+        idx_n = lay_n.topk_idx.cpu().numpy().reshape(cfg_n.T, cfg_n.k)
+        cn = lay_n.tables.counts.cpu().numpy()[cfg_n.first_local_expert:cfg_n.first_local_expert + cfg_n.E_loc]
+        Pn, Un, nen, g1w, g2w, _ = algorithmic_work(cfg_n, idx_n, cn)
+        gemm_n = float(gemm_n)
+        out["balanced_load_point"] = {
+            "workload": "deepseek_v3 shape with router=normal (Table I Large, k = 8)", "local_pairs_P": Pn,
+            "rows_per_expert_max": int(cn.max()), "gemm_launches": 1 if one_n else 2,
+            "ms_per_step": ms_n, "tokens_per_s": cfg.T / (ms_n * 1e-3), "gemm_ms": gemm_n,
+            "gemm_bytes": g1w["bytes"] + g2w["bytes"],
+            "hbm_gbs": (g1w["bytes"] + g2w["bytes"]) / (gemm_n * 1e-3) / 1e9,
+            "hbm_frac_of_peak": (g1w["bytes"] + g2w["bytes"]) / (gemm_n * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        del lay_n, lgn, wn
     # The whole step captured once in a HIP graph and replayed (what a serving loop would do): fewer host launches.
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
@@ -557,7 +582,7 @@ def main():
         lay8 = L.MoELayer(cfg8)
         lay8.packed_gate_up, lay8.packed_down = lay.packed_gate_up, lay.packed_down
         x8, lg8 = L.to_device(w8.x), L.to_device(w8.logits)
-        for _ in range(2):
+        for _ in range(12):
             lay8.step(lg8, x8)
         ms8, (_, g1_8, g2_8, _), _, _ = timed_steps(lay8, lg8, x8, 8)
         idx8 = lay8.topk_idx.cpu().numpy().reshape(cfg8.T, cfg8.k)
